@@ -1,0 +1,217 @@
+"""CPU oracle for the OSC dual-path linear layer -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end of ``osc_ref.c`` (see that file's header for what
+each function computes and which passage of the paper it follows).  Only the
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg import this
+package.  It shares nothing with, and never imports, the HIP library.
+
+All bf16 tensors are numpy ``uint16`` arrays holding the bf16 bit patterns.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "osc_ref.c")
+_LIB = os.path.join(_HERE, "liboscref.so")
+
+
+def build(force=False):
+    """Compile osc_ref.c with gcc (plain C, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", _SRC, "-lm",
+             "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ref_e2m1_decode.restype = C.c_double
+        _lib.ref_e2m1_decode.argtypes = [C.c_int]
+        _lib.ref_e2m1_encode.argtypes = [C.c_double, C.c_int]
+        _lib.ref_e8m0_code_for_amax.argtypes = [C.c_double]
+        _lib.ref_e4m3_decode.restype = C.c_double
+        _lib.ref_e4m3_decode.argtypes = [C.c_int]
+        _lib.ref_e4m3_encode.argtypes = [C.c_float]
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what} failed with code {rc}")
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dt):
+    a = np.ascontiguousarray(a, dtype=dt)
+    return a
+
+
+i64 = C.c_int64
+i32 = C.c_int32
+
+# ---- scalar codecs ---------------------------------------------------------
+
+
+def e2m1_decode(code):
+    return lib().ref_e2m1_decode(int(code))
+
+
+def e2m1_encode(v, negative=None):
+    if negative is None:
+        negative = bool(np.signbit(v))
+    return lib().ref_e2m1_encode(float(v), int(negative))
+
+
+def e8m0_code_for_amax(amax):
+    return lib().ref_e8m0_code_for_amax(float(amax))
+
+
+def e4m3_decode(code):
+    return lib().ref_e4m3_decode(int(code))
+
+
+def e4m3_encode(v):
+    return lib().ref_e4m3_encode(float(np.float32(v)))
+
+
+# ---- table -----------------------------------------------------------------
+
+
+def table_to_index(table):
+    """table[Kg, R] int16 (local index or -1) -> ascending channel ids int32[K_o]."""
+    table = _c(table, np.int16)
+    Kg, R = table.shape
+    oidx = np.zeros(max(Kg * min(R, 32), 1), np.int32)
+    ko = i32(0)
+    _check(lib().ref_table_to_index(_p(table), i32(Kg), i32(R), _p(oidx), C.byref(ko)),
+           "ref_table_to_index")
+    return oidx[:ko.value].copy()
+
+
+# ---- quantisers --------------------------------------------------------------
+
+
+def quantize_mxfp4_osc(X, oidx=None, ldb=None):
+    """Alg. 2.  X uint16[M, K] -> (Xq uint8[M, K/2], Xs uint8[M, K/32], B uint16[M, ldb])."""
+    X = _c(X, np.uint16)
+    M, K = X.shape
+    oidx = np.zeros(0, np.int32) if oidx is None else _c(oidx, np.int32)
+    K_o = int(oidx.shape[0])
+    if ldb is None:
+        ldb = (K_o + 31) // 32 * 32
+    Xq = np.empty((M, K // 2), np.uint8)
+    Xs = np.empty((M, K // 32), np.uint8)
+    B = np.empty((M, ldb), np.uint16)
+    _check(lib().ref_quantize_mxfp4_osc(_p(X), i64(M), i64(K), i64(K), _p(oidx), i32(K_o), _p(Xq),
+                                        _p(Xs), _p(B), i64(ldb)), "ref_quantize_mxfp4_osc")
+    return Xq, Xs, B
+
+
+def gather_wl(W, oidx):
+    """W uint16[N, K] -> W_L uint16[K_o, N] (rows of the unquantised weight)."""
+    W = _c(W, np.uint16)
+    N, K = W.shape
+    oidx = _c(oidx, np.int32)
+    WL = np.empty((oidx.shape[0], N), np.uint16)
+    _check(lib().ref_gather_wl(_p(W), i64(N), i64(K), i64(K), _p(oidx), i32(oidx.shape[0]),
+                               _p(WL)), "ref_gather_wl")
+    return WL
+
+
+def quantize_fp8_rows(X):
+    """X uint16[M, K] -> (X8 uint8[M, K] e4m3 codes, scale float32[M])."""
+    X = _c(X, np.uint16)
+    M, K = X.shape
+    X8 = np.empty((M, K), np.uint8)
+    xs = np.empty(M, np.float32)
+    _check(lib().ref_quantize_fp8_rows(_p(X), i64(M), i64(K), i64(K), _p(X8), _p(xs)),
+           "ref_quantize_fp8_rows")
+    return X8, xs
+
+
+# ---- GEMMs -------------------------------------------------------------------
+
+
+def dual_gemm(Xq, Xs, B, Wq, Ws, WL):
+    """Eq. (dual-path) in double.  B uint16[M, ldb>=K_o], WL uint16[K_o, N]."""
+    Xq, Xs, Wq, Ws = (_c(a, np.uint8) for a in (Xq, Xs, Wq, Ws))
+    M, N = Xq.shape[0], Wq.shape[0]
+    K = Xq.shape[1] * 2
+    assert Wq.shape[1] * 2 == K and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    K_o = 0 if WL is None else int(WL.shape[0])
+    if K_o:
+        B, WL = _c(B, np.uint16), _c(WL, np.uint16)
+        ldb = B.shape[1]
+        assert WL.shape[1] == N and B.shape[0] == M
+    else:
+        B, WL, ldb = None, None, 0
+    Y = np.empty((M, N), np.float64)
+    _check(lib().ref_dual_gemm(_p(Xq), _p(Xs), _p(B), i64(ldb), _p(Wq), _p(Ws), _p(WL), i64(M),
+                               i64(N), i64(K), i32(K_o), _p(Y), i64(N)), "ref_dual_gemm")
+    return Y
+
+
+def grouped_dual_gemm(Xq, Xs, B, row_map, offsets, Wq, Ws, WL):
+    """E experts: Wq uint8[E, N, K/2], Ws uint8[E, N, K/32], WL uint16[E, K_o, N]."""
+    Xq, Xs, Wq, Ws = (_c(a, np.uint8) for a in (Xq, Xs, Wq, Ws))
+    offsets = _c(offsets, np.int32)
+    E, N = Wq.shape[0], Wq.shape[1]
+    K = Xq.shape[1] * 2
+    K_o = 0 if WL is None else int(WL.shape[1])
+    if K_o:
+        B, WL = _c(B, np.uint16), _c(WL, np.uint16)
+        ldb = B.shape[1]
+    else:
+        B, WL, ldb = None, None, 0
+    row_map = None if row_map is None else _c(row_map, np.int32)
+    T = int(offsets[-1])
+    Y = np.zeros((T, N), np.float64)
+    _check(lib().ref_grouped_dual_gemm(_p(Xq), _p(Xs), _p(B), i64(ldb), _p(row_map), _p(offsets),
+                                       i32(E), _p(Wq), _p(Ws), _p(WL), i64(N), i64(K), i32(K_o),
+                                       _p(Y), i64(N)), "ref_grouped_dual_gemm")
+    return Y
+
+
+def fp8_gemm(X8, xs, W8, ws):
+    X8, W8 = _c(X8, np.uint8), _c(W8, np.uint8)
+    xs, ws = _c(xs, np.float32), _c(ws, np.float32)
+    M, K = X8.shape
+    N = W8.shape[0]
+    assert W8.shape[1] == K
+    Y = np.empty((M, N), np.float64)
+    _check(lib().ref_fp8_gemm(_p(X8), _p(xs), _p(W8), _p(ws), i64(M), i64(N), i64(K), _p(Y),
+                              i64(N)), "ref_fp8_gemm")
+    return Y
+
+
+def grouped_fp8_gemm(X8, xs, offsets, W8, ws):
+    """W8 uint8[E, N, K], ws float32[E, N]; rows [off[e], off[e+1]) use expert e."""
+    X8, W8 = _c(X8, np.uint8), _c(W8, np.uint8)
+    xs, ws = _c(xs, np.float32), _c(ws, np.float32)
+    offsets = _c(offsets, np.int32)
+    E, N, K = W8.shape
+    T = int(offsets[-1])
+    Y = np.zeros((T, N), np.float64)
+    _check(lib().ref_grouped_fp8_gemm(_p(X8), _p(xs), _p(offsets), i32(E), _p(W8), _p(ws), i64(N),
+                                      i64(K), _p(Y), i64(N)), "ref_grouped_fp8_gemm")
+    return Y
+
+
+def num_threads():
+    return int(lib().ref_num_threads())

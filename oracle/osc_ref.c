@@ -1,0 +1,376 @@
+/*
+ * CPU oracle for the OSC dual-path linear layer.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain reference that the HIP kernels are checked
+ * against.  Only the test-suite, the smoke check and the benchmark's
+ * cpu_baseline leg may link or call it; the product library never does and
+ * shares no source, header, table or constant generator with it.
+ *
+ * What it computes, and the passage of the paper each function follows:
+ *   ref_table_to_index      suppression vector I = L[p][l] (Section 3.1, Alg. 1
+ *                           output form: one local index per group or -1)
+ *   ref_quantize_mxfp4_osc  OSC-enhanced quantisation (Section 3.2 steps 1-4,
+ *                           Alg. 2): extract to buffer B, zero, micro-scale
+ *                           quantise.  "Standard micro-scaling" is read as
+ *                           OCP MX v1.0 MXFP4: one E8M0 scale per 32 elements,
+ *                           shared exponent floor(log2 amax) - 2, E2M1 elements
+ *                           rounded to nearest, ties to even, saturating.
+ *   ref_gather_wl           W_L: rows of the high-precision weight named by
+ *                           the same table (Section 3.3.1, second bullet)
+ *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
+ *   ref_quantize_fp8_rows   FP8 fallback quantiser (Section 3.4), read as
+ *                           e4m3 with one fp32 scale per row (per token for
+ *                           activations, per output channel for weights)
+ *   ref_fp8_gemm            the W8A8 linear layer on those operands
+ *   ref_grouped_*           the same two GEMMs for E independent experts
+ *                           (MoE model of Section 4.1)
+ *
+ * Floating point: every GEMM accumulates in double.  The FP8 quantiser's
+ * scale arithmetic is IEEE single precision (one division, one multiply),
+ * because it decides integer codes and both sides must take that decision
+ * in the same precision.
+ *
+ * Parity pins: tests/test_oracle_*.py.  Non-finite inputs are outside the
+ * contract: every quantiser returns REF_ERR_NONFINITE when it meets one.
+ *
+ * Build: gcc -O2 -fopenmp -ffp-contract=off -shared -fPIC osc_ref.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_OK 0
+#define REF_ERR_ARG (-1)
+#define REF_ERR_TABLE (-3)
+#define REF_ERR_NONFINITE (-7)
+
+#define G 32 /* MXFP4 block size (Section 4.1, implementation details) */
+
+/* ---- number formats ---------------------------------------------------- */
+
+static float bf16_to_float(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* E2M1 magnitudes by 3-bit code {exp[1:0], man}; bit 3 of a code is the sign. */
+static const double E2M1_MAG[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+double ref_e2m1_decode(int code) {
+    double m = E2M1_MAG[code & 7];
+    return (code & 8) ? -m : m;
+}
+
+/* Nearest E2M1 magnitude to |v|; a value half-way between two neighbours goes
+ * to the one whose mantissa bit (code bit 0) is 0; anything above 6 has 6 as
+ * its nearest value, which is the saturation rule. */
+static int e2m1_nearest_mag_code(double a) {
+    int best = 0;
+    double bd = fabs(a - E2M1_MAG[0]);
+    for (int c = 1; c < 8; ++c) {
+        double d = fabs(a - E2M1_MAG[c]);
+        if (d < bd || (d == bd && (c & 1) == 0)) {
+            best = c;
+            bd = d;
+        }
+    }
+    return best;
+}
+
+/* Shared exponent of one MX block: floor(log2(amax)) - emax(E2M1), emax = 2,
+ * clamped to the E8M0 range [-127, 127]; amax == 0 takes the lower clamp. */
+static int mx_shared_exponent(double amax) {
+    if (amax == 0.0) return -127;
+    int ex;
+    (void)frexp(amax, &ex); /* amax = m * 2^ex, m in [0.5, 1) */
+    int e = (ex - 1) - 2;
+    if (e < -127) e = -127;
+    if (e > 127) e = 127;
+    return e;
+}
+
+int ref_e8m0_code_for_amax(double amax) { return mx_shared_exponent(amax) + 127; }
+
+int ref_e2m1_encode(double v, int negative) {
+    return e2m1_nearest_mag_code(fabs(v)) | (negative ? 8 : 0);
+}
+
+/* OCP E4M3: bias 7, 3 mantissa bits, no infinity, largest finite 448,
+ * subnormal step 2^-9. */
+double ref_e4m3_decode(int code) {
+    int s = (code >> 7) & 1, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        v = ldexp((double)m, -9);
+    else
+        v = ldexp(1.0 + m / 8.0, e - 7);
+    return s ? -v : v;
+}
+
+/* Round a finite float to E4M3, nearest-even, saturating at +-448.
+ * The quantum of the binade holding |v| is 2^(floor(log2|v|) - 3), never
+ * below the subnormal step 2^-9; rint() rounds half to even. */
+int ref_e4m3_encode(float vf) {
+    double v = (double)vf;
+    int sign = signbit(v) ? 0x80 : 0;
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    int ex;
+    (void)frexp(a, &ex);
+    int p = ex - 1; /* floor(log2 a) */
+    if (p < -6) p = -6;
+    double q = ldexp(1.0, p - 3);
+    double r = rint(a / q) * q; /* a/q is exact: q is a power of two */
+    if (r > 448.0) r = 448.0;
+    if (r == 0.0) return sign;
+    /* encode the representable value r */
+    (void)frexp(r, &ex);
+    p = ex - 1;
+    int e, m;
+    if (p < -6) {
+        e = 0;
+        m = (int)ldexp(r, 9);
+    } else {
+        e = p + 7;
+        m = (int)(ldexp(r, -p) * 8.0) - 8;
+    }
+    return sign | (e << 3) | m;
+}
+
+/* ---- table ------------------------------------------------------------- */
+
+/* Paper-form table: Kg groups x R slots, each a local index in [0, 32) or -1
+ * (no suppression).  Output: the flat list of protected global channel ids in
+ * ascending order, and its length K_o. */
+int ref_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oidx, int32_t *K_o) {
+    if (!table || !oidx || !K_o || Kg < 0 || R < 0) return REF_ERR_ARG;
+    int32_t n = 0;
+    for (int32_t g = 0; g < Kg; ++g) {
+        uint32_t seen = 0;
+        for (int32_t s = 0; s < R; ++s) {
+            int j = table[(int64_t)g * R + s];
+            if (j == -1) continue;
+            if (j < 0 || j >= G) return REF_ERR_TABLE;
+            if (seen & (1u << j)) return REF_ERR_TABLE;
+            seen |= 1u << j;
+        }
+        for (int j = 0; j < G; ++j)
+            if (seen & (1u << j)) oidx[n++] = g * G + j;
+    }
+    *K_o = n;
+    return REF_OK;
+}
+
+/* ---- OSC-enhanced MXFP4 quantiser (Alg. 2) ------------------------------ */
+
+/* X[M, K] bf16 bits, row stride ldx.  oidx[K_o]: protected channel ids.
+ * Outputs: Xq[M, K/2] (element 2i in bits 3:0, 2i+1 in bits 7:4),
+ * Xs[M, K/32] E8M0 codes, B[M, ldb] bf16 bits with column o = the original
+ * value of channel oidx[o] and columns K_o..ldb-1 = +0. */
+int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                           const int32_t *oidx, int32_t K_o, uint8_t *Xq, uint8_t *Xs,
+                           uint16_t *B, int64_t ldb) {
+    if (M < 0 || K < 0 || K % G || ldx < K || K_o < 0 || ldb < K_o) return REF_ERR_ARG;
+    if (M == 0 || K == 0) return REF_OK;
+    if (!X || !Xq || !Xs || (K_o && (!oidx || !B))) return REF_ERR_ARG;
+    for (int32_t o = 0; o < K_o; ++o)
+        if (oidx[o] < 0 || oidx[o] >= K) return REF_ERR_TABLE;
+    int64_t Kg = K / G;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        /* the suppression flags of this row (the same for every row) */
+        uint8_t removed[K];
+        memset(removed, 0, (size_t)K);
+        /* steps 2-3: back up the protected values, then zero them */
+        if (B) {
+            for (int64_t o = 0; o < ldb; ++o) B[m * ldb + o] = 0;
+        }
+        for (int32_t o = 0; o < K_o; ++o) {
+            B[m * ldb + o] = x[oidx[o]];
+            removed[oidx[o]] = 1;
+        }
+        /* step 4: scale and quantise the modified tensor, group by group */
+        for (int64_t g = 0; g < Kg; ++g) {
+            double v[G];
+            int neg[G];
+            double amax = 0.0;
+            for (int j = 0; j < G; ++j) {
+                uint16_t h = removed[g * G + j] ? (uint16_t)0 : x[g * G + j];
+                if ((h & 0x7F80) == 0x7F80) bad = 1;
+                v[j] = (double)bf16_to_float(h);
+                neg[j] = (h >> 15) & 1;
+                if (fabs(v[j]) > amax) amax = fabs(v[j]);
+            }
+            int e = mx_shared_exponent(amax);
+            Xs[m * Kg + g] = (uint8_t)(e + 127);
+            for (int j = 0; j < G; j += 2) {
+                int lo = ref_e2m1_encode(ldexp(v[j], -e), neg[j]);
+                int hi = ref_e2m1_encode(ldexp(v[j + 1], -e), neg[j + 1]);
+                Xq[m * (K / 2) + (g * G + j) / 2] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* W_L[o, n] = W[n, oidx[o]] for o < K_o, taken from the unquantised weight
+ * W[N, K] (bf16 bits, row stride ldw).  W_L is [K_o, N] row-major. */
+int ref_gather_wl(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, const int32_t *oidx,
+                  int32_t K_o, uint16_t *WL) {
+    if (N < 0 || K < 0 || ldw < K || K_o < 0) return REF_ERR_ARG;
+    if (K_o == 0 || N == 0) return REF_OK;
+    if (!W || !oidx || !WL) return REF_ERR_ARG;
+    for (int32_t o = 0; o < K_o; ++o) {
+        if (oidx[o] < 0 || oidx[o] >= K) return REF_ERR_TABLE;
+        for (int64_t n = 0; n < N; ++n) WL[(int64_t)o * N + n] = W[n * ldw + oidx[o]];
+    }
+    return REF_OK;
+}
+
+/* ---- dual-path GEMM (Eq. dual-path) ------------------------------------ */
+
+/* Y[m, n] = sum_g 2^(Xs[m,g] + Ws[n,g] - 254) * sum_{j<32} e2m1(Xq[m,g,j]) * e2m1(Wq[n,g,j])
+ *         + sum_{o<K_o} B[m, o] * W_L[o, n]                       (all in double)
+ * Wq[N, K/2], Ws[N, K/32] are the weight quantised along K; W_L is [K_o, N]. */
+int ref_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint16_t *B, int64_t ldb,
+                  const uint8_t *Wq, const uint8_t *Ws, const uint16_t *WL, int64_t M, int64_t N,
+                  int64_t K, int32_t K_o, double *Y, int64_t ldy) {
+    if (M < 0 || N < 0 || K < 0 || K % G || K_o < 0 || ldb < K_o || ldy < N) return REF_ERR_ARG;
+    if (M == 0 || N == 0) return REF_OK;
+    if (!Y || (K && (!Xq || !Xs || !Wq || !Ws)) || (K_o && (!B || !WL))) return REF_ERR_ARG;
+    int64_t Kg = K / G;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            /* Path A: low-bit base */
+            for (int64_t g = 0; g < Kg; ++g) {
+                double s = 0.0;
+                for (int j = 0; j < G; ++j) {
+                    int64_t k = g * G + j;
+                    int qx = (Xq[m * (K / 2) + k / 2] >> (4 * (k & 1))) & 15;
+                    int qw = (Wq[n * (K / 2) + k / 2] >> (4 * (k & 1))) & 15;
+                    s += ref_e2m1_decode(qx) * ref_e2m1_decode(qw);
+                }
+                acc += ldexp(s, (int)Xs[m * Kg + g] + (int)Ws[n * Kg + g] - 254);
+            }
+            /* Path B: high-precision bypass */
+            for (int32_t o = 0; o < K_o; ++o)
+                acc += (double)bf16_to_float(B[m * ldb + o]) *
+                       (double)bf16_to_float(WL[(int64_t)o * N + n]);
+            Y[m * ldy + n] = acc;
+        }
+    }
+    return REF_OK;
+}
+
+/* E experts; rows [off[e], off[e+1]) of the sorted token list belong to expert
+ * e and use its weights.  row_map (may be NULL = identity) names, for each
+ * sorted position t, the row of Xq/Xs/B it reads.  Y is indexed by t. */
+int ref_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint16_t *B, int64_t ldb,
+                          const int32_t *row_map, const int32_t *off, int32_t E,
+                          const uint8_t *Wq, const uint8_t *Ws, const uint16_t *WL, int64_t N,
+                          int64_t K, int32_t K_o, double *Y, int64_t ldy) {
+    if (E < 0 || !off) return REF_ERR_ARG;
+    int64_t Kg = K / G;
+    for (int32_t e = 0; e < E; ++e) {
+        if (off[e + 1] < off[e]) return REF_ERR_ARG;
+        for (int64_t t = off[e]; t < off[e + 1]; ++t) {
+            int64_t r = row_map ? row_map[t] : t;
+            int rc = ref_dual_gemm(Xq + r * (K / 2), Xs + r * Kg, B ? B + r * ldb : B, ldb,
+                                   Wq + (int64_t)e * N * (K / 2), Ws + (int64_t)e * N * Kg,
+                                   WL ? WL + (int64_t)e * K_o * N : WL, 1, N, K, K_o,
+                                   Y + t * ldy, ldy);
+            if (rc) return rc;
+        }
+    }
+    return REF_OK;
+}
+
+/* ---- FP8 fallback (Section 3.4) ----------------------------------------- */
+
+/* One row of R[rows, K] (bf16 bits) -> e4m3 codes and one fp32 scale:
+ *   amax = max |x|;  rows with amax < 2^-100 (all-zero rows included) use
+ *   scale = inv = 1; otherwise scale = amax / 448 and inv = 448 / amax, each
+ *   one IEEE single division;  q = e4m3(x * inv), one IEEE single multiply. */
+int ref_quantize_fp8_rows(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, uint8_t *X8,
+                          float *xs) {
+    if (M < 0 || K < 0 || ldx < K) return REF_ERR_ARG;
+    if (M == 0) return REF_OK;
+    if (!X8 || !xs || (K && !X)) return REF_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            if ((x[k] & 0x7F80) == 0x7F80) bad = 1;
+            float a = fabsf(bf16_to_float(x[k]));
+            if (a > amax) amax = a;
+        }
+        volatile float scale = 1.0f, inv = 1.0f;
+        if (amax >= 0x1p-100f) {
+            scale = amax / 448.0f;
+            inv = 448.0f / amax;
+        }
+        xs[m] = scale;
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float p = bf16_to_float(x[k]) * inv;
+            X8[m * K + k] = (uint8_t)ref_e4m3_encode(p);
+        }
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* Y[m, n] = xs[m] * ws[n] * sum_k e4m3(X8[m,k]) * e4m3(W8[n,k])   (double) */
+int ref_fp8_gemm(const uint8_t *X8, const float *xs, const uint8_t *W8, const float *ws,
+                 int64_t M, int64_t N, int64_t K, double *Y, int64_t ldy) {
+    if (M < 0 || N < 0 || K < 0 || ldy < N) return REF_ERR_ARG;
+    if (M == 0 || N == 0) return REF_OK;
+    if (!Y || !xs || !ws || (K && (!X8 || !W8))) return REF_ERR_ARG;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                s += ref_e4m3_decode(X8[m * K + k]) * ref_e4m3_decode(W8[n * K + k]);
+            Y[m * ldy + n] = (double)xs[m] * (double)ws[n] * s;
+        }
+    }
+    return REF_OK;
+}
+
+int ref_grouped_fp8_gemm(const uint8_t *X8, const float *xs, const int32_t *off, int32_t E,
+                         const uint8_t *W8, const float *ws, int64_t N, int64_t K, double *Y,
+                         int64_t ldy) {
+    if (E < 0 || !off) return REF_ERR_ARG;
+    for (int32_t e = 0; e < E; ++e) {
+        if (off[e + 1] < off[e]) return REF_ERR_ARG;
+        int64_t t0 = off[e], Me = off[e + 1] - off[e];
+        int rc = ref_fp8_gemm(X8 + t0 * K, xs + t0, W8 + (int64_t)e * N * K, ws + (int64_t)e * N,
+                              Me, N, K, Y + t0 * ldy, ldy);
+        if (rc) return rc;
+    }
+    return REF_OK;
+}
+
+/* threads the parallel loops above actually use */
+int ref_num_threads(void) {
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

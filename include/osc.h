@@ -1,0 +1,171 @@
+/*
+ * libosc -- the inference-time dual-path linear layer of OSC (outlier separation
+ * in the channel dimension) for AMD MI355X (gfx950).  C ABI.
+ *
+ * Conventions shared by every entry point
+ *   - Linear layer Y = X . W^T with X[M, K] (tokens x input channels) and
+ *     W[N, K] (output x input channels).  Quantisation groups are 32 consecutive
+ *     input channels (MXFP4, G = 32).
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked
+ *     "host".  The library never allocates, frees or keeps a pointer past the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     enqueue work and return; they never synchronise the device.
+ *   - Return value: OSC_OK or a negative error; on error nothing was launched.
+ *     osc_last_error() gives a thread-local description of the last error.
+ *   - M == 0 or N == 0 is a valid no-op.
+ *   - bf16 tensors are raw 16-bit patterns.  Inputs must be finite.
+ */
+#ifndef OSC_H
+#define OSC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    OSC_OK = 0,
+    OSC_ERR_NULL = -1,        /* a required pointer is NULL */
+    OSC_ERR_SHAPE = -2,       /* negative extent, K % 32 != 0, leading dimension < extent */
+    OSC_ERR_TABLE = -3,       /* table entry outside [-1, 32) or repeated inside a group */
+    OSC_ERR_UNSUPPORTED = -4, /* unknown enum value, misaligned pointer or stride */
+    OSC_ERR_WORKSPACE = -5,   /* reserved */
+    OSC_ERR_HIP = -6          /* the HIP runtime refused a launch */
+};
+
+enum { OSC_DT_F32 = 0, OSC_DT_BF16 = 1 };                   /* dtype of Y */
+enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1 }; /* activation quantiser format */
+
+const char *osc_last_error(void);
+int osc_version(void);
+
+/* ---- offline helpers ------------------------------------------------------ */
+
+/*
+ * Suppression table -> flat channel list.  (Section 3.1: each table entry is a
+ * local index in [0, G-1] naming the protected channel of its group, or -1 to
+ * bypass suppression for that group.)  Generalised to R slots per group.
+ *   table  host, int16 [Kg, R] row-major
+ *   oidx   host, int32, room for Kg*min(R,32) entries: receives the protected
+ *          global channel ids (32*g + local index) in ascending order
+ *   K_o    host, receives the number of entries written
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE (Kg < 0, R < 0), OSC_ERR_TABLE.
+ */
+int osc_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oidx, int32_t *K_o);
+
+/*
+ * Offline weight preparation (Section 3.3.2, "zero-overhead offline weight
+ * quantisation": W pre-quantised to FP4 at full shape; the weight rows of the
+ * protected channels pre-stored in high precision).
+ *   W      bf16 [N, ldw], unquantised weight, K % 32 == 0, ldw >= K
+ *   oidx   int32 [K_o] ascending protected channel ids (device; may be NULL iff K_o == 0)
+ *   Wpack  osc_packed_weight_bytes(N, K, K_o) bytes, 256-byte aligned; receives the
+ *          MXFP4 codes and E8M0 scales of every row of W (nothing zeroed) and
+ *          W_L[o][n] = W[n][oidx[o]] in the layout the GEMM kernels read.
+ * osc_unpack_weight writes the canonical forms back out: Wq uint8 [N, K/2]
+ * (channel 2i in bits 3:0 of byte i, 2i+1 in bits 7:4), Ws uint8 [N, K/32]
+ * (E8M0), WL bf16 [K_o, N]; any of the three may be NULL to skip it.
+ */
+size_t osc_packed_weight_bytes(int64_t N, int64_t K, int32_t K_o);
+int osc_pack_weight(const void *W, int64_t N, int64_t K, int64_t ldw, const int32_t *oidx,
+                    int32_t K_o, void *Wpack, void *stream);
+int osc_unpack_weight(const void *Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t *Wq,
+                      uint8_t *Ws, void *WL, void *stream);
+
+/*
+ * FP8 fallback weights (Section 3.4): e4m3 codes with one fp32 scale per output
+ * channel, scale = amax/448 (1 for rows with amax < 2^-100).
+ *   W8pack  osc_packed_weight_fp8_bytes(N, K) bytes, 256-byte aligned
+ * osc_unpack_weight_fp8 writes W8 uint8 [N, K] and ws float [N] (either may be NULL).
+ */
+size_t osc_packed_weight_fp8_bytes(int64_t N, int64_t K);
+int osc_pack_weight_fp8(const void *W, int64_t N, int64_t K, int64_t ldw, void *W8pack,
+                        void *stream);
+int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8, float *ws,
+                          void *stream);
+
+/* ---- the hot path ----------------------------------------------------------- */
+
+/*
+ * Online activation quantiser.
+ *
+ * fmt = OSC_FMT_MXFP4_OSC: the OSC-enhanced quantisation workflow (Section 3.2,
+ * steps 2-4; Alg. 2).  For every protected channel c = oidx[o]:
+ * B[m, o] = X[m, c] (bit copy) and X[m, c] counts as +0 from then on; every
+ * 32-channel group of the modified row gets an E8M0 scale with exponent
+ * floor(log2(amax)) - 2 (code 0 when amax is zero or below 2^-124) and E2M1
+ * elements rounded to nearest, ties to even, saturating at +-6; an element's sign
+ * bit is kept even when it rounds to zero.
+ *   X     bf16 [M, ldx], ldx >= K, K % 32 == 0, 16-byte aligned rows (ldx % 8 == 0)
+ *   oidx  int32 [K_o], ascending, distinct, each in [0, K); NULL iff K_o == 0
+ *   Xq    uint8 [M, K/2]   channel 2i -> bits 3:0 of byte i, 2i+1 -> bits 7:4
+ *   Xs    uint8 [M, K/32]  E8M0 codes
+ *   B     bf16 [M, ldb], ldb >= K_o, ldb % 8 == 0; columns K_o..ldb-1 are set to +0.
+ *         May be NULL iff K_o == 0 (then ldb is ignored).
+ *
+ * fmt = OSC_FMT_FP8_E4M3_TOKEN: the FP8 fallback for W_2 inputs (Section 3.4),
+ * one scale per token.  amax = max_k |X[m,k]|; rows with amax < 2^-100 use
+ * scale = 1; otherwise scale = amax/448 and Xq[m,k] = e4m3(X[m,k] * (448/amax)),
+ * every operation one IEEE single-precision operation, e4m3 rounding to nearest
+ * even.  oidx, K_o, B, ldb are ignored; K need not be a multiple of 32 but
+ * must be a multiple of 8.
+ *   Xq    uint8 [M, K] e4m3 codes;  Xs  float [M] scales
+ *
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (fmt, alignment), OSC_ERR_HIP.
+ */
+int osc_quantize_act(const void *X, int64_t M, int64_t K, int64_t ldx, const int32_t *oidx,
+                     int32_t K_o, int fmt, uint8_t *Xq, void *Xs, void *B, int64_t ldb,
+                     void *stream);
+
+/*
+ * Dual-path GEMM (Section 3.3.1, Eq. dual-path):
+ *   Y[m,n] = sum_g 2^(Xs[m,g] + Ws[n,g] - 254) * sum_{j<32} e2m1(Xq[m,32g+j]) * e2m1(Wq[n,32g+j])
+ *          + sum_{o<K_o} B[m,o] * W_L[o,n]
+ * Path A on the block-scaled FP4 matrix cores, Path B on the bf16 matrix cores,
+ * both into one fp32 accumulator; Y is that accumulator, converted (round to
+ * nearest even) when y_dtype is OSC_DT_BF16.
+ *   Xq, Xs, B, ldb   as written by osc_quantize_act(fmt = MXFP4_OSC) with the same K, K_o
+ *   Wpack            from osc_pack_weight with the same N, K, K_o
+ *   Y                [M, ldy] of y_dtype, ldy >= N
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (y_dtype, ldb % 8), OSC_ERR_HIP.
+ */
+int osc_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, int64_t ldb,
+                  const void *Wpack, int64_t M, int64_t N, int64_t K, int32_t K_o, void *Y,
+                  int y_dtype, int64_t ldy, void *stream);
+
+/*
+ * FP8 W8A8 GEMM (Section 3.4; also the W8A8 comparison baseline of Table 2):
+ *   Y[m,n] = xs[m] * ws[n] * sum_k e4m3(X8[m,k]) * e4m3(W8[n,k])
+ *   X8 uint8 [M, K], xs float [M]   from osc_quantize_act(fmt = FP8_E4M3_TOKEN)
+ *   W8pack                           from osc_pack_weight_fp8; for the grouped form,
+ *                                    E packs osc_packed_weight_fp8_bytes(N, K) apart
+ *   expert_offsets  NULL: one problem of M rows.  Otherwise int32 [E+1] (device),
+ *                   non-decreasing, expert_offsets[0] == 0, expert_offsets[E] == M:
+ *                   rows [off[e], off[e+1]) use the e-th pack.
+ *   K % 16 == 0.
+ */
+int osc_fp8_gemm(const uint8_t *X8, const float *xs, const void *W8pack, int64_t M, int64_t N,
+                 int64_t K, const int32_t *expert_offsets, int32_t E, void *Y, int y_dtype,
+                 int64_t ldy, void *stream);
+
+/*
+ * Grouped dual-path GEMM for mixture-of-experts layers (the MoE model of
+ * Section 4.1): the dual-path GEMM above for E independent experts that share
+ * K, N and the suppression table.
+ *   T               number of routed rows (sum of the experts' row counts)
+ *   expert_offsets  int32 [E+1] (device), non-decreasing, [0] == 0, [E] == T
+ *   row_map         int32 [T] (device) or NULL: routed row t reads row row_map[t]
+ *                   of Xq/Xs/B (NULL: row t).  Y row t is written for every t.
+ *   Wpack           E packs, osc_packed_weight_bytes(N, K, K_o) bytes apart
+ */
+int osc_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, int64_t ldb,
+                          const int32_t *row_map, const int32_t *expert_offsets, int32_t E,
+                          int64_t T, const void *Wpack, int64_t N, int64_t K, int32_t K_o,
+                          void *Y, int y_dtype, int64_t ldy, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSC_H */

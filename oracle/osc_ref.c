@@ -67,9 +67,11 @@ double ref_e2m1_decode(int code) {
 }
 
 /* Nearest E2M1 magnitude to |v|; a value half-way between two neighbours goes
- * to the one whose mantissa bit (code bit 0) is 0; anything above 6 has 6 as
- * its nearest value, which is the saturation rule. */
+ * to the one whose mantissa bit (code bit 0) is 0; anything above the largest
+ * magnitude saturates to it (stated first, so that the distance comparison
+ * below never sees a magnitude large enough to absorb the grid values). */
 static int e2m1_nearest_mag_code(double a) {
+    if (a > E2M1_MAG[7]) return 7;
     int best = 0;
     double bd = fabs(a - E2M1_MAG[0]);
     for (int c = 1; c < 8; ++c) {

@@ -1,0 +1,203 @@
+"""ctypes binding of libosc.  Argument marshalling only: torch tensors in, torch tensors out,
+each function named after the C entry point it calls (see include/osc.h for the contract).
+
+bf16 tensors may be torch.bfloat16 or raw torch.uint16/int16 bit patterns.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+OSC_DT_F32, OSC_DT_BF16 = 0, 1
+OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libosc.so")
+_lib = None
+
+i64, i32, vp, sz = C.c_int64, C.c_int32, C.c_void_p, C.c_size_t
+_SIGS = {
+    "osc_last_error": (C.c_char_p, []),
+    "osc_version": (C.c_int, []),
+    "osc_table_to_index": (C.c_int, [vp, i32, i32, vp, vp]),
+    "osc_packed_weight_bytes": (sz, [i64, i64, i32]),
+    "osc_pack_weight": (C.c_int, [vp, i64, i64, i64, vp, i32, vp, vp]),
+    "osc_unpack_weight": (C.c_int, [vp, i64, i64, i32, vp, vp, vp, vp]),
+    "osc_packed_weight_fp8_bytes": (sz, [i64, i64]),
+    "osc_pack_weight_fp8": (C.c_int, [vp, i64, i64, i64, vp, vp]),
+    "osc_unpack_weight_fp8": (C.c_int, [vp, i64, i64, vp, vp, vp]),
+    "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
+    "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
+    "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
+    "osc_grouped_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, vp, i32, i64, vp, i64, i64, i32, vp,
+                                        C.c_int, i64, vp]),
+}
+
+
+class OscError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libosc error {code}: {msg}")
+        self.code = code
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise OSError(f"{_LIB_PATH} is missing: run `python paper_2604_12782_amd/build.py` "
+                          "(or __graft_entry__.build()) first")
+        _lib = C.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(_lib, name)
+            fn.restype, fn.argtypes = res, args
+    return _lib
+
+
+def osc_last_error():
+    return lib().osc_last_error().decode()
+
+
+def osc_version():
+    return lib().osc_version()
+
+
+def _check(rc):
+    if rc != 0:
+        raise OscError(rc, osc_last_error())
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _rows16(t):
+    assert t.dim() == 2 and t.stride(1) == 1 and t.element_size() == 2, "need a 2-D bf16 tensor"
+    return t
+
+
+def osc_table_to_index(table):
+    """table: int16 [Kg, R] (host; numpy or torch) -> int32 numpy array of channel ids."""
+    table = np.ascontiguousarray(np.asarray(table), dtype=np.int16)
+    Kg, R = table.shape
+    oidx = np.zeros(max(Kg * min(R, 32), 1), np.int32)
+    n = i32(0)
+    _check(lib().osc_table_to_index(table.ctypes.data, Kg, R, oidx.ctypes.data, C.addressof(n)))
+    return oidx[:n.value].copy()
+
+
+def osc_packed_weight_bytes(N, K, K_o):
+    return lib().osc_packed_weight_bytes(N, K, K_o)
+
+
+def osc_packed_weight_fp8_bytes(N, K):
+    return lib().osc_packed_weight_fp8_bytes(N, K)
+
+
+def osc_pack_weight(W, oidx, out=None):
+    """W bf16 [N, K] (device), oidx int32 [K_o] (device) -> packed weight (uint8 tensor)."""
+    W = _rows16(W)
+    N, K = W.shape
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if out is None:
+        out = torch.empty(osc_packed_weight_bytes(N, K, K_o), dtype=torch.uint8, device=W.device)
+    _check(lib().osc_pack_weight(_ptr(W), N, K, W.stride(0), _ptr(oidx) if K_o else None, K_o,
+                                 _ptr(out), _stream()))
+    return out
+
+
+def osc_unpack_weight(Wpack, N, K, K_o):
+    dev = Wpack.device
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    Ws = torch.empty((N, K // 32), dtype=torch.uint8, device=dev)
+    WL = torch.empty((K_o, N), dtype=torch.uint16, device=dev)
+    _check(lib().osc_unpack_weight(_ptr(Wpack), N, K, K_o, _ptr(Wq), _ptr(Ws), _ptr(WL), _stream()))
+    return Wq, Ws, WL
+
+
+def osc_pack_weight_fp8(W, out=None):
+    W = _rows16(W)
+    N, K = W.shape
+    if out is None:
+        out = torch.empty(osc_packed_weight_fp8_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib().osc_pack_weight_fp8(_ptr(W), N, K, W.stride(0), _ptr(out), _stream()))
+    return out
+
+
+def osc_unpack_weight_fp8(W8pack, N, K):
+    dev = W8pack.device
+    W8 = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    ws = torch.empty(N, dtype=torch.float32, device=dev)
+    _check(lib().osc_unpack_weight_fp8(_ptr(W8pack), N, K, _ptr(W8), _ptr(ws), _stream()))
+    return W8, ws
+
+
+def osc_quantize_act(X, oidx=None, fmt=OSC_FMT_MXFP4_OSC, ldb=None, out=None):
+    """X bf16 [M, K] (device).  MXFP4_OSC -> (Xq uint8 [M,K/2], Xs uint8 [M,K/32], B uint16 [M,ldb]);
+    FP8_E4M3_TOKEN -> (X8 uint8 [M,K], xs float32 [M]).  `out` may hold preallocated outputs."""
+    X = _rows16(X)
+    M, K = X.shape
+    dev = X.device
+    if fmt == OSC_FMT_FP8_E4M3_TOKEN:
+        X8, xs = out if out is not None else (torch.empty((M, K), dtype=torch.uint8, device=dev),
+                                              torch.empty(M, dtype=torch.float32, device=dev))
+        _check(lib().osc_quantize_act(_ptr(X), M, K, X.stride(0), None, 0, fmt, _ptr(X8), _ptr(xs),
+                                      None, 0, _stream()))
+        return X8, xs
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if out is not None:
+        Xq, Xs, B = out
+        ldb = 0 if B is None else B.stride(0)
+    else:
+        if ldb is None:
+            ldb = (K_o + 63) // 64 * 64
+        Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        Xs = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
+        B = torch.empty((M, ldb), dtype=torch.uint16, device=dev) if ldb else None
+    _check(lib().osc_quantize_act(_ptr(X), M, K, X.stride(0), _ptr(oidx) if K_o else None, K_o, fmt,
+                                  _ptr(Xq), _ptr(Xs), _ptr(B), ldb, _stream()))
+    return Xq, Xs, B
+
+
+def _y(M, N, y_dtype, dev, out):
+    if out is not None:
+        return out
+    return torch.empty((M, N), dtype=torch.float32 if y_dtype == OSC_DT_F32 else torch.bfloat16,
+                       device=dev)
+
+
+def osc_dual_gemm(Xq, Xs, B, Wpack, N, K, K_o, y_dtype=OSC_DT_F32, out=None):
+    M = Xq.shape[0]
+    Y = _y(M, N, y_dtype, Xq.device, out)
+    _check(lib().osc_dual_gemm(_ptr(Xq), _ptr(Xs), _ptr(B), 0 if B is None else B.stride(0),
+                               _ptr(Wpack), M, N, K, K_o, _ptr(Y), y_dtype, Y.stride(0) if M else N,
+                               _stream()))
+    return Y
+
+
+def osc_fp8_gemm(X8, xs, W8pack, N, K, expert_offsets=None, y_dtype=OSC_DT_F32, out=None):
+    M = X8.shape[0]
+    Y = _y(M, N, y_dtype, X8.device, out)
+    E = 0 if expert_offsets is None else int(expert_offsets.numel()) - 1
+    _check(lib().osc_fp8_gemm(_ptr(X8), _ptr(xs), _ptr(W8pack), M, N, K, _ptr(expert_offsets), E,
+                              _ptr(Y), y_dtype, Y.stride(0) if M else N, _stream()))
+    return Y
+
+
+def osc_grouped_dual_gemm(Xq, Xs, B, row_map, expert_offsets, T, Wpack, N, K, K_o,
+                          y_dtype=OSC_DT_F32, out=None):
+    Y = _y(T, N, y_dtype, Xq.device, out)
+    E = int(expert_offsets.numel()) - 1
+    _check(lib().osc_grouped_dual_gemm(_ptr(Xq), _ptr(Xs), _ptr(B), 0 if B is None else B.stride(0),
+                                       _ptr(row_map), _ptr(expert_offsets), E, T, _ptr(Wpack), N, K,
+                                       K_o, _ptr(Y), y_dtype, Y.stride(0) if T else N, _stream()))
+    return Y

@@ -1,0 +1,293 @@
+// C ABI of libosc: argument checking and dispatch.  Every check runs on the host before
+// anything is enqueued, so the error paths need no GPU.
+#include <cstdarg>
+#include <cstdio>
+
+#include "osc_internal.h"
+
+namespace osc {
+
+static thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(OSC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return OSC_OK;
+}
+
+PackLayout pack_layout(int64_t N, int64_t K, int32_t K_o) {
+    PackLayout L;
+    L.ldwl = ((int64_t)K_o + 63) / 64 * 64;
+    L.off_q = 0;
+    L.off_s = align_up((size_t)N * (size_t)(K / 2), 256);
+    L.off_l = align_up(L.off_s + (size_t)N * (size_t)(K / 32), 256);
+    L.total = align_up(L.off_l + (size_t)N * (size_t)L.ldwl * 2, 256);
+    return L;
+}
+
+Pack8Layout pack8_layout(int64_t N, int64_t K) {
+    Pack8Layout L;
+    L.off_w = 0;
+    L.off_s = align_up((size_t)N * (size_t)K, 256);
+    L.total = align_up(L.off_s + (size_t)N * 4, 256);
+    return L;
+}
+
+}  // namespace osc
+
+using namespace osc;
+
+#define REQUIRE(cond, code, ...) \
+    do {                         \
+        if (!(cond)) return fail(code, __VA_ARGS__); \
+    } while (0)
+
+extern "C" {
+
+const char* osc_last_error(void) { return g_err; }
+int osc_version(void) { return 100; }
+
+int osc_table_to_index(const int16_t* table, int32_t Kg, int32_t R, int32_t* oidx, int32_t* K_o) {
+    REQUIRE(table && oidx && K_o, OSC_ERR_NULL, "osc_table_to_index: null pointer");
+    REQUIRE(Kg >= 0 && R >= 0, OSC_ERR_SHAPE, "osc_table_to_index: Kg=%d R=%d", Kg, R);
+    int32_t n = 0;
+    for (int32_t g = 0; g < Kg; ++g) {
+        uint32_t seen = 0;
+        for (int32_t s = 0; s < R; ++s) {
+            const int j = table[(int64_t)g * R + s];
+            if (j == -1) continue;
+            REQUIRE(j >= 0 && j < 32, OSC_ERR_TABLE, "osc_table_to_index: group %d holds index %d", g, j);
+            REQUIRE(!(seen >> j & 1u), OSC_ERR_TABLE, "osc_table_to_index: group %d repeats index %d", g, j);
+            seen |= 1u << j;
+        }
+        while (seen) {
+            const int j = __builtin_ctz(seen);
+            seen &= seen - 1;
+            oidx[n++] = g * 32 + j;
+        }
+    }
+    *K_o = n;
+    return OSC_OK;
+}
+
+size_t osc_packed_weight_bytes(int64_t N, int64_t K, int32_t K_o) {
+    if (N < 0 || K < 0 || K % 32 || K_o < 0) return 0;
+    return pack_layout(N, K, K_o).total;
+}
+
+size_t osc_packed_weight_fp8_bytes(int64_t N, int64_t K) {
+    if (N < 0 || K < 0) return 0;
+    return pack8_layout(N, K).total;
+}
+
+static int check_mx_shape(const char* who, int64_t rows, int64_t K, int64_t ld, int32_t K_o) {
+    REQUIRE(rows >= 0 && K >= 0 && K_o >= 0, OSC_ERR_SHAPE, "%s: negative extent", who);
+    REQUIRE(K % 32 == 0, OSC_ERR_SHAPE, "%s: K=%lld is not a multiple of 32", who, (long long)K);
+    REQUIRE(ld >= K, OSC_ERR_SHAPE, "%s: leading dimension %lld < K=%lld", who, (long long)ld, (long long)K);
+    REQUIRE(K_o <= K, OSC_ERR_SHAPE, "%s: K_o=%d > K", who, K_o);
+    REQUIRE(rows <= 0x7fffffff && K <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "%s: extent above 2^31-1", who);
+    return OSC_OK;
+}
+
+int osc_pack_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
+                    int32_t K_o, void* Wpack, void* stream) {
+    int rc = check_mx_shape("osc_pack_weight", N, K, ldw, K_o);
+    if (rc) return rc;
+    if (N == 0) return OSC_OK;
+    REQUIRE(W && Wpack && (K_o == 0 || oidx), OSC_ERR_NULL, "osc_pack_weight: null pointer");
+    REQUIRE(ldw % 8 == 0 && aligned(W, 16) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_pack_weight: W rows must be 16-byte aligned and Wpack 256-byte aligned");
+    PackLayout L = pack_layout(N, K, K_o);
+    uint8_t* base = static_cast<uint8_t*>(Wpack);
+    if (K > 0) {
+        rc = launch_quant_mxfp4(static_cast<const uint16_t*>(W), N, K, ldw, nullptr, 0, base + L.off_q,
+                                base + L.off_s, nullptr, 0, as_stream(stream));
+        if (rc) return rc;
+    }
+    return launch_gather_wl(static_cast<const uint16_t*>(W), N, K, ldw, oidx, K_o,
+                            reinterpret_cast<uint16_t*>(base + L.off_l), L.ldwl, as_stream(stream));
+}
+
+int osc_unpack_weight(const void* Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t* Wq, uint8_t* Ws,
+                      void* WL, void* stream) {
+    int rc = check_mx_shape("osc_unpack_weight", N, K, K, K_o);
+    if (rc) return rc;
+    if (N == 0) return OSC_OK;
+    REQUIRE(Wpack, OSC_ERR_NULL, "osc_unpack_weight: null pointer");
+    PackLayout L = pack_layout(N, K, K_o);
+    const uint8_t* base = static_cast<const uint8_t*>(Wpack);
+    hipStream_t st = as_stream(stream);
+    if (Wq && K > 0 &&
+        hipMemcpyAsync(Wq, base + L.off_q, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight: copy of codes failed");
+    if (Ws && K > 0 &&
+        hipMemcpyAsync(Ws, base + L.off_s, (size_t)N * (K / 32), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight: copy of scales failed");
+    if (WL)
+        return launch_unpack_wl(reinterpret_cast<const uint16_t*>(base + L.off_l), L.ldwl, N, K_o,
+                                static_cast<uint16_t*>(WL), st);
+    return OSC_OK;
+}
+
+int osc_pack_weight_fp8(const void* W, int64_t N, int64_t K, int64_t ldw, void* W8pack, void* stream) {
+    REQUIRE(N >= 0 && K >= 0, OSC_ERR_SHAPE, "osc_pack_weight_fp8: negative extent");
+    REQUIRE(ldw >= K, OSC_ERR_SHAPE, "osc_pack_weight_fp8: ldw < K");
+    REQUIRE(K % 16 == 0, OSC_ERR_SHAPE, "osc_pack_weight_fp8: K=%lld is not a multiple of 16", (long long)K);
+    REQUIRE(N <= 0x7fffffff && K <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "osc_pack_weight_fp8: extent above 2^31-1");
+    if (N == 0) return OSC_OK;
+    REQUIRE(W && W8pack, OSC_ERR_NULL, "osc_pack_weight_fp8: null pointer");
+    REQUIRE(ldw % 8 == 0 && aligned(W, 16) && aligned(W8pack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_pack_weight_fp8: W rows must be 16-byte aligned and W8pack 256-byte aligned");
+    Pack8Layout L = pack8_layout(N, K);
+    uint8_t* base = static_cast<uint8_t*>(W8pack);
+    return launch_quant_fp8(static_cast<const uint16_t*>(W), N, K, ldw, base + L.off_w,
+                            reinterpret_cast<float*>(base + L.off_s), as_stream(stream));
+}
+
+int osc_unpack_weight_fp8(const void* W8pack, int64_t N, int64_t K, uint8_t* W8, float* ws, void* stream) {
+    REQUIRE(N >= 0 && K >= 0, OSC_ERR_SHAPE, "osc_unpack_weight_fp8: negative extent");
+    if (N == 0) return OSC_OK;
+    REQUIRE(W8pack, OSC_ERR_NULL, "osc_unpack_weight_fp8: null pointer");
+    Pack8Layout L = pack8_layout(N, K);
+    const uint8_t* base = static_cast<const uint8_t*>(W8pack);
+    hipStream_t st = as_stream(stream);
+    if (W8 && K > 0 &&
+        hipMemcpyAsync(W8, base + L.off_w, (size_t)N * K, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight_fp8: copy of codes failed");
+    if (ws && hipMemcpyAsync(ws, base + L.off_s, (size_t)N * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight_fp8: copy of scales failed");
+    return OSC_OK;
+}
+
+int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx, int32_t K_o,
+                     int fmt, uint8_t* Xq, void* Xs, void* B, int64_t ldb, void* stream) {
+    REQUIRE(fmt == OSC_FMT_MXFP4_OSC || fmt == OSC_FMT_FP8_E4M3_TOKEN, OSC_ERR_UNSUPPORTED,
+            "osc_quantize_act: unknown format %d", fmt);
+    if (fmt == OSC_FMT_FP8_E4M3_TOKEN) {
+        REQUIRE(M >= 0 && K >= 0, OSC_ERR_SHAPE, "osc_quantize_act: negative extent");
+        REQUIRE(ldx >= K, OSC_ERR_SHAPE, "osc_quantize_act: ldx < K");
+        REQUIRE(K % 8 == 0, OSC_ERR_SHAPE, "osc_quantize_act: FP8 needs K %% 8 == 0, got %lld", (long long)K);
+        REQUIRE(M <= 0x7fffffff && K <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "osc_quantize_act: extent above 2^31-1");
+        if (M == 0) return OSC_OK;
+        REQUIRE(Xq && Xs && (X || K == 0), OSC_ERR_NULL, "osc_quantize_act: null pointer");
+        REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 8) && aligned(Xs, 4), OSC_ERR_UNSUPPORTED,
+                "osc_quantize_act: misaligned pointer or ldx %% 8 != 0");
+        return launch_quant_fp8(static_cast<const uint16_t*>(X), M, K, ldx, Xq, static_cast<float*>(Xs),
+                                as_stream(stream));
+    }
+    int rc = check_mx_shape("osc_quantize_act", M, K, ldx, K_o);
+    if (rc) return rc;
+    REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "osc_quantize_act: ldb=%lld < K_o=%d", (long long)ldb, K_o);
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(X && Xq && Xs, OSC_ERR_NULL, "osc_quantize_act: null pointer");
+    REQUIRE(K_o == 0 || (oidx && B), OSC_ERR_NULL, "osc_quantize_act: K_o > 0 needs oidx and B");
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 4), OSC_ERR_UNSUPPORTED,
+            "osc_quantize_act: misaligned pointer or ldx %% 8 != 0");
+    if (B) {
+        REQUIRE(ldb >= 0, OSC_ERR_SHAPE, "osc_quantize_act: negative ldb");
+        REQUIRE(ldb % 8 == 0 && aligned(B, 16), OSC_ERR_UNSUPPORTED,
+                "osc_quantize_act: B must be 16-byte aligned with ldb %% 8 == 0");
+    }
+    return launch_quant_mxfp4(static_cast<const uint16_t*>(X), M, K, ldx, oidx, K_o, Xq,
+                              static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(B), B ? ldb : 0,
+                              as_stream(stream));
+}
+
+static int check_gemm_common(const char* who, int64_t M, int64_t N, int64_t K, const void* Y, int y_dtype,
+                             int64_t ldy) {
+    REQUIRE(M >= 0 && N >= 0 && K >= 0, OSC_ERR_SHAPE, "%s: negative extent", who);
+    REQUIRE(y_dtype == OSC_DT_F32 || y_dtype == OSC_DT_BF16, OSC_ERR_UNSUPPORTED, "%s: unknown y_dtype %d", who, y_dtype);
+    REQUIRE(ldy >= N, OSC_ERR_SHAPE, "%s: ldy=%lld < N=%lld", who, (long long)ldy, (long long)N);
+    REQUIRE(M <= 0x7fffffff && N <= 0x7fffffff && K <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "%s: extent above 2^31-1", who);
+    if (M > 0 && N > 0) REQUIRE(Y, OSC_ERR_NULL, "%s: Y is null", who);
+    return OSC_OK;
+}
+
+static int dual_common(const char* who, const uint8_t* Xq, const uint8_t* Xs, const void* B, int64_t ldb,
+                       const int32_t* row_map, const int32_t* off, int32_t E, int64_t M, const void* Wpack,
+                       int64_t N, int64_t K, int32_t K_o, void* Y, int y_dtype, int64_t ldy, void* stream) {
+    int rc = check_gemm_common(who, M, N, K, Y, y_dtype, ldy);
+    if (rc) return rc;
+    REQUIRE(K % 32 == 0, OSC_ERR_SHAPE, "%s: K=%lld is not a multiple of 32", who, (long long)K);
+    REQUIRE(K_o >= 0 && K_o <= K, OSC_ERR_SHAPE, "%s: K_o=%d out of range", who, K_o);
+    REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "%s: ldb=%lld < K_o=%d", who, (long long)ldb, K_o);
+    if (M == 0 || N == 0) return OSC_OK;
+    REQUIRE(Wpack && (K == 0 || (Xq && Xs)) && (K_o == 0 || B), OSC_ERR_NULL, "%s: null pointer", who);
+    REQUIRE(aligned(Xq, 16) && aligned(Wpack, 256) && (K / 2) % 16 == 0, OSC_ERR_UNSUPPORTED,
+            "%s: Xq must be 16-byte aligned, Wpack 256-byte aligned and K a multiple of 32", who);
+    REQUIRE(K_o == 0 || (ldb % 8 == 0 && aligned(B, 16)), OSC_ERR_UNSUPPORTED,
+            "%s: B must be 16-byte aligned with ldb %% 8 == 0", who);
+    GemmProblem p{};
+    p.Xq = Xq;
+    p.Xs = Xs;
+    p.B = static_cast<const uint16_t*>(B);
+    p.ldb = K_o ? ldb : 0;
+    p.row_map = row_map;
+    p.expert_offsets = off;
+    p.E = E;
+    p.Wpack = static_cast<const uint8_t*>(Wpack);
+    p.pack_stride = pack_layout(N, K, K_o).total;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.K_o = K_o;
+    p.Y = Y;
+    p.y_dtype = y_dtype;
+    p.ldy = ldy;
+    return launch_dual_gemm(p, as_stream(stream));
+}
+
+int osc_dual_gemm(const uint8_t* Xq, const uint8_t* Xs, const void* B, int64_t ldb, const void* Wpack,
+                  int64_t M, int64_t N, int64_t K, int32_t K_o, void* Y, int y_dtype, int64_t ldy,
+                  void* stream) {
+    return dual_common("osc_dual_gemm", Xq, Xs, B, ldb, nullptr, nullptr, 0, M, Wpack, N, K, K_o, Y, y_dtype,
+                       ldy, stream);
+}
+
+int osc_grouped_dual_gemm(const uint8_t* Xq, const uint8_t* Xs, const void* B, int64_t ldb,
+                          const int32_t* row_map, const int32_t* expert_offsets, int32_t E, int64_t T,
+                          const void* Wpack, int64_t N, int64_t K, int32_t K_o, void* Y, int y_dtype,
+                          int64_t ldy, void* stream) {
+    REQUIRE(E >= 0, OSC_ERR_SHAPE, "osc_grouped_dual_gemm: E=%d", E);
+    REQUIRE(expert_offsets, OSC_ERR_NULL, "osc_grouped_dual_gemm: expert_offsets is null");
+    if (E == 0) return OSC_OK;
+    return dual_common("osc_grouped_dual_gemm", Xq, Xs, B, ldb, row_map, expert_offsets, E, T, Wpack, N, K, K_o,
+                       Y, y_dtype, ldy, stream);
+}
+
+int osc_fp8_gemm(const uint8_t* X8, const float* xs, const void* W8pack, int64_t M, int64_t N, int64_t K,
+                 const int32_t* expert_offsets, int32_t E, void* Y, int y_dtype, int64_t ldy, void* stream) {
+    int rc = check_gemm_common("osc_fp8_gemm", M, N, K, Y, y_dtype, ldy);
+    if (rc) return rc;
+    REQUIRE(K % 16 == 0, OSC_ERR_SHAPE, "osc_fp8_gemm: K=%lld is not a multiple of 16", (long long)K);
+    REQUIRE(!expert_offsets || E >= 0, OSC_ERR_SHAPE, "osc_fp8_gemm: E=%d", E);
+    if (M == 0 || N == 0 || (expert_offsets && E == 0)) return OSC_OK;
+    REQUIRE(W8pack && xs && (K == 0 || X8), OSC_ERR_NULL, "osc_fp8_gemm: null pointer");
+    REQUIRE(aligned(X8, 16) && aligned(W8pack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_fp8_gemm: X8 must be 16-byte aligned and W8pack 256-byte aligned");
+    GemmProblem p{};
+    p.Xq = X8;
+    p.xs = xs;
+    p.expert_offsets = expert_offsets;
+    p.E = expert_offsets ? E : 0;
+    p.Wpack = static_cast<const uint8_t*>(W8pack);
+    p.pack_stride = pack8_layout(N, K).total;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.K_o = 0;
+    p.Y = Y;
+    p.y_dtype = y_dtype;
+    p.ldy = ldy;
+    return launch_fp8_gemm(p, as_stream(stream));
+}
+
+}  // extern "C"

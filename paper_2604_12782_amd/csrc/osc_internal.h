@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libosc (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/osc.h"
+
+namespace osc {
+
+int fail(int code, const char* fmt, ...);  // records the thread-local message, returns code
+int check_launch(const char* what);        // hipGetLastError -> OSC_OK / OSC_ERR_HIP
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Layout of a packed dual-path weight: three sections, each 256-byte aligned.
+struct PackLayout {
+    size_t off_q;   // uint8 [N, K/2]   MXFP4 codes, K-major
+    size_t off_s;   // uint8 [N, K/32]  E8M0 scales
+    size_t off_l;   // bf16  [N, ldwl]  W_L transposed (K_o-major), zero padded to ldwl
+    int64_t ldwl;   // round_up(K_o, 64)
+    size_t total;
+};
+PackLayout pack_layout(int64_t N, int64_t K, int32_t K_o);
+
+// Layout of a packed FP8 weight.
+struct Pack8Layout {
+    size_t off_w;  // uint8 [N, K]
+    size_t off_s;  // float [N]
+    size_t total;
+};
+Pack8Layout pack8_layout(int64_t N, int64_t K);
+
+// kernels' host launchers (each enqueues on `st`, returns OSC_OK / OSC_ERR_HIP)
+int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx,
+                       int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
+                       hipStream_t st);
+int launch_quant_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* X8, float* xs,
+                     hipStream_t st);
+int launch_gather_wl(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
+                     int32_t K_o, uint16_t* WLt, int64_t ldwl, hipStream_t st);
+int launch_unpack_wl(const uint16_t* WLt, int64_t ldwl, int64_t N, int32_t K_o, uint16_t* WL,
+                     hipStream_t st);
+
+struct GemmProblem {
+    // activations
+    const uint8_t* Xq;   // dual: codes [*, K/2]; fp8: codes [*, K]
+    const uint8_t* Xs;   // dual: E8M0 [*, K/32]
+    const float* xs;     // fp8: per-row scale
+    const uint16_t* B;   // dual: gathered bf16 [*, ldb]
+    int64_t ldb;
+    const int32_t* row_map;         // grouped dual: routed row -> activation row (or null)
+    const int32_t* expert_offsets;  // grouped: [E+1] (or null)
+    int32_t E;
+    // weights (first expert; experts are pack_stride bytes apart)
+    const uint8_t* Wpack;
+    size_t pack_stride;
+    int64_t M, N, K;
+    int32_t K_o;
+    void* Y;
+    int y_dtype;
+    int64_t ldy;
+};
+int launch_dual_gemm(const GemmProblem& p, hipStream_t st);
+int launch_fp8_gemm(const GemmProblem& p, hipStream_t st);
+
+}  // namespace osc

@@ -58,7 +58,7 @@ def test_e2m1_encode_ties_and_grid():
         assert oracle.e2m1_encode(a) == _e2m1_by_thresholds(a), a
         assert oracle.e2m1_encode(-a, True) == _e2m1_by_thresholds(a) | 8
     # saturation: 7.0 would tie with a non-existent 8; everything above 6 is 6
-    for a in (6.0, 6.5, 7.0, 7.5, 7.999, 100.0):
+    for a in (6.0, 6.5, 7.0, 7.5, 7.999, 100.0, 2.0 ** 60, 1.7e38, 1e300):
         assert oracle.e2m1_encode(a) == 7
     # the sign bit follows the input even when the magnitude rounds to zero
     assert oracle.e2m1_encode(-0.0, True) == 8

@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the OSC dual-path linear layer on one MI355X.
+
+One step = the whole hot path of one Qwen3-8B attention block's linear layers at M tokens
+(BASELINE configs[1]): quantise+gather the attention input, dual-path GEMMs q (4096->4096),
+k and v (4096->1024) on it, quantise+gather the o-projection input, dual-path GEMM o
+(4096->4096).  Inputs are synthetic (seeded N(0,1) with two token-persistent outlier channels
+per 32-group), resident in HBM before the timed region.  The same GEMM shapes are also run
+through the library's own FP8 W8A8 path for the speed-up figure.
+
+Prints one JSON line.  `value` = sum over the four GEMMs of 2*M*N*K, divided by the time of a
+whole step (quantisers included).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MXFP4_TFLOPS = 10066.0  # MI355X dense MXFP4 matrix peak
+PEAK_FP8_TFLOPS = 5033.0
+PEAK_HBM_GBS = 8000.0
+K_HID = 4096
+PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
+
+
+def cpu_baseline(rows=512):
+    """The oracle, as it stands, on a bounded sample of the same workload: `rows` tokens through
+    the quantiser and the q projection.  Reported baseline only."""
+    import oracle
+    import workloads as wl
+    c = wl.config2_attn(rows, 4096)
+    oidx = oracle.table_to_index(c["table"])
+    Wq, Ws, _ = oracle.quantize_mxfp4_osc(c["W"])
+    WL = oracle.gather_wl(c["W"], oidx)
+    t0 = time.perf_counter()
+    Xq, Xs, B = oracle.quantize_mxfp4_osc(c["X"], oidx)
+    Y = oracle.dual_gemm(Xq, Xs, B, Wq, Ws, WL)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * rows * 4096 * K_HID
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{rows} tokens of configs[1]: quantise+gather, then the q projection "
+                      f"(N=4096, K=4096, K_o=256) in {dt:.2f} s"}, float(np.abs(Y).max())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--tokens", type=int, default=8192)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import paper_2604_12782_amd as osc
+    import workloads as wl
+    osc.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    M = args.tokens
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- inputs (seeded, built on the CPU, uploaded once) -----------------------------------
+    X1, table1 = wl.activations_persistent(2001, M, K_HID, 2)
+    X2, table2 = wl.activations_persistent(2002, M, K_HID, 2)
+    oidx1 = up(osc.osc_table_to_index(table1))
+    oidx2 = up(osc.osc_table_to_index(table2))
+    K_o = int(oidx1.numel())
+    dX1, dX2 = up(X1), up(X2)
+    packs, packs8 = {}, {}
+    for name, N in PROJ:
+        W = up(wl.weights(2100 + len(packs), N, K_HID))
+        packs[name] = osc.osc_pack_weight(W, oidx2 if name == "o" else oidx1)
+        packs8[name] = osc.osc_pack_weight_fp8(W)
+        del W
+    ydt = osc.OSC_DT_BF16
+    q1 = osc.osc_quantize_act(dX1, oidx1)
+    q2 = osc.osc_quantize_act(dX2, oidx2)
+    f1 = osc.osc_quantize_act(dX1, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    f2 = osc.osc_quantize_act(dX2, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    Y = {n: torch.empty((M, N), dtype=torch.bfloat16, device=dev) for n, N in PROJ}
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    dom = []  # event pairs around the dominant kernel (q projection), on the launch stream
+
+    def step(timed=False):
+        osc.osc_quantize_act(dX1, oidx1, out=q1)
+        for n, N in PROJ[:3]:
+            if timed and n == "q":
+                e0, e1 = ev(), ev()
+                e0.record()
+            osc.osc_dual_gemm(*q1, packs[n], N, K_HID, K_o, ydt, out=Y[n])
+            if timed and n == "q":
+                e1.record()
+                dom.append((e0, e1))
+        osc.osc_quantize_act(dX2, oidx2, out=q2)
+        osc.osc_dual_gemm(*q2, packs["o"], 4096, K_HID, K_o, ydt, out=Y["o"])
+
+    def step_fp8():
+        osc.osc_quantize_act(dX1, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f1)
+        for n, N in PROJ[:3]:
+            osc.osc_fp8_gemm(*f1, packs8[n], N, K_HID, y_dtype=ydt, out=Y[n])
+        osc.osc_quantize_act(dX2, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f2)
+        osc.osc_fp8_gemm(*f2, packs8["o"], 4096, K_HID, y_dtype=ydt, out=Y["o"])
+
+    def timed_loop(fn, steps, warmup, **kw):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn(**kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_step = timed_loop(step, args.steps, args.warmup, timed=True)
+    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in dom]))
+    ms_fp8 = timed_loop(step_fp8, max(args.steps // 2, 1), 3)
+
+    def time_one(fn, reps=20):
+        fn()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_quant = time_one(lambda: osc.osc_quantize_act(dX1, oidx1, out=q1))
+    ms_quant8 = time_one(lambda: osc.osc_quantize_act(dX1, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f1))
+    per = {}
+    for n, N in PROJ:
+        qq = q2 if n == "o" else q1
+        ff = f2 if n == "o" else f1
+        per[n] = (time_one(lambda: osc.osc_dual_gemm(*qq, packs[n], N, K_HID, K_o, ydt, out=Y[n])),
+                  time_one(lambda: osc.osc_fp8_gemm(*ff, packs8[n], N, K_HID, y_dtype=ydt, out=Y[n])))
+
+    flops = sum(2.0 * M * N * K_HID for _, N in PROJ)
+    value = flops / (ms_step * 1e-3) / 1e12
+    dom_flops = 2.0 * M * 4096 * K_HID
+    dom_tflops = dom_flops / (dom_ms * 1e-3) / 1e12
+    quant_bytes = M * (K_HID * 2 + K_HID // 2 + K_HID // 32 + 2 * K_o)
+    out = {
+        "metric": "OSC linear TFLOP/s & % MXFP4 MFMA peak vs FP8 W8A8, Qwen3-8B shapes",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "mxfp4 x mxfp4 + bf16 x bf16 -> f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[1] Qwen3-8B attention projections, M={M}: quant+gather, "
+                               "q/o 4096->4096, k/v 4096->1024, 2 outliers per 32-group (K_o=256), Y bf16",
+                   "tokens": M, "K": K_HID, "K_o": K_o},
+        "roofline": {"bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_MXFP4_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_MXFP4_TFLOPS, 4), "traffic": None,
+                     "kernel": f"dual-path GEMM M={M} N=4096 K=4096 K_o={K_o}", "avg_ms": round(dom_ms, 4)},
+        "frac_mxfp4_peak_whole_step": round(value / PEAK_MXFP4_TFLOPS, 4),
+        "fp8_w8a8": {"ms_per_step": round(ms_fp8, 4), "tflops": round(flops / (ms_fp8 * 1e-3) / 1e12, 2),
+                     "speedup_osc_over_fp8": round(ms_fp8 / ms_step, 3),
+                     "model_speedup_compute_bound": round(2 / (1 + 4 * 2 / 32), 3)},
+        "kernels_ms": {"quant_mxfp4_gather": round(ms_quant, 4), "quant_fp8": round(ms_quant8, 4),
+                       **{f"dual_gemm_{n}": round(v[0], 4) for n, v in per.items()},
+                       **{f"fp8_gemm_{n}": round(v[1], 4) for n, v in per.items()}},
+        "quant_roofline": {"bound": "hbm", "achieved": round(quant_bytes / (ms_quant * 1e-3) / 1e9, 1),
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": round(quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+    if args.detail:
+        for k, v in out["kernels_ms"].items():
+            print(f"  {k:24s} {v:9.4f} ms", file=sys.stderr)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"], _ = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,103 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_12782_amd as osc
+from paper_2604_12782_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(osc.lib_path()):
+        from paper_2604_12782_amd import build
+        build.build()
+    return osc.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "osc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(osc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    names = declared_symbols()
+    assert {"osc_quantize_act", "osc_dual_gemm", "osc_fp8_gemm", "osc_grouped_dual_gemm"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in osc.h but not exported"
+        assert n in binding._SIGS, f"{n} has no ctypes signature"
+        assert hasattr(osc, n), f"{n} has no Python binding of the same name"
+    assert osc.osc_version() >= 100
+
+
+def test_table_to_index_host(lib):
+    t = np.array([[5, -1], [-1, -1], [31, 0], [-1, 7]], np.int16)
+    assert osc.osc_table_to_index(t).tolist() == [5, 64, 95, 96 + 7]
+    assert osc.osc_table_to_index(np.full((4, 1), -1, np.int16)).tolist() == []
+    for bad in ([[32]], [[-2]], [[4, 4]]):
+        with pytest.raises(osc.OscError) as e:
+            osc.osc_table_to_index(np.array(bad, np.int16))
+        assert e.value.code == -3
+
+
+def test_packed_sizes(lib):
+    # sections: codes N*K/2, scales N*K/32, W_L N*round_up(K_o,64)*2, each 256-byte aligned
+    assert osc.osc_packed_weight_bytes(4096, 4096, 256) == 4096 * 2048 + 4096 * 128 + 4096 * 256 * 2
+    assert osc.osc_packed_weight_bytes(256, 256, 8) == 256 * 128 + 256 * 8 + 256 * 64 * 2
+    assert osc.osc_packed_weight_bytes(3, 32, 0) == 256 + 256
+    assert osc.osc_packed_weight_bytes(16, 33, 0) == 0  # K % 32 != 0
+    assert osc.osc_packed_weight_fp8_bytes(4096, 12288) == 4096 * 12288 + 4096 * 4
+
+
+FAKE = 0x10000  # a non-null, suitably aligned "device pointer" that is never dereferenced
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    q = lib.osc_quantize_act
+    # null pointers
+    assert q(None, 4, 64, 64, None, 0, 0, FAKE, FAKE, None, 0, None) == -1
+    assert "null" in osc.osc_last_error()
+    assert q(FAKE, 4, 64, 64, None, 2, 0, FAKE, FAKE, FAKE, 8, None) == -1  # K_o > 0 without oidx
+    # shapes
+    assert q(FAKE, 4, 48, 48, None, 0, 0, FAKE, FAKE, None, 0, None) == -2  # K % 32
+    assert q(FAKE, 4, 64, 32, None, 0, 0, FAKE, FAKE, None, 0, None) == -2  # ldx < K
+    assert q(FAKE, -1, 64, 64, None, 0, 0, FAKE, FAKE, None, 0, None) == -2
+    assert q(FAKE, 4, 64, 64, FAKE, 9, 0, FAKE, FAKE, FAKE, 8, None) == -2  # ldb < K_o
+    # unsupported: format enum, alignment
+    assert q(FAKE, 4, 64, 64, None, 0, 7, FAKE, FAKE, None, 0, None) == -4
+    assert q(FAKE + 2, 4, 64, 64, None, 0, 0, FAKE, FAKE, None, 0, None) == -4
+    assert q(FAKE, 4, 64, 68, None, 0, 0, FAKE, FAKE, None, 0, None) == -4  # ldx % 8
+    assert q(FAKE, 4, 64, 64, FAKE, 2, 0, FAKE, FAKE, FAKE, 12, None) == -4  # ldb % 8
+    # empty problems are fine and touch nothing
+    assert q(None, 0, 64, 64, None, 0, 0, None, None, None, 0, None) == 0
+    g = lib.osc_dual_gemm
+    assert g(None, None, None, 0, None, 0, 64, 64, 0, None, 0, 64, None) == 0
+    assert g(FAKE, FAKE, None, 0, FAKE, 4, 64, 48, 0, FAKE, 0, 64, None) == -2  # K % 32
+    assert g(FAKE, FAKE, None, 0, FAKE, 4, 64, 64, 0, FAKE, 0, 32, None) == -2  # ldy < N
+    assert g(FAKE, FAKE, None, 0, FAKE, 4, 64, 64, 0, FAKE, 5, 64, None) == -4  # y_dtype
+    assert g(FAKE, FAKE, None, 0, None, 4, 64, 64, 0, FAKE, 0, 64, None) == -1  # Wpack null
+    assert g(FAKE, FAKE, None, 0, FAKE, 4, 64, 64, 8, FAKE, 0, 64, None) == -2  # K_o without ldb
+    f = lib.osc_fp8_gemm
+    assert f(FAKE, FAKE, FAKE, 4, 64, 40, None, 0, FAKE, 0, 64, None) == -2  # K % 16
+    assert f(FAKE, None, FAKE, 4, 64, 64, None, 0, FAKE, 0, 64, None) == -1
+    gg = lib.osc_grouped_dual_gemm
+    assert gg(FAKE, FAKE, None, 0, None, None, 2, 8, FAKE, 64, 64, 0, FAKE, 0, 64, None) == -1  # offsets null
+    assert gg(FAKE, FAKE, None, 0, None, FAKE, -1, 8, FAKE, 64, 64, 0, FAKE, 0, 64, None) == -2
+    p = lib.osc_pack_weight
+    assert p(FAKE, 4, 40, 40, None, 0, FAKE, None) == -2
+    assert p(None, 4, 64, 64, None, 0, FAKE, None) == -1
+    assert p(FAKE, 4, 64, 64, None, 0, FAKE + 16, None) == -4  # Wpack alignment
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libosc.so")
+    with pytest.raises(OSError):
+        binding.lib()

@@ -14,6 +14,12 @@
  *     osc_last_error() gives a thread-local description of the last error.
  *   - M == 0 or N == 0 is a valid no-op.
  *   - bf16 tensors are raw 16-bit patterns.  Inputs must be finite.
+ *   - E8M0 scale tensors of R rows and K channels use the ROW-BLOCK-MAJOR layout
+ *     uint8 [ceil(R/32)][ceil(K/128)][32][4]: the scale of (row m, group g) is byte
+ *       ((m/32) * ceil(K/128) + g/4) * 128 + (m%32) * 4 + g%4 .
+ *     The 32 rows of one matrix-core tile then read the four scales of a 128-channel
+ *     span as 128 contiguous bytes.  Bytes of groups >= K/32 are written as 0; bytes
+ *     of rows >= R are never written (the buffer must still hold them).
  */
 #ifndef OSC_H
 #define OSC_H
@@ -64,9 +70,9 @@ int osc_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oid
  *   Wpack  osc_packed_weight_bytes(N, K, K_o) bytes, 256-byte aligned; receives the
  *          MXFP4 codes and E8M0 scales of every row of W (nothing zeroed) and
  *          W_L[o][n] = W[n][oidx[o]] in the layout the GEMM kernels read.
- * osc_unpack_weight writes the canonical forms back out: Wq uint8 [N, K/2]
+ * osc_unpack_weight writes the plain forms back out: Wq uint8 [N, K/2]
  * (channel 2i in bits 3:0 of byte i, 2i+1 in bits 7:4), Ws uint8 [N, K/32]
- * (E8M0), WL bf16 [K_o, N]; any of the three may be NULL to skip it.
+ * (E8M0, plain row-major), WL bf16 [K_o, N]; any of the three may be NULL to skip it.
  */
 size_t osc_packed_weight_bytes(int64_t N, int64_t K, int32_t K_o);
 int osc_pack_weight(const void *W, int64_t N, int64_t K, int64_t ldw, const int32_t *oidx,
@@ -101,7 +107,7 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  *   X     bf16 [M, ldx], ldx >= K, K % 32 == 0, 16-byte aligned rows (ldx % 8 == 0)
  *   oidx  int32 [K_o], ascending, distinct, each in [0, K); NULL iff K_o == 0
  *   Xq    uint8 [M, K/2]   channel 2i -> bits 3:0 of byte i, 2i+1 -> bits 7:4
- *   Xs    uint8 [M, K/32]  E8M0 codes
+ *   Xs    E8M0 codes, row-block-major, osc_act_scale_bytes(M, K) bytes, 4-byte aligned
  *   B     bf16 [M, ldb], ldb >= K_o, ldb % 8 == 0; columns K_o..ldb-1 are set to +0.
  *         May be NULL iff K_o == 0 (then ldb is ignored).
  *
@@ -120,10 +126,17 @@ int osc_quantize_act(const void *X, int64_t M, int64_t K, int64_t ldx, const int
                      void *stream);
 
 /*
+ * Size in bytes of the row-block-major scale tensor of an [M, K] activation, and its
+ * conversion to plain row-major uint8 [M, K/32] (for inspection and tests).
+ */
+size_t osc_act_scale_bytes(int64_t M, int64_t K);
+int osc_unpack_act_scales(const uint8_t *Xs, int64_t M, int64_t K, uint8_t *out, void *stream);
+
+/*
  * Dual-path GEMM (Section 3.3.1, Eq. dual-path):
  *   Y[m,n] = sum_g 2^(Xs[m,g] + Ws[n,g] - 254) * sum_{j<32} e2m1(Xq[m,32g+j]) * e2m1(Wq[n,32g+j])
  *          + sum_{o<K_o} B[m,o] * W_L[o,n]
- * Path A on the block-scaled FP4 matrix cores, Path B on the bf16 matrix cores,
+ * (Xs[m,g] meaning the scale of row m, group g, wherever the layout puts it.)  Path A on the block-scaled FP4 matrix cores, Path B on the bf16 matrix cores,
  * both into one fp32 accumulator; Y is that accumulator, converted (round to
  * nearest even) when y_dtype is OSC_DT_BF16.
  *   Xq, Xs, B, ldb   as written by osc_quantize_act(fmt = MXFP4_OSC) with the same K, K_o

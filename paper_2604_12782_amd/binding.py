@@ -27,6 +27,8 @@ _SIGS = {
     "osc_packed_weight_fp8_bytes": (sz, [i64, i64]),
     "osc_pack_weight_fp8": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_unpack_weight_fp8": (C.c_int, [vp, i64, i64, vp, vp, vp]),
+    "osc_act_scale_bytes": (sz, [i64, i64]),
+    "osc_unpack_act_scales": (C.c_int, [vp, i64, i64, vp, vp]),
     "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
     "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
@@ -141,8 +143,20 @@ def osc_unpack_weight_fp8(W8pack, N, K):
     return W8, ws
 
 
+def osc_act_scale_bytes(M, K):
+    return lib().osc_act_scale_bytes(M, K)
+
+
+def osc_unpack_act_scales(Xs, M, K):
+    """Row-block-major scale tensor -> plain uint8 [M, K/32]."""
+    out = torch.empty((M, K // 32), dtype=torch.uint8, device=Xs.device)
+    _check(lib().osc_unpack_act_scales(_ptr(Xs), M, K, _ptr(out), _stream()))
+    return out
+
+
 def osc_quantize_act(X, oidx=None, fmt=OSC_FMT_MXFP4_OSC, ldb=None, out=None):
-    """X bf16 [M, K] (device).  MXFP4_OSC -> (Xq uint8 [M,K/2], Xs uint8 [M,K/32], B uint16 [M,ldb]);
+    """X bf16 [M, K] (device).  MXFP4_OSC -> (Xq uint8 [M,K/2], Xs uint8 row-block-major scales,
+    B uint16 [M,ldb]);
     FP8_E4M3_TOKEN -> (X8 uint8 [M,K], xs float32 [M]).  `out` may hold preallocated outputs."""
     X = _rows16(X)
     M, K = X.shape
@@ -161,7 +175,7 @@ def osc_quantize_act(X, oidx=None, fmt=OSC_FMT_MXFP4_OSC, ldb=None, out=None):
         if ldb is None:
             ldb = (K_o + 63) // 64 * 64
         Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
-        Xs = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
+        Xs = torch.empty(osc_act_scale_bytes(M, K), dtype=torch.uint8, device=dev)
         B = torch.empty((M, ldb), dtype=torch.uint16, device=dev) if ldb else None
     _check(lib().osc_quantize_act(_ptr(X), M, K, X.stride(0), _ptr(oidx) if K_o else None, K_o, fmt,
                                   _ptr(Xq), _ptr(Xs), _ptr(B), ldb, _stream()))

@@ -10,7 +10,7 @@ SOURCES = ["api.hip", "quant.hip", "gemm.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", *([f"-D{d}" for d in __import__("os").environ.get("OSC_DEFINES","").split()]),
 ]
 
 

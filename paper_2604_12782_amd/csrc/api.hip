@@ -28,8 +28,9 @@ PackLayout pack_layout(int64_t N, int64_t K, int32_t K_o) {
     L.ldwl = ((int64_t)K_o + 63) / 64 * 64;
     L.off_q = 0;
     L.off_s = align_up((size_t)N * (size_t)(K / 2), 256);
-    L.off_l = align_up(L.off_s + (size_t)N * (size_t)(K / 32), 256);
-    L.total = align_up(L.off_l + (size_t)N * (size_t)L.ldwl * 2, 256);
+    L.off_l = align_up(L.off_s + scale_bytes(N, K), 256);
+    L.off_z = align_up(L.off_l + (size_t)N * (size_t)L.ldwl * 2, 256);
+    L.total = L.off_z + 256;
     return L;
 }
 
@@ -37,7 +38,8 @@ Pack8Layout pack8_layout(int64_t N, int64_t K) {
     Pack8Layout L;
     L.off_w = 0;
     L.off_s = align_up((size_t)N * (size_t)K, 256);
-    L.total = align_up(L.off_s + (size_t)N * 4, 256);
+    L.off_z = align_up(L.off_s + (size_t)N * 4, 256);
+    L.total = L.off_z + 256;
     return L;
 }
 
@@ -112,6 +114,8 @@ int osc_pack_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const int3
                                 base + L.off_s, nullptr, 0, as_stream(stream));
         if (rc) return rc;
     }
+    if (hipMemsetAsync(base + L.off_z, 0, 256, as_stream(stream)) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_pack_weight: cannot clear the zero block");
     return launch_gather_wl(static_cast<const uint16_t*>(W), N, K, ldw, oidx, K_o,
                             reinterpret_cast<uint16_t*>(base + L.off_l), L.ldwl, as_stream(stream));
 }
@@ -128,13 +132,27 @@ int osc_unpack_weight(const void* Wpack, int64_t N, int64_t K, int32_t K_o, uint
     if (Wq && K > 0 &&
         hipMemcpyAsync(Wq, base + L.off_q, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, st) != hipSuccess)
         return fail(OSC_ERR_HIP, "osc_unpack_weight: copy of codes failed");
-    if (Ws && K > 0 &&
-        hipMemcpyAsync(Ws, base + L.off_s, (size_t)N * (K / 32), hipMemcpyDeviceToDevice, st) != hipSuccess)
-        return fail(OSC_ERR_HIP, "osc_unpack_weight: copy of scales failed");
+    if (Ws && K > 0) {
+        rc = launch_scales_to_rowmajor(base + L.off_s, N, K, Ws, st);
+        if (rc) return rc;
+    }
     if (WL)
         return launch_unpack_wl(reinterpret_cast<const uint16_t*>(base + L.off_l), L.ldwl, N, K_o,
                                 static_cast<uint16_t*>(WL), st);
     return OSC_OK;
+}
+
+size_t osc_act_scale_bytes(int64_t M, int64_t K) {
+    if (M < 0 || K < 0 || K % 32) return 0;
+    return scale_bytes(M, K);
+}
+
+int osc_unpack_act_scales(const uint8_t* Xs, int64_t M, int64_t K, uint8_t* out, void* stream) {
+    int rc = check_mx_shape("osc_unpack_act_scales", M, K, K, 0);
+    if (rc) return rc;
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(Xs && out, OSC_ERR_NULL, "osc_unpack_act_scales: null pointer");
+    return launch_scales_to_rowmajor(Xs, M, K, out, as_stream(stream));
 }
 
 int osc_pack_weight_fp8(const void* W, int64_t N, int64_t K, int64_t ldw, void* W8pack, void* stream) {
@@ -148,6 +166,8 @@ int osc_pack_weight_fp8(const void* W, int64_t N, int64_t K, int64_t ldw, void* 
             "osc_pack_weight_fp8: W rows must be 16-byte aligned and W8pack 256-byte aligned");
     Pack8Layout L = pack8_layout(N, K);
     uint8_t* base = static_cast<uint8_t*>(W8pack);
+    if (hipMemsetAsync(base + L.off_z, 0, 256, as_stream(stream)) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_pack_weight_fp8: cannot clear the zero block");
     return launch_quant_fp8(static_cast<const uint16_t*>(W), N, K, ldw, base + L.off_w,
                             reinterpret_cast<float*>(base + L.off_s), as_stream(stream));
 }
@@ -189,7 +209,7 @@ int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int
     if (M == 0 || K == 0) return OSC_OK;
     REQUIRE(X && Xq && Xs, OSC_ERR_NULL, "osc_quantize_act: null pointer");
     REQUIRE(K_o == 0 || (oidx && B), OSC_ERR_NULL, "osc_quantize_act: K_o > 0 needs oidx and B");
-    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 4), OSC_ERR_UNSUPPORTED,
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 4) && aligned(Xs, 4), OSC_ERR_UNSUPPORTED,
             "osc_quantize_act: misaligned pointer or ldx %% 8 != 0");
     if (B) {
         REQUIRE(ldb >= 0, OSC_ERR_SHAPE, "osc_quantize_act: negative ldb");
@@ -221,8 +241,8 @@ static int dual_common(const char* who, const uint8_t* Xq, const uint8_t* Xs, co
     REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "%s: ldb=%lld < K_o=%d", who, (long long)ldb, K_o);
     if (M == 0 || N == 0) return OSC_OK;
     REQUIRE(Wpack && (K == 0 || (Xq && Xs)) && (K_o == 0 || B), OSC_ERR_NULL, "%s: null pointer", who);
-    REQUIRE(aligned(Xq, 16) && aligned(Wpack, 256) && (K / 2) % 16 == 0, OSC_ERR_UNSUPPORTED,
-            "%s: Xq must be 16-byte aligned, Wpack 256-byte aligned and K a multiple of 32", who);
+    REQUIRE(aligned(Xq, 16) && aligned(Xs, 4) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
+            "%s: Xq must be 16-byte aligned, Xs 4-byte aligned and Wpack 256-byte aligned", who);
     REQUIRE(K_o == 0 || (ldb % 8 == 0 && aligned(B, 16)), OSC_ERR_UNSUPPORTED,
             "%s: B must be 16-byte aligned with ldb %% 8 == 0", who);
     GemmProblem p{};

@@ -1,20 +1,33 @@
 // Dual-path GEMM (Section 3.3.1, Eq. dual-path) and FP8 W8A8 GEMM (Section 3.4) on the CDNA4
-// matrix cores, single and grouped (mixture-of-experts) forms.
+// matrix cores, single and grouped (mixture-of-experts) forms, one kernel template.
 //
-// One kernel skeleton serves all of them.  Every operand is seen as a row-major byte matrix
-// whose rows run along the reduction axis (FP4 codes: K/2 bytes per row, FP8 codes: K bytes,
-// bf16 branch: 2*K_o bytes); the reduction axis is consumed 128 bytes per row per step.
+// Operands.  Every operand is a row-major byte matrix whose rows run along the reduction axis
+// (FP4 codes: K/2 bytes per row, FP8 codes: K bytes, bf16 branch: 2*K_o bytes).  The reduction
+// axis is consumed 64 bytes per row per step: 128 FP4 channels = four scale groups = one scale
+// word of the row-block-major scale layout (see osc.h), 64 FP8 channels, or 32 bf16 channels.
 //
-// Matrix-core operand layout used (32x32 tiles, 64-lane wavefront, lane = 32*q + r):
+// Matrix-core operand layout (32x32 tiles, 64-lane wavefront, lane = 32*q + r):
 //   v_mfma_scale_f32_32x32x64_f8f6f4, FP4: lane holds row r, 32 consecutive elements (16 bytes) of
 //     reduction block q and, in one byte of its scale register picked by op_sel, their E8M0 scale.
+//     FP8: lane holds 32 bytes of block q; unit scales, row/column scales applied in the epilogue.
 //   v_mfma_f32_32x32x16_bf16: lane holds row r, 8 consecutive bf16 (16 bytes) of block q.
 //   Result register i of lane (q, r'): row 8*(i/4) + 4*q + i%4, column r'.
-// The hardware only pairs lane-block q of A with lane-block q of B, so the order in which the
-// reduction axis is dealt to (q, instruction) is free as long as both operands agree.  Here
-// the 128-byte step is split in two 64-byte halves, half q goes to lanes of block q, and the
-// i-th 16-byte piece of the half feeds the i-th of four MFMAs.  For FP4 the four scale bytes of
-// those pieces are then one aligned 32-bit word of the canonical [rows, K/32] scale matrix.
+// The hardware only pairs lane-block q of A with lane-block q of B, so how the reduction axis is
+// dealt to (q, instruction) is free as long as both operands agree.  Here lanes of block q take
+// bytes [32q, 32q+32) of the 64-byte step, i.e. 16-byte pieces 2q and 2q+1, and piece I feeds
+// MFMA I; the FP4 scale word is shifted right by 16q bits so that byte I is the scale of piece I.
+//
+// Data path.  global --16-byte loads--> registers --ds_write_b128--> LDS --ds_read_b128--> MFMA.
+// (The direct global->LDS path of gfx950 was measured at half the throughput of plain loads for
+// data that misses L2, and this kernel lives on L2 misses served by the Infinity Cache.)  Loads
+// for step s+2 are issued during step s and rest in registers for more than a step; they are
+// written to LDS late in step s+1, into one of three stages; one barrier per step.  Loads, LDS
+// writes and LDS reads are spread between the MFMAs of a step.  Rows past the end of an operand
+// and pieces past the end of a row are zero-filled in registers, so any legal shape runs here.
+#include <cstdio>
+#include <cstdlib>
+#include <type_traits>
+
 #include "osc_internal.h"
 
 namespace osc {
@@ -31,14 +44,14 @@ struct KArgs {
     const uint8_t* Xq;
     const uint8_t* Xs;
     const float* xs;
-    const uint16_t* B;
-    int64_t ldb;
+    const uint8_t* B;
+    int64_t bpitch;  // bytes per row of B
     const int32_t* row_map;
     const int32_t* off;
     int E;
     const uint8_t* Wpack;
-    size_t pack_stride, off_q, off_s, off_l;
-    int64_t ldwl;
+    size_t pack_stride, off_q, off_s, off_l, off_z;
+    int64_t wlpitch;  // bytes per row of W_L^T
     int M, N, K, K_o;
     void* Y;
     int y_bf16;
@@ -48,52 +61,51 @@ struct KArgs {
 
 // 16-byte piece `c` (0..7) of row `r` sits at piece c ^ swz(r): lanes of one LDS access
 // (consecutive rows, same piece) then spread over all banks.
-__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
-__device__ __forceinline__ int lds_off(int r, int c) { return r * 128 + ((c ^ swz(r)) << 4); }
-
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
 
-template <int MODE, int TM, int TN>
-__global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int SA = BM / 32, SB = BN / 32;  // 16-byte load slots per thread and step
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    uint8_t* sA = lds;
-    uint8_t* sB = lds + BM * 128;
 
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+struct TilePos {
+    int m0, n0, row_begin, row_end;
+    const uint8_t* wp;
+    bool valid;
+};
 
-    // ---- which tile -----------------------------------------------------------------
-    // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD owns a
-    // contiguous run of tiles and its L2 sees neighbouring tiles.
+// Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD owns a contiguous
+// run of tiles and its L2 sees neighbouring tiles.  Single problem: tiles walk down bands of 8
+// m-tiles.  Grouped: m-tiles are numbered expert by expert (the grid is an upper bound).
+template <int BM, int BN>
+__device__ __forceinline__ TilePos locate_tile(const KArgs& a) {
+    TilePos p;
     int tile = blockIdx.x;
     {
         const int per = gridDim.x >> 3;
         if (tile < (per << 3)) tile = (tile & 7) * per + (tile >> 3);
     }
-    int row_begin = 0, row_end = a.M, tm_idx, tn_idx;
-    const uint8_t* wp = a.Wpack;
-    if (a.off) {  // grouped: m-tiles are numbered expert by expert
+    p.row_begin = 0;
+    p.row_end = a.M;
+    p.wp = a.Wpack;
+    p.valid = true;
+    int tm_idx, tn_idx;
+    if (a.off) {
         tn_idx = tile % a.tiles_n;
         int j = tile / a.tiles_n, e = 0;
         for (; e < a.E; ++e) {
             const int b = a.off[e], n = a.off[e + 1] - b;
             const int te = (n + BM - 1) / BM;
             if (j < te) {
-                row_begin = b;
-                row_end = b + n;
+                p.row_begin = b;
+                p.row_end = b + n;
                 break;
             }
             j -= te;
         }
-        if (e == a.E) return;  // surplus workgroup of the upper-bound grid
+        if (e == a.E) p.valid = false;  // surplus workgroup
         tm_idx = j;
-        wp += (size_t)e * a.pack_stride;
+        p.wp += (size_t)e * a.pack_stride;
     } else {
         const int tiles_m = (a.M + BM - 1) / BM;
         const int band = tile / (8 * a.tiles_n), within = tile - band * 8 * a.tiles_n;
@@ -101,28 +113,189 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
         tm_idx = band * 8 + within % rows;
         tn_idx = within / rows;
     }
-    const int m0 = row_begin + tm_idx * BM, n0 = tn_idx * BN;
+    p.m0 = p.row_begin + tm_idx * BM;
+    p.n0 = tn_idx * BN;
+    return p;
+}
 
-    // ---- per-thread source rows for the global -> LDS copies ------------------------------
-    int arow[SA], brow[SB];
+template <int MODE, int TM, int TN>
+__device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, v16f (&acc)[TM][TN]) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
+    const uint8_t* wp = tp.wp;
+    // ---- epilogue ---------------------------------------------------------------------------
+    // Result register k of lane (q, r): row 8*(k/4) + 4*q + k%4, column r of its 32x32 tile.
+    // fp32: every register is one 128-byte row segment per half-wave.  bf16: neighbouring lanes
+    // swap one register of each pair so that every lane owns two adjacent columns of one row and
+    // writes them as one 32-bit word (even lanes row k, odd lanes row k+1).
+    const float* wsc = (MODE == MODE_FP8) ? reinterpret_cast<const float*>(wp + a.off_s) : nullptr;
+    const int odd = r & 1;
+    auto store_tile = [&](auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;  // tile entirely inside Y: no bounds tests
 #pragma unroll
-    for (int i = 0; i < SA; ++i) {
-        int g = min(m0 + ((t + GT * i) >> 3), row_end - 1);
-        arow[i] = (MODE == MODE_DUAL && a.row_map) ? a.row_map[g] : g;
+        for (int i = 0; i < TM; ++i) {
+            const int rbase = m0 + wm * (TM * 32) + i * 32 + 4 * q;
+            float xr[16];
+            if (MODE == MODE_FP8) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int row = rbase + 8 * (k >> 2) + (k & 3);
+                    xr[k] = a.xs[FULL ? row : min(row, row_end - 1)];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (TN * 32) + j * 32 + r;
+                float cs = 1.0f;
+                if (MODE == MODE_FP8) cs = wsc[FULL ? col : min(col, a.N - 1)];
+                float v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k)
+                    v[k] = (MODE == MODE_FP8) ? acc[i][j][k] * (xr[k] * cs) : acc[i][j][k];
+                if (a.y_bf16) {
+                    uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
+#pragma unroll
+                    for (int k = 0; k < 16; k += 2) {
+                        const float send = odd ? v[k] : v[k + 1];
+                        // neighbour lane's value: DPP quad_perm [1,0,3,2]
+                        const float recv = __builtin_bit_cast(
+                            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));
+                        const float lo = odd ? recv : v[k], hi = odd ? v[k + 1] : recv;
+                        const int row = rbase + 8 * (k >> 2) + (k & 3) + odd;
+                        const int c0 = col - odd;
+                        uint16_t* dst = Y + (int64_t)row * a.ldy + c0;
+                        const uint32_t word =
+                            (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+                        if (FULL) {
+                            *reinterpret_cast<uint32_t*>(dst) = word;
+                        } else if (row < row_end) {
+                            if (c0 < a.N) dst[0] = (uint16_t)word;
+                            if (c0 + 1 < a.N) dst[1] = (uint16_t)(word >> 16);
+                        }
+                    }
+                } else {
+                    float* Y = reinterpret_cast<float*>(a.Y);
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int row = rbase + 8 * (k >> 2) + (k & 3);
+                        if (FULL || (row < row_end && col < a.N)) Y[(int64_t)row * a.ldy + col] = v[k];
+                    }
+                }
+            }
+        }
+    };
+    // 32-bit stores of bf16 pairs need an even leading dimension and a 4-byte aligned Y
+    const bool full = (m0 + BM <= row_end) && (n0 + BN <= a.N) &&
+                      (!a.y_bf16 || (((a.ldy & 1) == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 3) == 0)));
+    if (full)
+        store_tile(std::true_type{});
+    else
+        store_tile(std::false_type{});
+}
+
+// ------------------------------------------------------------------------------------------
+// Ring kernel.  Per step every row contributes 64 contiguous bytes (FP4: 128 channels = four
+// scale groups = one scale word; FP8: 64 channels; bf16: 32 channels).  Lanes of block q take
+// bytes [32q, 32q+32) of the step, i.e. 16-byte pieces 2q and 2q+1; piece I feeds MFMA I.  The
+// FP4 scale word is shifted right by 16q bits so that byte I is again the scale of piece I.
+//
+// LDS holds four stages of (BM + BN) rows x 64 bytes.  In step s a workgroup computes from stage
+// s % 4 and refills stage (s+3) % 4, which every wave left before the barrier that ended step
+// s-1, with the operands of step s+3.  Those loads are spread between the MFMAs of the step (a
+// wave that issued them in one burst would sit in the memory queue instead of feeding the matrix
+// core).  The barrier that ends step s first waits for the loads issued during step s-1, so the
+// operands of step s+2 are published there; a load has between one and two steps to land.
+// ------------------------------------------------------------------------------------------
+
+// piece `c` (0..3) of stage row `r` sits at piece position c ^ ((r >> 2) & 3): the 16 lanes of one
+// LDS access phase (consecutive rows, same piece) then cover all 64 banks
+__device__ __forceinline__ int ring_off(int row, int piece) {
+    return row * 64 + ((piece ^ ((row >> 2) & 3)) << 4);
+}
+
+// Scheduling hint for one half step: ND LDS reads, NW LDS writes and NV VMEM operations spread
+// evenly between NM MFMAs (the compiler would otherwise bunch them).
+template <int NM, int ND, int NW, int NV, int K = 0>
+__device__ __forceinline__ void spread_hint() {
+    constexpr int G = (ND > NW ? ND : NW) > 0 ? (ND > NW ? ND : NW) : 1;
+    if constexpr (K < G) {
+        constexpr int m = NM / G + (K < NM % G ? 1 : 0);
+        constexpr int d = ND / G + (K < ND % G ? 1 : 0);
+        constexpr int w = NW / G + (K < NW % G ? 1 : 0);
+        constexpr int v = NV / G + (K < NV % G ? 1 : 0);
+        if constexpr (m > 0) __builtin_amdgcn_sched_group_barrier(0x008, m, 0);
+        if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
+        if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+        spread_hint<NM, ND, NW, NV, K + 1>();
+    }
+}
+
+// RAGGED = false needs every operand row to be a whole number of 64-byte steps; RAGGED = true
+// redirects, lane by lane, the pieces past the end of a row to a block of zeros in the packed
+// weight (address arithmetic only: nothing may depend on a loaded value before it is used, or
+// the compiler waits for the load right after issuing it).
+template <int MODE, int TM, int TN, bool RAGGED>
+__global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int STG = (BM + BN) * 64;        // bytes per LDS stage
+    constexpr int LA = BM / 64, LB = BN / 64;  // 16-byte loads per thread and step
+    constexpr int NSC = (MODE == MODE_DUAL) ? TM + TN : 0;  // scale words per lane and step
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const TilePos tp = locate_tile<BM, BN>(a);
+    if (!tp.valid) return;
+    const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
+    const uint8_t* wp = tp.wp;
+
+    const int Kg4 = ((a.K >> 5) + 3) >> 2;
+    const int rowbytes = (MODE == MODE_DUAL) ? (a.K >> 1) : a.K;
+    const int nA = (rowbytes + 63) >> 6;                                  // steps of the main phase
+    const int nB = (MODE == MODE_DUAL) ? ((a.K_o * 2 + 63) >> 6) : 0;     // steps of the bf16 branch
+    const int nS = nA + nB;
+    const int validB_a = (int)a.bpitch, validB_b = (int)a.wlpitch;  // bytes per row in the bf16 phase
+
+    // ---- global -> registers: thread t owns stage position (row (t >> 2) + 64 i, piece t & 3) ----
+    const int c4 = (t & 3) ^ ((t >> 4) & 3);  // reduction-axis piece stored at that position
+    // 32-bit byte offsets of this thread's piece in each operand (the launcher checks that they fit)
+    uint32_t oa[LA], ob[LB], oa2[LA], ob2[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        int g = min(m0 + (t >> 2) + 64 * i, row_end - 1);
+        if (MODE == MODE_DUAL && a.row_map) g = a.row_map[g];
+        oa[i] = (uint32_t)g * (uint32_t)rowbytes + c4 * 16;
+        oa2[i] = (uint32_t)g * (uint32_t)a.bpitch + c4 * 16;
     }
 #pragma unroll
-    for (int i = 0; i < SB; ++i) brow[i] = min(n0 + ((t + GT * i) >> 3), a.N - 1);
-    const int c8 = t & 7;
-
-    // rows whose fragments this lane feeds to the matrix cores
-    int frow_a[TM], frow_b[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        int g = min(m0 + wm * (TM * 32) + i * 32 + r, row_end - 1);
-        frow_a[i] = (MODE == MODE_DUAL && a.row_map) ? a.row_map[g] : g;
+    for (int i = 0; i < LB; ++i) {
+        const int n = min(n0 + (t >> 2) + 64 * i, a.N - 1);
+        ob[i] = (uint32_t)n * (uint32_t)rowbytes + c4 * 16;
+        ob2[i] = (uint32_t)n * (uint32_t)a.wlpitch + c4 * 16;
     }
+    const uint8_t* wq = wp + a.off_q;
+    const uint8_t* wl = wp + a.off_l;
+    const uint8_t* zeros = wp + a.off_z;  // 256 bytes of zeros at the end of every packed weight
+
+    // ---- scale words: one per (row, step) -----------------------------------------------------
+    uint32_t so_a[TM], so_b[TN];
+    if (MODE == MODE_DUAL) {
 #pragma unroll
-    for (int i = 0; i < TN; ++i) frow_b[i] = min(n0 + wn * (TN * 32) + i * 32 + r, a.N - 1);
+        for (int i = 0; i < TM; ++i) {
+            int g = min(m0 + wm * (TM * 32) + i * 32 + r, row_end - 1);
+            if (a.row_map) g = a.row_map[g];
+            so_a[i] = (uint32_t)(g >> 5) * (uint32_t)Kg4 * 128u + (g & 31) * 4;
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int n = min(n0 + wn * (TN * 32) + i * 32 + r, a.N - 1);
+            so_b[i] = (uint32_t)(n >> 5) * (uint32_t)Kg4 * 128u + (n & 31) * 4;
+        }
+    }
+    const uint8_t* wsb = wp + a.off_s;
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -132,194 +305,460 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
 #pragma unroll
             for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
 
-    u32x4 ra[SA], rb[SB];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const int ra0 = wm * (TM * 32) + r, rb0 = BM + wn * (TN * 32) + r;  // stage rows of tile 0
 
-    auto gload = [&](const uint8_t* abase, int64_t apitch, int64_t avalid, const uint8_t* bbase,
-                     int64_t bpitch, int64_t bvalid, int T) {
-        const int64_t o = (int64_t)T * 128 + c8 * 16;
-#pragma unroll
-        for (int i = 0; i < SA; ++i)
-            ra[i] = (o < avalid) ? *reinterpret_cast<const u32x4*>(abase + arow[i] * apitch + o) : zero4;
-#pragma unroll
-        for (int i = 0; i < SB; ++i)
-            rb[i] = (o < bvalid) ? *reinterpret_cast<const u32x4*>(bbase + brow[i] * bpitch + o) : zero4;
-    };
-    auto lstore = [&]() {
-#pragma unroll
-        for (int i = 0; i < SA; ++i)
-            *reinterpret_cast<u32x4*>(sA + lds_off((t + GT * i) >> 3, c8)) = ra[i];
-#pragma unroll
-        for (int i = 0; i < SB; ++i)
-            *reinterpret_cast<u32x4*>(sB + lds_off((t + GT * i) >> 3, c8)) = rb[i];
-    };
-    auto frag = [&](const uint8_t* s, int row, int piece) {
-        return *reinterpret_cast<const u32x4*>(s + lds_off(row, piece));
-    };
-
-    if (MODE == MODE_DUAL) {
-        // ---- Path A: block-scaled FP4 ------------------------------------------------------
-        const int Kg = a.K >> 5;
-        const int64_t rowbytes = a.K >> 1;
-        const int nA = (int)((rowbytes + 127) >> 7);
-        const uint8_t* wq = wp + a.off_q;
-        const uint8_t* ws = wp + a.off_s;
-        const bool word_ok = (Kg & 3) == 0;
-        auto scale_word = [&](const uint8_t* base, int row, int T) -> int {
-            const int g0 = 8 * T + 4 * q;
-            const uint8_t* p = base + (int64_t)row * Kg + g0;
-            if (word_ok && g0 + 4 <= Kg) return *reinterpret_cast<const int*>(p);
-            int v = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (g0 + k < Kg) v |= (int)p[k] << (8 * k);
-            return v;
-        };
-        int sa_n[TM], sb_n[TN];
-        gload(a.Xq, rowbytes, rowbytes, wq, rowbytes, rowbytes, 0);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) sa_n[i] = scale_word(a.Xs, frow_a[i], 0);
-#pragma unroll
-        for (int i = 0; i < TN; ++i) sb_n[i] = scale_word(ws, frow_b[i], 0);
-        for (int T = 0; T < nA; ++T) {
-            int sa[TM], sb[TN];
-            __syncthreads();
-            lstore();
-#pragma unroll
-            for (int i = 0; i < TM; ++i) sa[i] = sa_n[i];
-#pragma unroll
-            for (int i = 0; i < TN; ++i) sb[i] = sb_n[i];
-            __syncthreads();
-            if (T + 1 < nA) {
-                gload(a.Xq, rowbytes, rowbytes, wq, rowbytes, rowbytes, T + 1);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) sa_n[i] = scale_word(a.Xs, frow_a[i], T + 1);
-#pragma unroll
-                for (int i = 0; i < TN; ++i) sb_n[i] = scale_word(ws, frow_b[i], T + 1);
-            }
-#define OSC_FP4_STEP(I)                                                                          \
-    {                                                                                            \
-        u32x4 fa[TM], fb[TN];                                                                    \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[i] =                                   \
-            frag(sA, wm * (TM * 32) + i * 32 + r, 4 * q + I);                                    \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[j] =                                   \
-            frag(sB, wn * (TN * 32) + j * 32 + r, 4 * q + I);                                    \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
-            const v8i av = {(int)fa[i].x, (int)fa[i].y, (int)fa[i].z, (int)fa[i].w, 0, 0, 0, 0}; \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                     \
-                const v8i bv = {(int)fb[j].x, (int)fb[j].y, (int)fb[j].z, (int)fb[j].w,          \
-                                0,            0,            0,            0};                    \
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                     \
-                    av, bv, acc[i][j], 4, 4, I, sa[i], I, sb[j]);                                \
-            }                                                                                    \
-        }                                                                                        \
+    // Macros rather than closures: the compiler keeps arrays that closures capture, when those
+    // closures are expanded in several loops, in scratch memory.
+    //
+    // Operands of step T_ of a phase into a register set.  A step past the end of the phase
+    // re-reads the last one (the data is never used); with RAGGED, pieces past the end of a row
+    // come from the block of zeros.
+#define OSC_LOAD(T_, NSTEP_, ABASE_, BBASE_, OA_, OB_, AVALID_, BVALID_, RA_, RB_)                   \
+    {                                                                                                \
+        const int T__ = min((T_), (NSTEP_)-1);                                                       \
+        const uint8_t* ab__ = (ABASE_) + T__ * 64;                                                   \
+        const uint8_t* bb__ = (BBASE_) + T__ * 64;                                                   \
+        if (RAGGED) {                                                                                \
+            const bool ina__ = T__ * 64 + c4 * 16 < (AVALID_), inb__ = T__ * 64 + c4 * 16 < (BVALID_); \
+            _Pragma("unroll") for (int i = 0; i < LA; ++i) RA_[i] =                                  \
+                *reinterpret_cast<const u32x4*>(ina__ ? ab__ + OA_[i] : zeros);                      \
+            _Pragma("unroll") for (int i = 0; i < LB; ++i) RB_[i] =                                  \
+                *reinterpret_cast<const u32x4*>(inb__ ? bb__ + OB_[i] : zeros);                      \
+        } else {                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < LA; ++i) RA_[i] =                                  \
+                *reinterpret_cast<const u32x4*>(ab__ + OA_[i]);                                      \
+            _Pragma("unroll") for (int i = 0; i < LB; ++i) RB_[i] =                                  \
+                *reinterpret_cast<const u32x4*>(bb__ + OB_[i]);                                      \
+        }                                                                                            \
     }
-            OSC_FP4_STEP(0)
-            OSC_FP4_STEP(1)
-            OSC_FP4_STEP(2)
-            OSC_FP4_STEP(3)
-#undef OSC_FP4_STEP
+#define OSC_LOAD_MAIN(T_, RA_, RB_) OSC_LOAD(T_, nA, a.Xq, wq, oa, ob, rowbytes, rowbytes, RA_, RB_)
+#define OSC_LOAD_BRANCH(T_, RA_, RB_) OSC_LOAD(T_, nB, a.B, wl, oa2, ob2, validB_a, validB_b, RA_, RB_)
+    // step S_ of the whole sequence (main phase, then bf16 branch); nothing to load past its end
+#define OSC_LOAD_ANY(S_, RA_, RB_)                 \
+    {                                              \
+        if ((S_) < nA) {                           \
+            OSC_LOAD_MAIN((S_), RA_, RB_)          \
+        } else if ((S_) < nS) {                    \
+            OSC_LOAD_BRANCH((S_)-nA, RA_, RB_)     \
+        }                                          \
+    }
+    // a register set into LDS stage STG_
+#define OSC_PUT(STG_, RA_, RB_)                                                                       \
+    {                                                                                                 \
+        uint8_t* st__ = lds + (STG_)*STG + t * 16;                                                    \
+        _Pragma("unroll") for (int i = 0; i < LA; ++i) *reinterpret_cast<u32x4*>(st__ + i * 4096) = RA_[i]; \
+        _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                \
+            *reinterpret_cast<u32x4*>(st__ + BM * 64 + i * 4096) = RB_[i];                            \
+    }
+    // fragments of piece P_ from stage STG_
+#define OSC_FRAGS(STG_, P_, FA_, FB_)                                                                 \
+    {                                                                                                 \
+        const uint8_t* st__ = lds + (STG_)*STG;                                                       \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) FA_[i] =                                       \
+            *reinterpret_cast<const u32x4*>(st__ + ring_off(ra0 + 32 * i, (P_)));                     \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) FB_[j] =                                       \
+            *reinterpret_cast<const u32x4*>(st__ + ring_off(rb0 + 32 * j, (P_)));                     \
+    }
+    // scale words of step T_ (a step past the end re-reads the last one and is never used; the
+    // scale bytes of groups past K/32 inside the last word are zero by layout)
+#define OSC_SCALES(T_, SA_, SB_)                                                                      \
+    {                                                                                                 \
+        const uint32_t o__ = (uint32_t)min((T_), Kg4 - 1) * 128u;                                     \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) SA_[i] =                                       \
+            *reinterpret_cast<const int*>(a.Xs + o__ + so_a[i]);                                      \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i) SB_[i] =                                       \
+            *reinterpret_cast<const int*>(wsb + o__ + so_b[i]);                                       \
+    }
+#define OSC_MFMA_FP4(I_, FA_, FB_, SA_, SB_)                                                          \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                              \
+            const v8i av__ = {(int)FA_[i].x, (int)FA_[i].y, (int)FA_[i].z, (int)FA_[i].w, 0, 0, 0, 0}; \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                          \
+                const v8i bv__ = {(int)FB_[j].x, (int)FB_[j].y, (int)FB_[j].z, (int)FB_[j].w, 0, 0, 0, 0}; \
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i][j], 4, 4, I_, \
+                                                                            SA_[i], I_, SB_[j]);      \
+            }                                                                                         \
+        }                                                                                             \
+    }
+#define OSC_MFMA_BF16(FA_, FB_)                                                                       \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) acc[i][j] =                                \
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, FA_[i]),             \
+                                                        __builtin_bit_cast(v8bf, FB_[j]), acc[i][j], 0, 0, 0); \
+    }
+    // FP8: one MFMA per tile pair and step; tile pairs [LO_, HI_)
+#define OSC_MFMA_FP8(LO_, HI_, FA_, GA_, FB_, GB_)                                                    \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                              \
+            const v8i av__ = {(int)FA_[i].x, (int)FA_[i].y, (int)FA_[i].z, (int)FA_[i].w,             \
+                              (int)GA_[i].x, (int)GA_[i].y, (int)GA_[i].z, (int)GA_[i].w};            \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                          \
+                if (i * TN + j < (LO_) || i * TN + j >= (HI_)) continue;                              \
+                const v8i bv__ = {(int)FB_[j].x, (int)FB_[j].y, (int)FB_[j].z, (int)FB_[j].w,         \
+                                  (int)GB_[j].x, (int)GB_[j].y, (int)GB_[j].z, (int)GB_[j].w};        \
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i][j], 0, 0, 0, \
+                                                                            0x7f7f7f7f, 0, 0x7f7f7f7f); \
+            }                                                                                         \
+        }                                                                                             \
+    }
+
+    // ---- prologue: step 0 in LDS, step 1 in registers ------------------------------------------
+    // Two register sets hold operands in flight.  At the top of a step, set W holds the operands
+    // of the next step (written to LDS during this step) and set L is free (receives the loads of
+    // the step after the next).
+    u32x4 ra0s[LA], rb0s[LB], ra1s[LA], rb1s[LB];
+    int sn_a[TM], sn_b[TN];
+    OSC_LOAD_ANY(0, ra0s, rb0s)
+    OSC_LOAD_ANY(1, ra1s, rb1s)
+    if (MODE == MODE_DUAL && nA > 0) OSC_SCALES(0, sn_a, sn_b)
+    OSC_PUT(0, ra0s, rb0s)
+    __syncthreads();
+    int stg = 0;  // stage of the current step; the next one is (stg + 1) % 3
+
+#define OSC_NEXT_STAGE (stg == 2 ? 0 : stg + 1)
+    // One step of the FP4 phase.  LOADER_(step, set) fetches the operands two steps ahead into set
+    // L; set W goes to the next LDS stage.
+#define OSC_STEP_FP4(S_, LOADER_, RLA_, RLB_, RWA_, RWB_)                              \
+    {                                                                                  \
+        u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                      \
+        int sa[TM], sb[TN];                                                            \
+        OSC_FRAGS(stg, 2 * q, fa0, fb0)                                                \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) sa[i] = (unsigned)sn_a[i] >> (16 * q); \
+        _Pragma("unroll") for (int i = 0; i < TN; ++i) sb[i] = (unsigned)sn_b[i] >> (16 * q); \
+        OSC_SCALES((S_) + 1, sn_a, sn_b)                                               \
+        LOADER_((S_) + 2, RLA_, RLB_)                                                  \
+        OSC_FRAGS(stg, 2 * q + 1, fa1, fb1)                                            \
+        OSC_MFMA_FP4(0, fa0, fb0, sa, sb)                                              \
+        spread_hint<TM * TN, TM + TN, 0, NSC + LA + LB>();                             \
+        OSC_PUT(OSC_NEXT_STAGE, RWA_, RWB_)                                            \
+        OSC_MFMA_FP4(1, fa1, fb1, sa, sb)                                              \
+        spread_hint<TM * TN, 0, LA + LB, 0>();                                         \
+        __syncthreads();                                                               \
+        stg = OSC_NEXT_STAGE;                                                          \
+    }
+#define OSC_STEP_BF16(S_, RLA_, RLB_, RWA_, RWB_)                                      \
+    {                                                                                  \
+        u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                      \
+        OSC_FRAGS(stg, 2 * q, fa0, fb0)                                                \
+        OSC_LOAD_BRANCH((S_) + 2 - nA, RLA_, RLB_)                                     \
+        OSC_FRAGS(stg, 2 * q + 1, fa1, fb1)                                            \
+        OSC_MFMA_BF16(fa0, fb0)                                                        \
+        spread_hint<TM * TN, TM + TN, 0, LA + LB>();                                   \
+        OSC_PUT(OSC_NEXT_STAGE, RWA_, RWB_)                                            \
+        OSC_MFMA_BF16(fa1, fb1)                                                        \
+        spread_hint<TM * TN, 0, LA + LB, 0>();                                         \
+        __syncthreads();                                                               \
+        stg = OSC_NEXT_STAGE;                                                          \
+    }
+#define OSC_STEP_FP8(S_, RLA_, RLB_, RWA_, RWB_)                                       \
+    {                                                                                  \
+        u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];                                      \
+        OSC_FRAGS(stg, 2 * q, fa0, fb0)                                                \
+        OSC_FRAGS(stg, 2 * q + 1, fa1, fb1)                                            \
+        OSC_LOAD_MAIN((S_) + 2, RLA_, RLB_)                                            \
+        OSC_MFMA_FP8(0, (TM * TN) / 2, fa0, fa1, fb0, fb1)                             \
+        spread_hint<(TM * TN) / 2, 0, 0, LA + LB>();                                   \
+        OSC_PUT(OSC_NEXT_STAGE, RWA_, RWB_)                                            \
+        OSC_MFMA_FP8((TM * TN) / 2, TM * TN, fa0, fa1, fb0, fb1)                       \
+        spread_hint<TM * TN - (TM * TN) / 2, 0, LA + LB, 0>();                         \
+        __syncthreads();                                                               \
+        stg = OSC_NEXT_STAGE;                                                          \
+    }
+    // after an odd step the roles of the two sets are swapped: move the live one back to set 1
+#define OSC_RESET_SETS                                                       \
+    {                                                                        \
+        _Pragma("unroll") for (int i = 0; i < LA; ++i) ra1s[i] = ra0s[i];    \
+        _Pragma("unroll") for (int i = 0; i < LB; ++i) rb1s[i] = rb0s[i];    \
+    }
+
+    // Two steps per trip so that the register sets alternate statically.
+    if (MODE == MODE_FP8) {
+        int s = 0;
+#pragma unroll 1
+        for (; s + 1 < nA; s += 2) {
+            OSC_STEP_FP8(s, ra0s, rb0s, ra1s, rb1s)
+            OSC_STEP_FP8(s + 1, ra1s, rb1s, ra0s, rb0s)
         }
-        // ---- Path B: bf16 branch into the same accumulators --------------------------------
-        if (a.K_o > 0) {
-            const uint8_t* bsrc = reinterpret_cast<const uint8_t*>(a.B);
-            const uint8_t* wl = wp + a.off_l;
-            const int64_t ab = a.ldb * 2, wb = a.ldwl * 2;
-            const int nB = (int)(((int64_t)a.K_o * 2 + 127) >> 7);
-            gload(bsrc, ab, ab, wl, wb, wb, 0);
-            for (int T = 0; T < nB; ++T) {
-                __syncthreads();
-                lstore();
-                __syncthreads();
-                if (T + 1 < nB) gload(bsrc, ab, ab, wl, wb, wb, T + 1);
-#pragma unroll
-                for (int I = 0; I < 4; ++I) {
-                    u32x4 fa[TM], fb[TN];
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) fa[i] = frag(sA, wm * (TM * 32) + i * 32 + r, 4 * q + I);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[j] = frag(sB, wn * (TN * 32) + j * 32 + r, 4 * q + I);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(v8bf, fa[i]), __builtin_bit_cast(v8bf, fb[j]),
-                                acc[i][j], 0, 0, 0);
-                }
-            }
-        }
+        if (s < nA) OSC_STEP_FP8(s, ra0s, rb0s, ra1s, rb1s)
     } else {
-        // ---- FP8: e4m3 x e4m3, unit block scales; row/column scales applied at the end -------
-        const int64_t rowbytes = a.K;
-        const int nA = (int)((rowbytes + 127) >> 7);
-        const uint8_t* w8 = wp + a.off_q;
-        gload(a.Xq, rowbytes, rowbytes, w8, rowbytes, rowbytes, 0);
-        for (int T = 0; T < nA; ++T) {
-            __syncthreads();
-            lstore();
-            __syncthreads();
-            if (T + 1 < nA) gload(a.Xq, rowbytes, rowbytes, w8, rowbytes, rowbytes, T + 1);
-#pragma unroll
-            for (int I = 0; I < 2; ++I) {
-                v8i fa[TM], fb[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    u32x4 lo = frag(sA, wm * (TM * 32) + i * 32 + r, 4 * q + 2 * I);
-                    u32x4 hi = frag(sA, wm * (TM * 32) + i * 32 + r, 4 * q + 2 * I + 1);
-                    fa[i] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w,
-                                  (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    u32x4 lo = frag(sB, wn * (TN * 32) + j * 32 + r, 4 * q + 2 * I);
-                    u32x4 hi = frag(sB, wn * (TN * 32) + j * 32 + r, 4 * q + 2 * I + 1);
-                    fb[j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w,
-                                  (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fa[i], fb[j], acc[i][j], 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-            }
+        int s = 0;
+        // Path A: block-scaled FP4.  Its last two steps already load the bf16 branch.
+#pragma unroll 1
+        for (; s + 3 < nA; s += 2) {
+            OSC_STEP_FP4(s, OSC_LOAD_MAIN, ra0s, rb0s, ra1s, rb1s)
+            OSC_STEP_FP4(s + 1, OSC_LOAD_MAIN, ra1s, rb1s, ra0s, rb0s)
         }
-    }
-
-    // ---- epilogue ---------------------------------------------------------------------------
-    const float* wsc = (MODE == MODE_FP8) ? reinterpret_cast<const float*>(wp + a.off_s) : nullptr;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (TN * 32) + j * 32 + r;
-            float cs = 1.0f;
-            if (MODE == MODE_FP8 && col < a.N) cs = wsc[col];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int row = m0 + wm * (TM * 32) + i * 32 + 8 * (k >> 2) + 4 * q + (k & 3);
-                if (row < row_end && col < a.N) {
-                    float v = acc[i][j][k];
-                    if (MODE == MODE_FP8) v *= a.xs[row] * cs;
-                    if (a.y_bf16)
-                        reinterpret_cast<uint16_t*>(a.Y)[(int64_t)row * a.ldy + col] = f32_to_bf16_rne(v);
-                    else
-                        reinterpret_cast<float*>(a.Y)[(int64_t)row * a.ldy + col] = v;
-                }
-            }
+        if (s + 2 < nA) {  // odd remainder: one more step that still loads the main phase
+            OSC_STEP_FP4(s, OSC_LOAD_MAIN, ra0s, rb0s, ra1s, rb1s)
+            OSC_RESET_SETS
+            ++s;
         }
+        if (s + 1 < nA) {
+            OSC_STEP_FP4(s, OSC_LOAD_ANY, ra0s, rb0s, ra1s, rb1s)
+            OSC_STEP_FP4(s + 1, OSC_LOAD_ANY, ra1s, rb1s, ra0s, rb0s)
+            s += 2;
+        } else if (s < nA) {
+            OSC_STEP_FP4(s, OSC_LOAD_ANY, ra0s, rb0s, ra1s, rb1s)
+            OSC_RESET_SETS
+            ++s;
+        }
+        // Path B: bf16 branch into the same accumulators
+#pragma unroll 1
+        for (; s + 1 < nS; s += 2) {
+            OSC_STEP_BF16(s, ra0s, rb0s, ra1s, rb1s)
+            OSC_STEP_BF16(s + 1, ra1s, rb1s, ra0s, rb0s)
+        }
+        if (s < nS) OSC_STEP_BF16(s, ra0s, rb0s, ra1s, rb1s)
     }
+    store_result<MODE, TM, TN>(a, tp, acc);
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+__device__ __forceinline__ void load_to_lds16(const uint8_t* src, uint8_t* lds_wave_base) {
+    // each lane's 16 bytes land at lds_wave_base + 16 * lane
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------
+// DMA variant with full cache lines: every row contributes 128 contiguous bytes per stage (one
+// DMA instruction then covers 8 rows x 128 bytes; with 64-byte row segments the DMA path was
+// measured at half the L2 throughput).  Two LDS stages of (BM + BN) rows x 128 bytes.  A stage is
+// consumed as two 64-byte half steps, laid out as in the other kernels (lanes of block q take
+// pieces 2q and 2q+1 of the half step).  The loads of the next stage are spread between the
+// MFMAs of the first three quarters of the current one; the stage ends with "all loads landed"
+// and one barrier.  Needs operand rows that are whole 128-byte stages.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int swz8(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+__device__ __forceinline__ int st128_off(int row, int piece) { return row * 128 + ((piece ^ swz8(row)) << 4); }
+
 template <int MODE, int TM, int TN>
-static int launch_cfg(const KArgs& a, int tiles_m, hipStream_t st) {
+__global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    const size_t smem = (size_t)(BM + BN) * 128;
-    const int64_t grid = (int64_t)tiles_m * a.tiles_n;
+    constexpr int STG = (BM + BN) * 128;
+    constexpr int LA = BM / 32, LB = BN / 32;  // DMA loads per thread and stage
+    constexpr int NBLK = (BM + BN) / 32;      // 32-row blocks of a stage
+    constexpr int NSB = NBLK / 4;              // scale DMA loads per wave and stage (one block each)
+    constexpr int SCL = NBLK * 256;            // bytes of scale words per stage: [block][half step][32 rows][4]
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint8_t* const scl = lds + 2 * STG;        // scale words of the two stages
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const TilePos tp = locate_tile<BM, BN>(a);
+    if (!tp.valid) return;
+    const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
+    const uint8_t* wp = tp.wp;
+
+    const int Kg4 = ((a.K >> 5) + 3) >> 2;
+    const int rowbytes = (MODE == MODE_DUAL) ? (a.K >> 1) : a.K;
+    const int nTA = rowbytes >> 7;                                       // stages of the main phase
+    const int nTB = (MODE == MODE_DUAL) ? ((a.K_o * 2 + 127) >> 7) : 0;  // stages of the bf16 branch
+    const int nT = nTA + nTB;
+
+    // thread t fills stage position (row (t >> 3) + 32 i, piece position t & 7)
+    const int c8 = (t & 7) ^ swz8(t >> 3);
+    uint32_t oa[LA], ob[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        int g = min(m0 + (t >> 3) + 32 * i, row_end - 1);
+        if (MODE == MODE_DUAL && a.row_map) g = a.row_map[g];
+        oa[i] = (uint32_t)g;
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) ob[i] = (uint32_t)min(n0 + (t >> 3) + 32 * i, a.N - 1);
+    const uint8_t* wq = wp + a.off_q;
+    const uint8_t* wl = wp + a.off_l;
+    // Scale words travel through LDS as well (a register load in the loop would make the compiler
+    // wait for "all vector memory", which includes the DMA loads just issued).  Wave w moves blocks
+    // w*NSB .. w*NSB+NSB-1: lanes 0-31 fetch the word of the first half step of their row, lanes
+    // 32-63 that of the second.
+    uint32_t sco[NSB];
+    if (MODE == MODE_DUAL) {
+#pragma unroll
+        for (int k = 0; k < NSB; ++k) {
+            const int b = wave * NSB + k;
+            int g;
+            if (b < BM / 32) {
+                g = min(m0 + 32 * b + r, row_end - 1);
+                if (a.row_map) g = a.row_map[g];
+            } else {
+                g = min(n0 + 32 * (b - BM / 32) + r, a.N - 1);
+            }
+            sco[k] = (uint32_t)(g >> 5) * (uint32_t)Kg4 * 128u + (g & 31) * 4 + q * 128;
+        }
+    }
+    const uint8_t* wsb = wp + a.off_s;
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
+    const int ra0 = wm * (TM * 32) + r, rb0 = BM + wn * (TN * 32) + r;
+
+    // loads [LO_, HI_) of the A rows and of the B rows of stage T_ of a phase into LDS buffer BUF_
+#define OSC_D2(T_, ABASE_, APITCH_, BBASE_, BPITCH_, BUF_, ALO_, AHI_, BLO_, BHI_)                   \
+    {                                                                                                \
+        uint8_t* st__ = lds + (BUF_)*STG + wave * 1024;                                              \
+        const uint32_t o__ = (uint32_t)(T_)*128u + c8 * 16;                                          \
+        _Pragma("unroll") for (int i = (ALO_); i < (AHI_); ++i)                                      \
+            load_to_lds16((ABASE_) + (oa[i] * (uint32_t)(APITCH_) + o__), st__ + i * 4096);          \
+        _Pragma("unroll") for (int i = (BLO_); i < (BHI_); ++i)                                      \
+            load_to_lds16((BBASE_) + (ob[i] * (uint32_t)(BPITCH_) + o__), st__ + BM * 128 + i * 4096); \
+    }
+    // stage S_ of the whole sequence (main phase, then bf16 branch); nothing past the end
+#define OSC_D2_ANY(S_, BUF_, ALO_, AHI_, BLO_, BHI_)                                                  \
+    {                                                                                                 \
+        if ((S_) < nTA) {                                                                             \
+            OSC_D2((S_), a.Xq, rowbytes, wq, rowbytes, BUF_, ALO_, AHI_, BLO_, BHI_)                  \
+        } else if ((S_) < nT) {                                                                       \
+            OSC_D2((S_)-nTA, a.B, a.bpitch, wl, a.wlpitch, BUF_, ALO_, AHI_, BLO_, BHI_)              \
+        }                                                                                             \
+    }
+#define OSC_D2_MAIN(S_, BUF_, ALO_, AHI_, BLO_, BHI_) OSC_D2((S_), a.Xq, rowbytes, wq, rowbytes, BUF_, ALO_, AHI_, BLO_, BHI_)
+#define OSC_D2_BRANCH(S_, BUF_, ALO_, AHI_, BLO_, BHI_) \
+    { if ((S_) < nT) OSC_D2((S_)-nTA, a.B, a.bpitch, wl, a.wlpitch, BUF_, ALO_, AHI_, BLO_, BHI_) }
+    // fragments of piece P_ (0..7) from buffer BUF_
+#define OSC_F2(BUF_, P_, FA_, FB_)                                                                    \
+    {                                                                                                 \
+        const uint8_t* st__ = lds + (BUF_)*STG;                                                       \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) FA_[i] =                                       \
+            *reinterpret_cast<const u32x4*>(st__ + st128_off(ra0 + 32 * i, (P_)));                    \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) FB_[j] =                                       \
+            *reinterpret_cast<const u32x4*>(st__ + st128_off(rb0 + 32 * j, (P_)));                    \
+    }
+
+    // scale words of stage T_ (half steps 2T_, 2T_+1) into scale buffer BUF_
+#define OSC_D2_SCALES(T_, BUF_)                                                                       \
+    {                                                                                                 \
+        const uint32_t o__ = (uint32_t)min(2 * (T_), Kg4 - 2) * 128u;                                 \
+        _Pragma("unroll") for (int k = 0; k < NSB; ++k) {                                             \
+            const int b__ = wave * NSB + k;                                                           \
+            const uint8_t* src__ = (b__ < BM / 32 ? a.Xs : wsb) + (o__ + sco[k]);                     \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src__,    \
+                                             (__attribute__((address_space(3))) void*)(scl + (BUF_)*SCL + b__ * 256), \
+                                             4, 0, 0);                                                \
+        }                                                                                             \
+    }
+    // this lane's scale words of half step H_ of buffer BUF_, byte I = scale of piece 2q+I
+#define OSC_D2_READ_SCALES(BUF_, H_, SA_, SB_)                                                        \
+    {                                                                                                 \
+        const uint8_t* sc__ = scl + (BUF_)*SCL + (H_)*128 + r * 4;                                    \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) SA_[i] =                                       \
+            *reinterpret_cast<const uint32_t*>(sc__ + (wm * TM + i) * 256) >> (16 * q);               \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) SB_[j] =                                       \
+            *reinterpret_cast<const uint32_t*>(sc__ + (BM / 32 + wn * TN + j) * 256) >> (16 * q);     \
+    }
+
+    // ---- prologue ---------------------------------------------------------------------------------
+    if (MODE == MODE_DUAL && nTA > 0) OSC_D2_SCALES(0, 0)
+    OSC_D2_ANY(0, 0, 0, LA, 0, LB)
+    wait_vmcnt<0>();
+    __syncthreads();
+    u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    int buf = 0;
+
+    // One FP4 stage = two half steps x two pieces.  REFILL_(stage, buffer, alo, ahi, blo, bhi)
+    // issues part of the next stage's loads.
+#define OSC_D2_STAGE_FP4(T_, REFILL_)                                                          \
+    {                                                                                          \
+        int sa[TM], sb[TN], ta[TM], tb[TN];                                                    \
+        OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
+        OSC_D2_READ_SCALES(buf, 0, sa, sb)                                                     \
+        if ((T_) + 1 < nTA) OSC_D2_SCALES((T_) + 1, buf ^ 1)                                   \
+        REFILL_((T_) + 1, buf ^ 1, 0, (LA * 3 + 7) / 8, 0, (LB * 3 + 7) / 8)                    \
+        OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
+        OSC_MFMA_FP4(0, fa0, fb0, sa, sb)                                                      \
+        spread_hint<TM * TN, TM + TN, 0, NSB + (LA * 3 + 7) / 8 + (LB * 3 + 7) / 8>();         \
+        REFILL_((T_) + 1, buf ^ 1, (LA * 3 + 7) / 8, (LA * 6 + 7) / 8, (LB * 3 + 7) / 8, (LB * 6 + 7) / 8) \
+        OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
+        OSC_D2_READ_SCALES(buf, 1, ta, tb)                                                     \
+        OSC_MFMA_FP4(1, fa1, fb1, sa, sb)                                                      \
+        spread_hint<TM * TN, 2 * (TM + TN), 0, (LA * 6 + 7) / 8 - (LA * 3 + 7) / 8 + (LB * 6 + 7) / 8 - (LB * 3 + 7) / 8>(); \
+        REFILL_((T_) + 1, buf ^ 1, (LA * 6 + 7) / 8, LA, (LB * 6 + 7) / 8, LB)                 \
+        OSC_F2(buf, 4 + 2 * q + 1, fa1, fb1)                                                   \
+        OSC_MFMA_FP4(0, fa0, fb0, ta, tb)                                                      \
+        spread_hint<TM * TN, TM + TN, 0, LA - (LA * 6 + 7) / 8 + LB - (LB * 6 + 7) / 8>();     \
+        OSC_MFMA_FP4(1, fa1, fb1, ta, tb)                                                      \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        buf ^= 1;                                                                              \
+    }
+#define OSC_D2_STAGE_BF16(T_)                                                                  \
+    {                                                                                          \
+        OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
+        OSC_D2_BRANCH((T_) + 1, buf ^ 1, 0, LA / 2, 0, LB / 2)                                 \
+        OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
+        OSC_MFMA_BF16(fa0, fb0)                                                                \
+        spread_hint<TM * TN, TM + TN, 0, LA / 2 + LB / 2>();                                   \
+        OSC_D2_BRANCH((T_) + 1, buf ^ 1, LA / 2, LA, LB / 2, LB)                               \
+        OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
+        OSC_MFMA_BF16(fa1, fb1)                                                                \
+        spread_hint<TM * TN, TM + TN, 0, LA - LA / 2 + LB - LB / 2>();                         \
+        OSC_F2(buf, 4 + 2 * q + 1, fa1, fb1)                                                   \
+        OSC_MFMA_BF16(fa0, fb0)                                                                \
+        spread_hint<TM * TN, TM + TN, 0, 0>();                                                 \
+        OSC_MFMA_BF16(fa1, fb1)                                                                \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        buf ^= 1;                                                                              \
+    }
+    // FP8 stage: 128 channels = two MFMAs per tile pair (pieces 2q,2q+1 and 4+2q,4+2q+1)
+#define OSC_D2_STAGE_FP8(T_)                                                                   \
+    {                                                                                          \
+        u32x4 ga0[TM], gb0[TN], ga1[TM], gb1[TN];                                              \
+        OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
+        OSC_F2(buf, 2 * q + 1, ga0, gb0)                                                       \
+        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, LA, 0, LB / 2)                    \
+        OSC_F2(buf, 4 + 2 * q, fa1, fb1)                                                       \
+        OSC_F2(buf, 4 + 2 * q + 1, ga1, gb1)                                                   \
+        OSC_MFMA_FP8(0, TM * TN, fa0, ga0, fb0, gb0)                                           \
+        spread_hint<TM * TN, 2 * (TM + TN), 0, LA + LB / 2>();                                 \
+        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, 0, LB / 2, LB)                    \
+        OSC_MFMA_FP8(0, TM * TN, fa1, ga1, fb1, gb1)                                           \
+        spread_hint<TM * TN, 0, 0, LB - LB / 2>();                                             \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        buf ^= 1;                                                                              \
+    }
+
+    if (MODE == MODE_FP8) {
+#pragma unroll 1
+        for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8(T)
+    } else {
+        int T = 0;
+#pragma unroll 1
+        for (; T + 1 < nTA; ++T) OSC_D2_STAGE_FP4(T, OSC_D2_MAIN)
+        if (T < nTA) {
+            OSC_D2_STAGE_FP4(T, OSC_D2_ANY)
+            ++T;
+        }
+#pragma unroll 1
+        for (; T < nT; ++T) OSC_D2_STAGE_BF16(T)
+    }
+    store_result<MODE, TM, TN>(a, tp, acc);
+}
+
+template <int MODE, int TM, int TN, bool RAGGED>
+static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const size_t smem = (size_t)(BM + BN) * 64 * 3;
+    a.tiles_n = (int)((a.N + BN - 1) / BN);
+    int64_t tiles_m = (rows_total + BM - 1) / BM;
+    if (grouped) tiles_m += a.E;  // upper bound: every expert may add one ragged tile
+    const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
-    auto kern = gemm_kernel<MODE, TM, TN>;
+    auto kern = gemm_kernel<MODE, TM, TN, RAGGED>;
     if (smem > 64 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -329,14 +768,34 @@ static int launch_cfg(const KArgs& a, int tiles_m, hipStream_t st) {
     return check_launch("gemm_kernel");
 }
 
+template <int MODE, int TM, int TN>
+static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
+    a.tiles_n = (int)((a.N + BN - 1) / BN);
+    int64_t tiles_m = (rows_total + BM - 1) / BM;
+    if (grouped) tiles_m += a.E;
+    const int64_t grid = tiles_m * a.tiles_n;
+    if (grid <= 0) return OSC_OK;
+    if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
+    auto kern = gemm_dma2_kernel<MODE, TM, TN>;
+    if (smem > 64 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), smem, st, a);
+    return check_launch("gemm_dma2_kernel");
+}
+
 template <int MODE>
 static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     KArgs a;
     a.Xq = p.Xq;
     a.Xs = p.Xs;
     a.xs = p.xs;
-    a.B = p.B;
-    a.ldb = p.ldb;
+    a.B = reinterpret_cast<const uint8_t*>(p.B);
+    a.bpitch = p.ldb * 2;
     a.row_map = p.row_map;
     a.off = p.expert_offsets;
     a.E = p.E;
@@ -347,13 +806,15 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         a.off_q = L.off_q;
         a.off_s = L.off_s;
         a.off_l = L.off_l;
-        a.ldwl = L.ldwl;
+        a.off_z = L.off_z;
+        a.wlpitch = L.ldwl * 2;
     } else {
         Pack8Layout L = pack8_layout(p.N, p.K);
         a.off_q = L.off_w;
         a.off_s = L.off_s;
         a.off_l = 0;
-        a.ldwl = 0;
+        a.off_z = L.off_z;
+        a.wlpitch = 0;
     }
     a.M = (int)p.M;
     a.N = (int)p.N;
@@ -362,20 +823,42 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     a.Y = p.Y;
     a.y_bf16 = p.y_dtype == OSC_DT_BF16;
     a.ldy = p.ldy;
-    // Tile choice: 128x128 workgroup tiles by default, 64-row tiles for short problems.
+    a.tiles_n = 0;
     const bool grouped = p.expert_offsets != nullptr;
-    auto tiles_m_for = [&](int BM) -> int {
-        int64_t tm = (p.M + BM - 1) / BM;
-        if (grouped) tm += p.E;  // upper bound: every expert may add one ragged tile
-        return (int)tm;
-    };
-    const int64_t rows = grouped && p.E > 0 ? (p.M + p.E - 1) / p.E : p.M;
-    if (rows <= 64) {
-        a.tiles_n = (int)((p.N + 127) / 128);
-        return launch_cfg<MODE, 1, 2>(a, tiles_m_for(64), st);
+    const int64_t rowbytes = (MODE == MODE_DUAL) ? p.K / 2 : p.K;
+    // the kernel addresses operand rows through 32-bit byte offsets (with a row_map the caller
+    // guarantees the same for the rows it names)
+    const int64_t lim = (int64_t)1 << 32;
+    if (p.M * rowbytes >= lim || p.N * rowbytes >= lim || p.M * a.bpitch >= lim || p.N * a.wlpitch >= lim ||
+        (p.M / 32 + 1) * ((p.K / 32 + 3) / 4) * 128 >= lim)
+        return fail(OSC_ERR_UNSUPPORTED, "gemm: an operand of 4 GiB or more");
+    const int64_t rows = grouped && p.E > 0 ? (p.M + p.E - 1) / p.E : p.M;  // rows per problem
+    // Kernel and tile choice.
+    //  - operand rows that are whole 128-byte lines: the DMA kernel; 256x256 tiles when they give
+    //    every CU at least one tile, else 128x128;
+    //  - short problems (<= 64 rows) and everything else: the staged kernel, 64x128 or 128x128
+    //    tiles, with per-lane zero fill when rows are not whole 64-byte steps.
+    const int64_t t256 = ((rows + 255) / 256) * ((p.N + 255) / 256) * (grouped ? p.E : 1);
+    const bool lines = rowbytes > 0 && rowbytes % 128 == 0 &&
+                       (MODE != MODE_DUAL || p.K_o == 0 || a.bpitch % 128 == 0);
+    const bool ragged = rowbytes % 64 != 0 || (MODE == MODE_DUAL && p.K_o > 0 && a.bpitch % 64 != 0);
+    int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : 2;
+    int kind = (lines && tm > 1) ? 1 : 0;  // 1 = DMA kernel
+    if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
+        int k2 = kind;
+        if (sscanf(ov, "%d,%d", &tm, &k2) == 2 && k2 == 1 && !(lines && tm > 1)) k2 = 0;
+        kind = k2;
     }
-    a.tiles_n = (int)((p.N + 127) / 128);
-    return launch_cfg<MODE, 2, 2>(a, tiles_m_for(128), st);
+    if (kind == 1) {
+        if (tm == 4) return launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
+        return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
+    }
+    if (ragged) {
+        if (tm == 1) return launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st);
+        return launch_cfg<MODE, 2, 2, true>(a, p.M, grouped, st);
+    }
+    if (tm == 1) return launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
+    return launch_cfg<MODE, 2, 2, false>(a, p.M, grouped, st);
 }
 
 int launch_dual_gemm(const GemmProblem& p, hipStream_t st) { return launch_gemm<MODE_DUAL>(p, st); }

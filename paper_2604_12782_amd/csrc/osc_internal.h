@@ -18,17 +18,24 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 // Layout of a packed dual-path weight: three sections, each 256-byte aligned.
 struct PackLayout {
     size_t off_q;   // uint8 [N, K/2]   MXFP4 codes, K-major
-    size_t off_s;   // uint8 [N, K/32]  E8M0 scales
+    size_t off_s;   // E8M0 scales, row-block-major (scale_bytes(N, K) bytes)
     size_t off_l;   // bf16  [N, ldwl]  W_L transposed (K_o-major), zero padded to ldwl
     int64_t ldwl;   // round_up(K_o, 64)
+    size_t off_z;   // 256 bytes of zeros (stand-in for anything past the end of an operand row)
     size_t total;
 };
 PackLayout pack_layout(int64_t N, int64_t K, int32_t K_o);
+// bytes of a row-block-major E8M0 scale tensor: [ceil(rows/32)][ceil(K/128)][32][4]
+inline size_t scale_bytes(int64_t rows, int64_t K) {
+    return (size_t)((rows + 31) / 32) * (size_t)((K / 32 + 3) / 4) * 128;
+}
+int launch_scales_to_rowmajor(const uint8_t* S, int64_t rows, int64_t K, uint8_t* out, hipStream_t st);
 
 // Layout of a packed FP8 weight.
 struct Pack8Layout {
     size_t off_w;  // uint8 [N, K]
     size_t off_s;  // float [N]
+    size_t off_z;  // 256 bytes of zeros
     size_t total;
 };
 Pack8Layout pack8_layout(int64_t N, int64_t K);

@@ -27,7 +27,7 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
     int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, uint16_t* __restrict__ B,
     int64_t ldb) {
     extern __shared__ uint32_t smem[];
-    const int Kg = K >> 5;
+    const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
     uint32_t* mask = smem;                                     // [Kg]
     int* first = reinterpret_cast<int*>(smem + Kg);            // [Kg]
@@ -97,7 +97,18 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
                 a = max(a, (uint32_t)__shfl_xor((int)a, 2));
                 // shared exponent floor(log2 amax) - 2, clamped below: E8M0 code = max(E - 2, 0)
                 int code = max((int)(a >> 7) - 2, 0);
-                if (sub == 0) Xs[(int64_t)m * Kg + g] = (uint8_t)code;
+                {   // four groups (16 lanes) -> one 32-bit word of the row-block-major scale layout
+                    const int g0 = g & ~3;
+                    uint32_t word = (uint32_t)code;
+                    uint32_t c1 = (uint32_t)__shfl_down(code, 4, 16);
+                    uint32_t c2 = (uint32_t)__shfl_down(code, 8, 16);
+                    uint32_t c3 = (uint32_t)__shfl_down(code, 12, 16);
+                    if (g0 + 1 < Kg) word |= c1 << 8;
+                    if (g0 + 2 < Kg) word |= c2 << 16;
+                    if (g0 + 3 < Kg) word |= c3 << 24;
+                    if ((c & 15) == 0)
+                        *reinterpret_cast<uint32_t*>(Xs + ((int64_t)(m >> 5) * Kg4 + (g >> 2)) * 128 + (m & 31) * 4) = word;
+                }
                 float scale = __builtin_bit_cast(float, (uint32_t)code << 23);
                 uint32_t out = 0;
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[0]), scale, 0);
@@ -154,6 +165,27 @@ int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, con
     else return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld exceeds 16384", (long long)K);
 #undef OSC_QLAUNCH
     return check_launch("quant_mxfp4_osc_kernel");
+}
+
+// Row-block-major scales -> plain [rows, K/32].
+__global__ void scales_to_rowmajor_kernel(const uint8_t* __restrict__ S, int64_t rows, int Kg,
+                                          uint8_t* __restrict__ out) {
+    const int Kg4 = (Kg + 3) >> 2;
+    const int64_t total = rows * Kg;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t m = i / Kg;
+        const int g = (int)(i - m * Kg);
+        out[i] = S[((m >> 5) * Kg4 + (g >> 2)) * 128 + (m & 31) * 4 + (g & 3)];
+    }
+}
+
+int launch_scales_to_rowmajor(const uint8_t* S, int64_t rows, int64_t K, uint8_t* out, hipStream_t st) {
+    const int64_t total = rows * (K / 32);
+    if (total == 0) return OSC_OK;
+    int grid = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(scales_to_rowmajor_kernel, dim3(grid), dim3(256), 0, st, S, rows, (int)(K / 32), out);
+    return check_launch("scales_to_rowmajor_kernel");
 }
 
 // ------------------------------------------------------------------------------------------

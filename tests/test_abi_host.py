@@ -48,12 +48,15 @@ def test_table_to_index_host(lib):
 
 
 def test_packed_sizes(lib):
-    # sections: codes N*K/2, scales N*K/32, W_L N*round_up(K_o,64)*2, each 256-byte aligned
-    assert osc.osc_packed_weight_bytes(4096, 4096, 256) == 4096 * 2048 + 4096 * 128 + 4096 * 256 * 2
-    assert osc.osc_packed_weight_bytes(256, 256, 8) == 256 * 128 + 256 * 8 + 256 * 64 * 2
-    assert osc.osc_packed_weight_bytes(3, 32, 0) == 256 + 256
+    # sections: codes N*K/2, scales, W_L N*round_up(K_o,64)*2, 256 zero bytes; each 256-byte aligned
+    assert osc.osc_packed_weight_bytes(4096, 4096, 256) == 4096 * 2048 + 4096 * 128 + 4096 * 256 * 2 + 256
+    assert osc.osc_packed_weight_bytes(256, 256, 8) == 256 * 128 + 256 * 8 + 256 * 64 * 2 + 256
+    assert osc.osc_packed_weight_bytes(3, 32, 0) == 256 + 256 + 256
+    # row-block-major scales: [ceil(M/32)][ceil(K/128)][32][4]
+    assert osc.osc_act_scale_bytes(8192, 4096) == 8192 * 128
+    assert osc.osc_act_scale_bytes(33, 96) == 2 * 1 * 128
     assert osc.osc_packed_weight_bytes(16, 33, 0) == 0  # K % 32 != 0
-    assert osc.osc_packed_weight_fp8_bytes(4096, 12288) == 4096 * 12288 + 4096 * 4
+    assert osc.osc_packed_weight_fp8_bytes(4096, 12288) == 4096 * 12288 + 4096 * 4 + 256
 
 
 FAKE = 0x10000  # a non-null, suitably aligned "device pointer" that is never dereferenced

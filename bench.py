@@ -136,8 +136,21 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    ms_quant = time_one(lambda: osc.osc_quantize_act(dX1, oidx1, out=q1))
-    ms_quant8 = time_one(lambda: osc.osc_quantize_act(dX1, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f1))
+    # The quantisers are HBM-bound: time them over a ring of inputs and outputs larger than the
+    # 256 MB last-level cache, so no call finds its operands left behind by the previous one.
+    nring = max(2, -(-(640 << 20) // (M * K_HID * 2)))
+    ringX = [dX1.clone() for _ in range(nring)]
+    ringQ = [tuple(torch.empty_like(t) for t in q1) for _ in range(nring)]
+    ringF = [tuple(torch.empty_like(t) for t in f1) for _ in range(nring)]
+    turn = [0]
+
+    def quant_ring(fmt, oidx, outs):
+        i = turn[0] = (turn[0] + 1) % nring
+        osc.osc_quantize_act(ringX[i], oidx, fmt, out=outs[i])
+
+    ms_quant = time_one(lambda: quant_ring(osc.OSC_FMT_MXFP4_OSC, oidx1, ringQ), reps=4 * nring)
+    ms_quant8 = time_one(lambda: quant_ring(osc.OSC_FMT_FP8_E4M3_TOKEN, None, ringF), reps=4 * nring)
+    del ringX, ringQ, ringF
     per = {}
     for n, N in PROJ:
         qq = q2 if n == "o" else q1

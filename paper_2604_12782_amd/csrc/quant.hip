@@ -13,127 +13,162 @@ constexpr int QT = 256;  // threads per workgroup
 // ------------------------------------------------------------------------------------------
 // MXFP4 + outlier gather.
 //
-// A row is cut into 16-byte chunks of 8 channels; chunk c belongs to thread c % 256 and the four
-// chunks of a 32-channel group sit in four neighbouring lanes, so the group's amax is two
-// cross-lane steps.  The suppression list is turned, once per workgroup, into one 32-bit mask
-// per group plus the column of B where the group's first protected channel goes; protected
-// values are parked in LDS at their column and the B row leaves with 16-byte stores.
+// A row is cut into 16-byte chunks of 8 channels and into segments of 128 chunks (1024
+// channels).  One wavefront converts one segment of one row at a time, two chunks per lane:
+// chunk c of the segment belongs to lane c % 64, the four chunks of a 32-channel group sit in
+// one quad of lanes (the group's amax is two DPP steps) and the sixteen chunks of four groups in
+// one DPP row (their four scale codes leave as one 32-bit word of the row-block-major layout).
+// The four wavefronts of a workgroup never wait for each other inside the loop.
 //
-// CPT = chunks per thread held in registers (row length <= 256*8*CPT channels).
+// The suppression list becomes, once per workgroup, a table of AND masks (one 32-bit word per
+// channel pair; zeroing protected channels is four ANDs per chunk, no branch) and the list of
+// B columns that each segment owns (the list is ascending, so a segment owns a contiguous run).
+// Every wavefront parks its raw segment in its own LDS strip; the lanes then pick the
+// protected channels out of the strip and store the run of B columns themselves.
+//
+// Work is dealt so that the workgroups which the hardware places on one XCD hold 32 consecutive
+// rows at a time: the 4-byte scale words of those rows share 128-byte lines and meet in that
+// XCD's L2 before they are written back.
 // ------------------------------------------------------------------------------------------
-template <int CPT>
+constexpr int SEG_CHUNKS = 128;             // chunks per segment (two per lane)
+constexpr int SEG_CH = SEG_CHUNKS * 8;      // channels per segment
+
+
+struct QItem {
+    int m, seg;
+};
+// linear work item (four per workgroup trip) -> (row, segment).  A block of 32 rows is
+// 32*nseg items; XCD x = workgroup % 8 owns blocks x, x+8, ...
+__device__ __forceinline__ QItem quant_item(int wg, int wave, int nseg, int M) {
+    const int per_block = 8 * nseg;          // workgroups per 32-row block
+    const int x = wg & 7, s = wg >> 3;
+    const int block = x + 8 * (s / per_block);
+    const int it = (s % per_block) * 4 + wave;  // item within the block, row-major (row, segment)
+    QItem q;
+    q.m = block * 32 + it / nseg;
+    q.seg = it % nseg;
+    if (q.m >= M) q.m = -1;
+    return q;
+}
+
 __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
     const uint16_t* __restrict__ X, int M, int K, int64_t ldx, const int32_t* __restrict__ oidx,
     int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, uint16_t* __restrict__ B,
-    int64_t ldb) {
+    int64_t ldb, int nseg, int total_wg) {
     extern __shared__ uint32_t smem[];
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    uint32_t* mask = smem;                                     // [Kg]
-    int* first = reinterpret_cast<int*>(smem + Kg);            // [Kg]
-    uint16_t* stage = reinterpret_cast<uint16_t*>(smem + ((2 * Kg + 3) & ~3));  // [ldb], 16-byte aligned
-    const int t = threadIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    // LDS: strips [4][SEG_CHUNKS] x 16 B | keep [K/2] words | colstart [nseg+1] | oidx16 [K_o]
+    u32x4* strip = reinterpret_cast<u32x4*>(smem) + wave * SEG_CHUNKS;
+    uint32_t* keep = smem + 4 * SEG_CHUNKS * 4;
+    int* colstart = reinterpret_cast<int*>(keep + (K >> 1));
+    uint16_t* och = reinterpret_cast<uint16_t*>(colstart + nseg + 1);
 
-    int m = blockIdx.x;
-    u32x4 v[CPT];
-    auto load_row = [&](int row) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(X + (int64_t)row * ldx);
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int c = t + QT * i;
-            if (c < nchunk) v[i] = __builtin_nontemporal_load(src + c);
-        }
-    };
-    if (m < M) load_row(m);  // in flight while the table is set up
+    int wg = blockIdx.x;
+    QItem cur = wg < total_wg ? quant_item(wg, wave, nseg, M) : QItem{-1, 0};
+    u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
+#define OSC_Q_LOAD(A0_, A1_, IT_)                                                              \
+    do {                                                                                       \
+        A0_ = (u32x4){0u, 0u, 0u, 0u};                                                         \
+        A1_ = (u32x4){0u, 0u, 0u, 0u};                                                         \
+        if ((IT_).m >= 0) {                                                                    \
+            const u32x4* src_ = reinterpret_cast<const u32x4*>(X + (int64_t)(IT_).m * ldx);    \
+            const int c_ = (IT_).seg * SEG_CHUNKS + lane;                                      \
+            if (c_ < nchunk) A0_ = __builtin_nontemporal_load(src_ + c_);                      \
+            if (c_ + 64 < nchunk) A1_ = __builtin_nontemporal_load(src_ + c_ + 64);            \
+        }                                                                                      \
+    } while (0)
+    OSC_Q_LOAD(v0, v1, cur);  // in flight during the set-up
 
     if (K_o > 0) {
-        for (int g = t; g < Kg; g += QT) {
-            mask[g] = 0u;
-            first[g] = 0x7fffffff;
-        }
-        for (int o = t; o < (int)(ldb >> 1); o += QT)
-            reinterpret_cast<uint32_t*>(stage)[o] = 0u;  // padding columns stay +0
+        for (int i = t; i < (K >> 1); i += QT) keep[i] = 0xffffffffu;
         __syncthreads();
         for (int o = t; o < K_o; o += QT) {
-            int c = oidx[o];
-            atomicOr(&mask[c >> 5], 1u << (c & 31));
-            atomicMin(&first[c >> 5], o);
+            const int c = oidx[o];
+            const int prev = o ? oidx[o - 1] : -1;
+            if (c >= 0 && c < K) atomicAnd(&keep[c >> 1], (c & 1) ? 0x0000ffffu : 0xffff0000u);
+            och[o] = (uint16_t)c;
+            // segments that start between the previous listed channel and this one start here
+            for (int sgm = (prev < 0 ? -1 : prev / SEG_CH) + 1; sgm <= c / SEG_CH && sgm <= nseg; ++sgm)
+                colstart[sgm] = o;
+            if (o == K_o - 1)
+                for (int sgm = c / SEG_CH + 1; sgm <= nseg; ++sgm) colstart[sgm] = K_o;
         }
         __syncthreads();
     }
 
-    for (; m < M; m += gridDim.x) {
-        uint32_t packed[CPT];
+    while (wg < total_wg) {
+        const int wgn = wg + gridDim.x;
+        const QItem nxt = wgn < total_wg ? quant_item(wgn, wave, nseg, M) : QItem{-1, 0};
+        u32x4 n0, n1;
+        OSC_Q_LOAD(n0, n1, nxt);  // next trip's loads fly while this one is converted
+        if (cur.m >= 0) {
+            const int m = cur.m;
+            const int cbase = cur.seg * SEG_CHUNKS;
+            uint32_t* dst = reinterpret_cast<uint32_t*>(Xq + (int64_t)m * (K >> 1));
+            uint8_t* sdst = Xs + (int64_t)(m >> 5) * Kg4 * 128 + (m & 31) * 4;
+            if (K_o > 0) {
+                strip[lane] = v0;
+                strip[lane + 64] = v1;
+            }
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int c = t + QT * i;
-            if (c < nchunk) {
-                uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-                const int g = c >> 2, sub = c & 3;
-                if (K_o > 0) {
-                    const uint32_t gm = mask[g];
-                    const uint32_t mb = (gm >> (8 * sub)) & 0xffu;
-                    if (mb) {  // steps 2-3 of Section 3.2: back up, then zero
-                        const int base = first[g];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            if (mb & (1u << j)) {
-                                int col = base + __builtin_popcount(gm & ((1u << (8 * sub + j)) - 1u));
-                                uint32_t word = w[j >> 1];
-                                stage[col] = (uint16_t)((j & 1) ? (word >> 16) : (word & 0xffffu));
-                                w[j >> 1] = (j & 1) ? (word & 0x0000ffffu) : (word & 0xffff0000u);
-                            }
-                        }
-                    }
+            for (int i = 0; i < 2; ++i) {
+                const int c = cbase + lane + 64 * i;
+                u32x4 w = i ? v1 : v0;
+                if (K_o > 0 && c < nchunk) {  // steps 2-3 of Section 3.2: (back-up is the strip) zero
+                    const u32x4 kp = *reinterpret_cast<const u32x4*>(keep + 4 * c);
+                    w &= kp;
                 }
-                // amax of the group on bit patterns: for finite bf16, |x| orders like bits & 0x7fff
-                uint32_t a = 0;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    uint32_t lo = w[k] & 0x7fffu, hi = (w[k] >> 16) & 0x7fffu;
-                    a = max(a, max(lo, hi));
-                }
-                a = max(a, (uint32_t)__shfl_xor((int)a, 1));
-                a = max(a, (uint32_t)__shfl_xor((int)a, 2));
+                // amax of the group on bit patterns: for finite bf16 |x| orders like bits & 0x7fff
+                u32x4 ab = w & 0x7fff7fffu;
+                uint32_t a = max(max(ab.x & 0xffffu, ab.x >> 16), max(ab.y & 0xffffu, ab.y >> 16));
+                a = max(a, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
+                a = max(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0xB1, 0xF, 0xF, false));  // lane ^ 1
+                a = max(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x4E, 0xF, 0xF, false));  // lane ^ 2
                 // shared exponent floor(log2 amax) - 2, clamped below: E8M0 code = max(E - 2, 0)
-                int code = max((int)(a >> 7) - 2, 0);
-                {   // four groups (16 lanes) -> one 32-bit word of the row-block-major scale layout
-                    const int g0 = g & ~3;
-                    uint32_t word = (uint32_t)code;
-                    uint32_t c1 = (uint32_t)__shfl_down(code, 4, 16);
-                    uint32_t c2 = (uint32_t)__shfl_down(code, 8, 16);
-                    uint32_t c3 = (uint32_t)__shfl_down(code, 12, 16);
-                    if (g0 + 1 < Kg) word |= c1 << 8;
-                    if (g0 + 2 < Kg) word |= c2 << 16;
-                    if (g0 + 3 < Kg) word |= c3 << 24;
-                    if ((c & 15) == 0)
-                        *reinterpret_cast<uint32_t*>(Xs + ((int64_t)(m >> 5) * Kg4 + (g >> 2)) * 128 + (m & 31) * 4) = word;
-                }
-                float scale = __builtin_bit_cast(float, (uint32_t)code << 23);
+                const uint32_t code = (uint32_t)max((int)(a >> 7) - 2, 0);
+                // four groups (one DPP row of 16 lanes) -> one 32-bit scale word in the row's first lane;
+                // chunks past the end of the row hold zeros, so their code is 0
+                uint32_t word = code;
+                word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;   // lane + 4
+                word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;  // lane + 8
+                word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;  // lane + 12
+                if ((lane & 15) == 0 && c < nchunk)
+                    *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+                const float scale = __builtin_bit_cast(float, code << 23);
+                // (scalars first: a bit cast applied to a vector component reads component 0)
+                const uint32_t w0 = w.x, w1 = w.y, w2 = w.z, w3 = w.w;
                 uint32_t out = 0;
-                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[0]), scale, 0);
-                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[1]), scale, 1);
-                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[2]), scale, 2);
-                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[3]), scale, 3);
-                packed[i] = out;
+                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w0), scale, 0);
+                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w1), scale, 1);
+                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w2), scale, 2);
+                out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w3), scale, 3);
+                if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
+            }
+            if (K_o > 0) {
+                // The strip was written by this wavefront, and LDS runs a wavefront's operations in
+                // order; the fences keep the compiler from moving the reads above the writes.
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const uint16_t* raw = reinterpret_cast<const uint16_t*>(strip);
+                uint16_t* brow = B + (int64_t)m * ldb;
+                const int o1 = colstart[cur.seg + 1];
+                for (int o = colstart[cur.seg] + lane; o < o1; o += 64)
+                    brow[o] = raw[(int)och[o] - cur.seg * SEG_CH];
+                if (cur.seg == nseg - 1)
+                    for (int o = K_o + lane; o < (int)ldb; o += 64) brow[o] = 0;  // padding columns: +0
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
             }
         }
-        const int mn = m + gridDim.x;
-        if (mn < M) load_row(mn);  // next row's loads overlap this row's stores
-        uint32_t* dst = reinterpret_cast<uint32_t*>(Xq + (int64_t)m * (K >> 1));
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int c = t + QT * i;
-            if (c < nchunk) __builtin_nontemporal_store(packed[i], dst + c);
-        }
-        if (K_o > 0) {
-            __syncthreads();
-            u32x4* bdst = reinterpret_cast<u32x4*>(B + (int64_t)m * ldb);
-            for (int i = t; i < (int)(ldb >> 3); i += QT)
-                __builtin_nontemporal_store(reinterpret_cast<const u32x4*>(stage)[i], bdst + i);
-            __syncthreads();
-        }
+        cur = nxt;
+        v0 = n0;
+        v1 = n1;
+        wg = wgn;
     }
+#undef OSC_Q_LOAD
 }
 
 // B columns of a table-free call still have to read +0 when the caller passes a buffer.
@@ -147,23 +182,28 @@ __global__ void zero_rows_kernel(uint16_t* B, int M, int64_t ldb) {
 int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx,
                        int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
                        hipStream_t st) {
-    const int64_t Kg = K / 32;
+    if (K > 65536) return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld exceeds 65536", (long long)K);
     const int64_t nchunk = K / 8;
-    const int cpt = (int)((nchunk + QT - 1) / QT);
-    size_t smem = (size_t)((2 * Kg + 3) & ~(int64_t)3) * 4 + (K_o > 0 ? (size_t)ldb * 2 : 0);
-    if (smem > 60 * 1024) return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld / ldb=%lld too large for the table in LDS", (long long)K, (long long)ldb);
-    int grid = (int)(M < 2048 ? M : 2048);
+    const int nseg = (int)((nchunk + SEG_CHUNKS - 1) / SEG_CHUNKS);
+    size_t smem = 4 * SEG_CHUNKS * 16;
+    if (K_o > 0) smem += (size_t)(K / 2) * 4 + (size_t)(nseg + 1) * 4 + (size_t)K_o * 2;
+    if (smem > 160 * 1024)
+        return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld with K_o=%d needs %zu bytes of LDS", (long long)K, (int)K_o, smem);
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(quant_mxfp4_osc_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(OSC_ERR_HIP, "quantize: LDS attribute: %s", hipGetErrorString(e));
+    }
+    // 32-row blocks of 8*nseg workgroups each, dealt to XCDs in groups of eight blocks
+    const int64_t blocks = (M + 31) / 32;
+    const int64_t total_wg = (blocks + 7) / 8 * 8 * (8 * nseg);
+    if (total_wg > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "quantize: M=%lld too large", (long long)M);
+    const int64_t cap = 2048;  // eight workgroups per compute unit
+    int grid = (int)(total_wg < cap ? total_wg : cap);
     if (K_o == 0 && B && ldb > 0)
         hipLaunchKernelGGL(zero_rows_kernel, dim3(grid), dim3(QT), 0, st, B, (int)M, ldb);
-#define OSC_QLAUNCH(C)                                                                           \
-    hipLaunchKernelGGL(quant_mxfp4_osc_kernel<C>, dim3(grid), dim3(QT), smem, st, X, (int)M, (int)K, \
-                       ldx, oidx, (int)K_o, Xq, Xs, B, ldb)
-    if (cpt <= 1) OSC_QLAUNCH(1);
-    else if (cpt <= 2) OSC_QLAUNCH(2);
-    else if (cpt <= 4) OSC_QLAUNCH(4);
-    else if (cpt <= 8) OSC_QLAUNCH(8);
-    else return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld exceeds 16384", (long long)K);
-#undef OSC_QLAUNCH
+    hipLaunchKernelGGL(quant_mxfp4_osc_kernel, dim3(grid), dim3(QT), smem, st, X, (int)M, (int)K, ldx, oidx,
+                       (int)K_o, Xq, Xs, B, ldb, nseg, (int)total_wg);
     return check_launch("quant_mxfp4_osc_kernel");
 }
 

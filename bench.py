@@ -26,6 +26,11 @@ PEAK_MXFP4_TFLOPS = 10066.0  # MI355X dense MXFP4 matrix peak
 PEAK_FP8_TFLOPS = 5033.0
 PEAK_HBM_GBS = 8000.0
 K_HID = 4096
+# Bytes between L2 and the fabric per launch of the dominant kernel (dual-path GEMM 8192x4096x4096,
+# K_o=256, bf16 out), from rocprofv3 FETCH_SIZE/WRITE_SIZE runs of this script scaled by a 1 GiB
+# plain copy (summary: profiles/configs1_M8192_step__hbm_traffic.txt).  A profiler reading, not
+# something this script can measure itself.
+DOMINANT_TRAFFIC_BYTES = {8192: 200.1e6}
 PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
 
 
@@ -56,6 +61,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a counter yardstick for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -122,6 +129,13 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    if args.copy_mib:
+        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_step = timed_loop(step, args.steps, args.warmup, timed=True)
     dom_ms = float(np.mean([a.elapsed_time(b) for a, b in dom]))
     ms_fp8 = timed_loop(step_fp8, max(args.steps // 2, 1), 3)
@@ -173,7 +187,8 @@ def main():
                                "q/o 4096->4096, k/v 4096->1024, 2 outliers per 32-group (K_o=256), Y bf16",
                    "tokens": M, "K": K_HID, "K_o": K_o},
         "roofline": {"bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_MXFP4_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_MXFP4_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_MXFP4_TFLOPS, 4),
+                     "traffic": DOMINANT_TRAFFIC_BYTES.get(M),
                      "kernel": f"dual-path GEMM M={M} N=4096 K=4096 K_o={K_o}", "avg_ms": round(dom_ms, 4)},
         "frac_mxfp4_peak_whole_step": round(value / PEAK_MXFP4_TFLOPS, 4),
         "fp8_w8a8": {"ms_per_step": round(ms_fp8, 4), "tflops": round(flops / (ms_fp8 * 1e-3) / 1e12, 2),

@@ -36,6 +36,8 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 constexpr int GT = 256;  // 4 wavefronts, arranged 2 x 2 over the workgroup tile
 enum { MODE_DUAL = 0, MODE_FP8 = 1 };
@@ -78,34 +80,74 @@ struct TilePos {
 // run of tiles and its L2 sees neighbouring tiles.  Single problem: tiles walk down bands of 8
 // m-tiles.  Grouped: m-tiles are numbered expert by expert (the grid is an upper bound).
 template <int BM, int BN>
+__device__ __forceinline__ TilePos tile_at(const KArgs& a, int tile);
+
+template <int BM, int BN>
 __device__ __forceinline__ TilePos locate_tile(const KArgs& a) {
-    TilePos p;
     int tile = blockIdx.x;
-    {
+    if (a.off) {
+        // grouped: XCD x takes m-tiles x, x+8, ... and walks the n-tiles of each in turn (they share
+        // the activation rows).  The surplus m-tiles at the end of the numbering (the grid is an
+        // upper bound, a multiple of 8 m-tiles) are then spread over all XCDs.
+        const int x = tile & 7, sidx = tile >> 3;
+        tile = ((sidx / a.tiles_n) * 8 + x) * a.tiles_n + sidx % a.tiles_n;
+    } else {
         const int per = gridDim.x >> 3;
         if (tile < (per << 3)) tile = (tile & 7) * per + (tile >> 3);
     }
+    return tile_at<BM, BN>(a, tile);
+}
+
+// position of tile number `tile` (numbered so that neighbours share operand panels)
+template <int BM, int BN>
+__device__ __forceinline__ TilePos tile_at(const KArgs& a, int tile) {
+    TilePos p;
     p.row_begin = 0;
     p.row_end = a.M;
     p.wp = a.Wpack;
     p.valid = true;
     int tm_idx, tn_idx;
     if (a.off) {
+        // m-tiles are numbered expert by expert.  Every wavefront finds the expert of m-tile j by
+        // itself: 64 experts at a time, one per lane, prefix sum of their tile counts, first lane
+        // whose running total exceeds j.  (A serial walk over the offsets costs one dependent
+        // memory round trip per expert.)
         tn_idx = tile % a.tiles_n;
-        int j = tile / a.tiles_n, e = 0;
-        for (; e < a.E; ++e) {
-            const int b = a.off[e], n = a.off[e + 1] - b;
+        const int j = tile / a.tiles_n;
+        const int lane = threadIdx.x & 63;
+        int before = 0, e_found = -1, j_in = 0;
+        for (int e0 = 0; e0 < a.E; e0 += 64) {
+            const int e = e0 + lane;
+            const int b = e < a.E ? a.off[e] : 0;
+            const int n = e < a.E ? a.off[e + 1] - b : 0;
             const int te = (n + BM - 1) / BM;
-            if (j < te) {
-                p.row_begin = b;
-                p.row_end = b + n;
+            int ps = te;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int v = __shfl_up(ps, d);
+                if (lane >= d) ps += v;
+            }
+            const int total = __shfl(ps, 63);
+            if (j < before + total) {
+                const int l = __ffsll((unsigned long long)__ballot(before + ps > j)) - 1;
+                e_found = e0 + l;
+                j_in = j - (before + __shfl(ps, l) - __shfl(te, l));
+                p.row_begin = __shfl(b, l);
+                p.row_end = p.row_begin + __shfl(n, l);
                 break;
             }
-            j -= te;
+            before += total;
         }
-        if (e == a.E) p.valid = false;  // surplus workgroup
-        tm_idx = j;
-        p.wp += (size_t)e * a.pack_stride;
+        e_found = __builtin_amdgcn_readfirstlane(e_found);
+        j_in = __builtin_amdgcn_readfirstlane(j_in);
+        p.row_begin = __builtin_amdgcn_readfirstlane(p.row_begin);
+        p.row_end = __builtin_amdgcn_readfirstlane(p.row_end);
+        if (e_found < 0) {  // surplus workgroup (the grid is an upper bound)
+            p.valid = false;
+            e_found = 0;
+        }
+        tm_idx = j_in;
+        p.wp += (size_t)e_found * a.pack_stride;
     } else {
         const int tiles_m = (a.M + BM - 1) / BM;
         const int band = tile / (8 * a.tiles_n), within = tile - band * 8 * a.tiles_n;
@@ -132,8 +174,14 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
     // writes them as one 32-bit word (even lanes row k, odd lanes row k+1).
     const float* wsc = (MODE == MODE_FP8) ? reinterpret_cast<const float*>(wp + a.off_s) : nullptr;
     const int odd = r & 1;
-    auto store_tile = [&](auto full_tag) __attribute__((always_inline)) {
-        constexpr bool FULL = decltype(full_tag)::value;  // tile entirely inside Y: no bounds tests
+    const int wu_m = __builtin_amdgcn_readfirstlane(wm), wu_n = __builtin_amdgcn_readfirstlane(wn);
+    // byte offset of this lane's pair inside a 32x32 result tile: row 4q + odd, columns r - odd, r - odd + 1
+    const uint32_t yoff = 2u * (uint32_t)((4 * q + odd) * (int)a.ldy + r - odd);
+    auto store_tile = [&](auto kind_tag) __attribute__((always_inline)) {
+        // 2: tile entirely inside Y, no bounds tests; 1: all columns inside, rows tested (ragged
+        // last tile of a problem or an expert); 0: everything tested, 2-byte stores
+        constexpr int KIND = decltype(kind_tag)::value;
+        constexpr bool FULL = KIND == 2;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int rbase = m0 + wm * (TM * 32) + i * 32 + 4 * q;
@@ -154,7 +202,23 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
 #pragma unroll
                 for (int k = 0; k < 16; ++k)
                     v[k] = (MODE == MODE_FP8) ? acc[i][j][k] * (xr[k] * cs) : acc[i][j][k];
-                if (a.y_bf16) {
+                if (a.y_bf16 && KIND >= 1) {
+                    // whole tile, 4-byte stores: uniform base per (tile, register pair) + one per-lane offset;
+                    // the pair is rounded to bf16 (nearest even) by one packed conversion
+                    uint8_t* const ybase = reinterpret_cast<uint8_t*>(a.Y) +
+                        2 * ((int64_t)(m0 + wu_m * (TM * 32) + i * 32) * a.ldy + n0 + wu_n * (TN * 32) + j * 32);
+#pragma unroll
+                    for (int k = 0; k < 16; k += 2) {
+                        const float send = odd ? v[k] : v[k + 1];
+                        const float recv = __builtin_bit_cast(
+                            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));
+                        const v2f pair = {odd ? recv : v[k], odd ? v[k + 1] : recv};
+                        const uint32_t word = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, v2bf));
+                        uint8_t* const kbase = ybase + 2 * (int64_t)(8 * (k >> 2) + (k & 3)) * a.ldy;
+                        if (FULL || rbase + 8 * (k >> 2) + (k & 3) + odd < row_end)
+                            *reinterpret_cast<uint32_t*>(kbase + yoff) = word;
+                    }
+                } else if (a.y_bf16) {
                     uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
 #pragma unroll
                     for (int k = 0; k < 16; k += 2) {
@@ -168,9 +232,7 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
                         uint16_t* dst = Y + (int64_t)row * a.ldy + c0;
                         const uint32_t word =
                             (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
-                        if (FULL) {
-                            *reinterpret_cast<uint32_t*>(dst) = word;
-                        } else if (row < row_end) {
+                        if (row < row_end) {
                             if (c0 < a.N) dst[0] = (uint16_t)word;
                             if (c0 + 1 < a.N) dst[1] = (uint16_t)(word >> 16);
                         }
@@ -180,19 +242,21 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
 #pragma unroll
                     for (int k = 0; k < 16; ++k) {
                         const int row = rbase + 8 * (k >> 2) + (k & 3);
-                        if (FULL || (row < row_end && col < a.N)) Y[(int64_t)row * a.ldy + col] = v[k];
+                        if (FULL || (row < row_end && (KIND == 1 || col < a.N))) Y[(int64_t)row * a.ldy + col] = v[k];
                     }
                 }
             }
         }
     };
     // 32-bit stores of bf16 pairs need an even leading dimension and a 4-byte aligned Y
-    const bool full = (m0 + BM <= row_end) && (n0 + BN <= a.N) &&
+    const bool cols = (n0 + BN <= a.N) &&
                       (!a.y_bf16 || (((a.ldy & 1) == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 3) == 0)));
-    if (full)
-        store_tile(std::true_type{});
+    if (cols && m0 + BM <= row_end)
+        store_tile(std::integral_constant<int, 2>{});
+    else if (cols)
+        store_tile(std::integral_constant<int, 1>{});
     else
-        store_tile(std::false_type{});
+        store_tile(std::integral_constant<int, 0>{});
 }
 
 // ------------------------------------------------------------------------------------------
@@ -689,8 +753,10 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
         OSC_MFMA_FP4(0, fa0, fb0, ta, tb)                                                      \
         spread_hint<TM * TN, TM + TN, 0, LA - (LA * 6 + 7) / 8 + LB - (LB * 6 + 7) / 8>();     \
         OSC_MFMA_FP4(1, fa1, fb1, ta, tb)                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         wait_vmcnt<0>();                                                                       \
         __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         buf ^= 1;                                                                              \
     }
 #define OSC_D2_STAGE_BF16(T_)                                                                  \
@@ -708,8 +774,10 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
         OSC_MFMA_BF16(fa0, fb0)                                                                \
         spread_hint<TM * TN, TM + TN, 0, 0>();                                                 \
         OSC_MFMA_BF16(fa1, fb1)                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         wait_vmcnt<0>();                                                                       \
         __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         buf ^= 1;                                                                              \
     }
     // FP8 stage: 128 channels = two MFMAs per tile pair (pieces 2q,2q+1 and 4+2q,4+2q+1)
@@ -726,8 +794,10 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
         if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, 0, LB / 2, LB)                    \
         OSC_MFMA_FP8(0, TM * TN, fa1, ga1, fb1, gb1)                                           \
         spread_hint<TM * TN, 0, 0, LB - LB / 2>();                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         wait_vmcnt<0>();                                                                       \
         __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
         buf ^= 1;                                                                              \
     }
 
@@ -748,13 +818,506 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     store_result<MODE, TM, TN>(a, tp, acc);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Persistent pipelined kernel (dual path) for one problem made of whole tiles (M % BM == 0,
+// N % BN == 0, no row map).  Same operands and LDS image as the DMA kernel above, but
+//  (1) the order of every instruction of a stage is pinned: a stage is a row of slots, one MFMA per
+//      slot, and every LDS read and DMA load is tied to a slot and fenced there (sched_barrier).
+//      Left alone, the compiler hoists all memory operations of a stage above its MFMAs (or sinks
+//      the MFMAs below the last branch of the loop body) and the matrix core idles while they issue;
+//  (2) a stage releases its LDS buffer early.  Stage T computes from buffer T % 2:
+//        group 0 (piece 2q,     set X, scales S0): reads piece 4+2q+1 into set Z and scales S1
+//        group 1 (piece 2q+1,   set Y):            reads piece 4+2q into set X
+//        slot A_AT: every wave has read the whole stage -> barrier -> the loads of stage T+2 start
+//                   flowing into the buffer, spread evenly over the rest of the stage
+//        group 2 (piece 4+2q,   set X, scales S1)
+//        slot B_AT: loads of stage T+1 have landed (vmcnt leaves the younger ones in flight) -> barrier
+//        group 3 (piece 4+2q+1, set Z): reads pieces 2q, 2q+1 of stage T+1 into X, Y and scales S0
+//      so a load has about one to 1.3 stages to land and the first MFMA of a stage never waits;
+//  (3) one workgroup per compute unit walks a list of tiles, and the stream of loads runs ahead of
+//      the stream of MFMAs across tile borders: the load cursor (tile, stage) is two stages ahead of
+//      the compute cursor, so while the last two stages of a tile are computed the first two of the
+//      next tile arrive, and the result stores of a tile drain under the next tile's main loop.
+// Every stage moves the same number of loads (a bf16 branch stage carries idle scale loads; past
+// the last tile the last stage is fetched again into a buffer nobody reads), so the wait before the
+// second barrier of a stage is a compile-time count and the stage has no branch.  Addresses are a
+// uniform base per (tile, stage, 32-row block) plus one per-thread 32-bit offset.  XCD x
+// (= workgroup % 8) owns the x-th eighth of the tile list; its workgroups take neighbouring tiles
+// at any time (8 m-tiles x 4 n-tiles with 32 workgroups).
+// ------------------------------------------------------------------------------------------
+template <int TM, int TN>
+__global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int STG = (BM + BN) * 128;
+    constexpr int LA = BM / 32, LB = BN / 32;
+    constexpr int NBLK = (BM + BN) / 32, NSB = NBLK / 4, SCL = NBLK * 256;
+    constexpr int NT = TM * TN, NSLOT = 4 * NT, NRD = 2 * (TM + TN), NLD = NSB + LA + LB;
+    // Three register sets: X holds piece 2q, then 4+2q, then piece 2q of the next stage; Y holds piece
+    // 2q+1; Z holds piece 4+2q+1.  Reads: Z in group 0, X again in group 1 (after group 0 consumed
+    // it), and X, Y of the next stage in group 3.
+    constexpr int HR = TM + TN;                       // 16-byte reads per piece
+    constexpr int RPS = (HR + NT - 1) / NT;           // reads per slot
+    constexpr int A_AT = NT + (HR + RPS - 1) / RPS + NT / 4;  // free point: the reads of group 1 have landed
+    constexpr int B_AT = 3 * NT - 1;
+    // loads: spread evenly over the LW slots behind the free point; load l goes to slot A_AT + 1 + l * LW / NLD
+    constexpr int LW = NSLOT - A_AT - 1;
+    constexpr int LPS = NLD / LW + 2;  // upper bound of loads in one slot
+    static_assert(LW >= 2, "no room for the loads");
+    constexpr int RPS2 = (2 * HR + NSLOT - B_AT - 2) / (NSLOT - B_AT - 1);
+    constexpr int N_BEFORE_B = []() {
+        int n = 0;
+        for (int l = 0; l < NLD; ++l)
+            if (A_AT + 1 + l * LW / NLD <= B_AT) ++n;
+        return n;
+    }();
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint8_t* const scl = lds + 2 * STG;
+
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const int Kg4 = ((a.K >> 5) + 3) >> 2;
+    const int rowbytes = a.K >> 1;
+    const int nTA = rowbytes >> 7;
+    const int nTB = (a.K_o * 2 + 127) >> 7;
+    const int nT = nTA + nTB;  // >= 3 (checked on the host)
+    const int ra0 = wm * (TM * 32) + r, rb0 = BM + wn * (TN * 32) + r;
+    const int tiles_m = a.M / BM;
+
+    // this workgroup's tiles: first, first + step, ... below last
+    const int per = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7;
+    const int step = (gridDim.x + 7 - xcd) >> 3;  // workgroups on this XCD
+    const int last = min(ntiles, (xcd + 1) * per);
+    int ctile = xcd * per + (blockIdx.x >> 3);    // compute cursor
+    if (ctile >= last) return;
+
+    // per-thread parts of the addresses: row (t >> 3) of a 32-row block, 16-byte piece c8
+    const uint32_t c8 = (uint32_t)((t & 7) ^ swz8(t >> 3)) * 16u;
+    const uint32_t vo_main = (uint32_t)(t >> 3) * (uint32_t)rowbytes + c8;       // FP4 phase, both operands
+    const uint32_t vo_ba = (uint32_t)(t >> 3) * (uint32_t)a.bpitch + c8;         // branch phase, B rows
+    const uint32_t vo_bw = (uint32_t)(t >> 3) * (uint32_t)a.wlpitch + c8;        // branch phase, W_L rows
+    const uint32_t vo_s = (uint32_t)(r * 4 + q * 128);                            // scale word of row r, half step q
+    const uint8_t* const wq = a.Wpack + a.off_q;
+    const uint8_t* const wl = a.Wpack + a.off_l;
+    const uint8_t* const wsb = a.Wpack + a.off_s;
+
+    // ---- load cursor: tile (m0, n0), stage lT; uniform bases of the stage's first 32-row blocks ----
+    int lT = 0, lm0, ln0;
+    int nm0 = 0, nn0 = 0;      // position of this workgroup's tile after the one under the load cursor
+    bool hasnext;
+    const uint8_t *pa, *pb, *psa, *psb;  // A rows, B rows, A scale block, B scale block at this stage
+    uint32_t sa32, sb32;                 // bytes between consecutive 32-row blocks
+    uint32_t voa, vob;                   // per-thread offsets in use
+#define PIPE2_TILE_POS(TILE_, M0_, N0_)                                                              \
+    {                                                                                                \
+        const int band__ = (TILE_) / (8 * a.tiles_n), within__ = (TILE_)-band__ * 8 * a.tiles_n;     \
+        const int rows__ = min(8, tiles_m - band__ * 8);                                             \
+        M0_ = (band__ * 8 + within__ % rows__) * BM;                                                 \
+        N0_ = (within__ / rows__) * BN;                                                              \
+    }
+#define PIPE2_STAGE_SETUP                                                                            \
+    {                                                                                                \
+        /* selects only: a branch here would split the stage into basic blocks, and the compiler     \
+           then sinks every MFMA of the stage below the last of them */                              \
+        const bool fp4__ = lT < nTA;                                                                 \
+        const uint32_t ko__ = (uint32_t)(fp4__ ? lT : lT - nTA) * 128u;                              \
+        const uint32_t pitcha__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.bpitch;                   \
+        const uint32_t pitchb__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.wlpitch;                  \
+        sa32 = 32u * pitcha__;                                                                       \
+        sb32 = 32u * pitchb__;                                                                       \
+        pa = (fp4__ ? a.Xq : a.B) + ((size_t)lm0 * pitcha__ + ko__);                                 \
+        pb = (fp4__ ? wq : wl) + ((size_t)ln0 * pitchb__ + ko__);                                    \
+        voa = fp4__ ? vo_main : vo_ba;                                                               \
+        vob = fp4__ ? vo_main : vo_bw;                                                               \
+        const uint32_t so__ = (uint32_t)min(2 * lT, Kg4 - 2) * 128u;                                 \
+        psa = a.Xs + ((size_t)(lm0 >> 5) * (uint32_t)Kg4 * 128u + so__);                             \
+        psb = wsb + ((size_t)(ln0 >> 5) * (uint32_t)Kg4 * 128u + so__);                              \
+    }
+    // advance the load cursor by one stage; at the end of a tile it moves to (nm0, nn0), the next
+    // tile of this workgroup, or, if there is none, stays on the last stage
+#define PIPE2_ADVANCE                                                                                \
+    {                                                                                                \
+        const bool wrap__ = lT + 1 == nT;                                                            \
+        const bool jump__ = wrap__ && hasnext;                                                       \
+        lT = wrap__ ? (hasnext ? 0 : lT) : lT + 1;                                                   \
+        lm0 = jump__ ? nm0 : lm0;                                                                    \
+        ln0 = jump__ ? nn0 : ln0;                                                                    \
+        PIPE2_STAGE_SETUP                                                                            \
+    }
+    // load number L_ (0..NLD-1) of the stage under the load cursor into buffer BUF_
+#define PIPE2_LOAD(L_, BUF_)                                                                         \
+    {                                                                                                \
+        if ((L_) < NSB) {                                                                            \
+            const int b__ = wave * NSB + (L_);                                                       \
+            const uint8_t* src__ = (b__ < BM / 32 ? psa + (size_t)b__ * ((uint32_t)Kg4 * 128u)       \
+                                                  : psb + (size_t)(b__ - BM / 32) * ((uint32_t)Kg4 * 128u)) + vo_s; \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src__,   \
+                                             (__attribute__((address_space(3))) void*)(scl + (BUF_)*SCL + b__ * 256), \
+                                             4, 0, 0);                                               \
+        } else if ((L_) < NSB + LA) {                                                                \
+            const int i__ = (L_)-NSB;                                                                \
+            load_to_lds16(pa + (size_t)i__ * sa32 + voa, lds + (BUF_)*STG + wave * 1024 + i__ * 4096); \
+        } else {                                                                                     \
+            const int i__ = (L_)-NSB - LA;                                                           \
+            load_to_lds16(pb + (size_t)i__ * sb32 + vob,                                             \
+                          lds + (BUF_)*STG + wave * 1024 + BM * 128 + i__ * 4096);                   \
+        }                                                                                            \
+    }
+
+    // scale word number R_ (0..TM+TN-1) of half step H_
+#define PIPE_READ_SCALE(R_, BUF_, H_, SA_, SB_)                                                         \
+    {                                                                                                   \
+        /* a 16-bit read at byte 2q of the word: byte I of the register = scale of piece 2q+I, no shift */ \
+        const uint8_t* sc__ = scl + (BUF_)*SCL + (H_)*128 + r * 4 + 2 * q;                              \
+        if ((R_) < TM)                                                                                  \
+            SA_[(R_) < TM ? (R_) : 0] = *reinterpret_cast<const uint16_t*>(sc__ + (wm * TM + (R_)) * 256); \
+        else                                                                                            \
+            SB_[(R_) >= TM ? (R_)-TM : 0] =                                                             \
+                *reinterpret_cast<const uint16_t*>(sc__ + (BM / 32 + wn * TN + (R_)-TM) * 256);         \
+    }
+#define PIPE_MFMA_FP4(N_, FA_, FB_, SA_, SB_, SEL_)                                                     \
+    {                                                                                                   \
+        const int i__ = (N_) / TN, j__ = (N_) % TN;                                                     \
+        const v8i av__ = {(int)FA_[i__].x, (int)FA_[i__].y, (int)FA_[i__].z, (int)FA_[i__].w, 0, 0, 0, 0}; \
+        const v8i bv__ = {(int)FB_[j__].x, (int)FB_[j__].y, (int)FB_[j__].z, (int)FB_[j__].w, 0, 0, 0, 0}; \
+        acc[i__][j__] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i__][j__], 4, 4, SEL_, \
+                                                                        SA_[i__], SEL_, SB_[j__]);      \
+    }
+#define PIPE_MFMA_BF16(N_, FA_, FB_)                                                                    \
+    {                                                                                                   \
+        const int i__ = (N_) / TN, j__ = (N_) % TN;                                                     \
+        acc[i__][j__] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, FA_[i__]),     \
+                                                                __builtin_bit_cast(v8bf, FB_[j__]),     \
+                                                                acc[i__][j__], 0, 0, 0);                \
+    }
+    // read number R_ (0..TM+TN-1) of piece P_ from buffer BUF_ into set SA_/SB_
+#define PIPE_READ1(R_, BUF_, P_, SA_, SB_)                                                             \
+    {                                                                                                  \
+        const uint8_t* st__ = lds + (BUF_)*STG;                                                        \
+        const u32x4 v__ = *reinterpret_cast<const u32x4*>(                                             \
+            st__ + st128_off(((R_) < TM ? ra0 + 32 * (R_) : rb0 + 32 * ((R_)-TM)), (P_)));             \
+        if ((R_) < TM) SA_[(R_) < TM ? (R_) : 0] = v__;                                                \
+        else SB_[(R_) >= TM ? (R_)-TM : 0] = v__;                                                      \
+    }
+    u32x4 Xa[TM], Xb[TN], Ya[TM], Yb[TN], Za[TM], Zb[TN];
+    int s0a[TM], s0b[TN], s1a[TM], s1b[TN];
+    v16f acc[TM][TN];
+
+    // ---- prologue: the first two stages of the first tile ---------------------------------------
+    PIPE2_TILE_POS(ctile, lm0, ln0)
+    hasnext = false;  // the first two stages belong to the first tile (nT >= 3)
+    PIPE2_STAGE_SETUP
+#pragma unroll
+    for (int l = 0; l < NLD; ++l) PIPE2_LOAD(l, 0)
+    PIPE2_ADVANCE
+#pragma unroll
+    for (int l = 0; l < NLD; ++l) PIPE2_LOAD(l, 1)
+    PIPE2_ADVANCE
+    wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q, Xa, Xb)
+#pragma unroll
+    for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q + 1, Ya, Yb)
+#pragma unroll
+    for (int rd = 0; rd < TM + TN; ++rd) PIPE_READ_SCALE(rd, 0, 0, s0a, s0b)
+    int buf = 0;
+
+#define PIPE2_FENCE __builtin_amdgcn_sched_barrier(0);
+#define PIPE2_GROUP(G_, FP4_)                                                                          \
+    {                                                                                                  \
+        _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
+            constexpr int g__ = (G_);                                                                  \
+            const int k = g__ * NT + n__;                                                              \
+            if (FP4_) {                                                                                \
+                if (g__ == 0) PIPE_MFMA_FP4(n__, Xa, Xb, s0a, s0b, 0)                                  \
+                else if (g__ == 1) PIPE_MFMA_FP4(n__, Ya, Yb, s0a, s0b, 1)                             \
+                else if (g__ == 2) PIPE_MFMA_FP4(n__, Xa, Xb, s1a, s1b, 0)                             \
+                else PIPE_MFMA_FP4(n__, Za, Zb, s1a, s1b, 1)                                           \
+            } else {                                                                                   \
+                if (g__ == 0) PIPE_MFMA_BF16(n__, Xa, Xb)                                              \
+                else if (g__ == 1) PIPE_MFMA_BF16(n__, Ya, Yb)                                         \
+                else if (g__ == 2) PIPE_MFMA_BF16(n__, Xa, Xb)                                         \
+                else PIPE_MFMA_BF16(n__, Za, Zb)                                                       \
+            }                                                                                          \
+            /* group 0: piece 4+2q+1 -> Z, scales of the second half -> S1 */                          \
+            if (g__ == 0) {                                                                            \
+                _Pragma("unroll") for (int u = 0; u < RPS; ++u)                                        \
+                    if (n__ * RPS + u < HR) PIPE_READ1(n__ * RPS + u, buf, 4 + 2 * q + 1, Za, Zb)      \
+                if (FP4_ && n__ < HR) PIPE_READ_SCALE(n__, buf, 1, s1a, s1b)                           \
+            }                                                                                          \
+            /* group 1: piece 4+2q -> X (group 0 has consumed piece 2q) */                             \
+            if (g__ == 1) {                                                                            \
+                _Pragma("unroll") for (int u = 0; u < RPS; ++u)                                        \
+                    if (n__ * RPS + u < HR) PIPE_READ1(n__ * RPS + u, buf, 4 + 2 * q, Xa, Xb)          \
+            }                                                                                          \
+            if (k == A_AT) {                                                                           \
+                PIPE2_FENCE                                                                            \
+                __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0): this wave has read the whole stage */ \
+                __builtin_amdgcn_s_barrier();                                                          \
+                PIPE2_FENCE                                                                            \
+            }                                                                                          \
+            if (k > A_AT) {                                                                            \
+                const int l0__ = ((k - A_AT - 1) * NLD + LW - 1) / LW, l1__ = ((k - A_AT) * NLD + LW - 1) / LW; \
+                _Pragma("unroll") for (int u = 0; u < LPS; ++u)                                        \
+                    if (l0__ + u < l1__ && l0__ + u < NLD) PIPE2_LOAD(l0__ + u, buf)                   \
+            }                                                                                          \
+            if (k == B_AT) {                                                                           \
+                PIPE2_FENCE                                                                            \
+                wait_vmcnt<N_BEFORE_B>();                                                              \
+                __builtin_amdgcn_s_barrier();                                                          \
+                PIPE2_FENCE                                                                            \
+            }                                                                                          \
+            /* group 3: pieces 2q, 2q+1 of the next stage -> X, Y; its first scales -> S0 */           \
+            if (k > B_AT) {                                                                            \
+                _Pragma("unroll") for (int u = 0; u < RPS2; ++u) {                                     \
+                    const int rd__ = (k - B_AT - 1) * RPS2 + u;                                        \
+                    if (rd__ < HR) PIPE_READ1(rd__, buf ^ 1, 2 * q, Xa, Xb)                            \
+                    else if (rd__ < 2 * HR) PIPE_READ1(rd__ - HR, buf ^ 1, 2 * q + 1, Ya, Yb)          \
+                }                                                                                      \
+                if (k - B_AT - 1 < HR) PIPE_READ_SCALE(k - B_AT - 1, buf ^ 1, 0, s0a, s0b)             \
+            }                                                                                          \
+            PIPE2_FENCE                                                                                \
+        }                                                                                              \
+    }
+#define PIPE2_STAGE(FP4_)                                                                              \
+    {                                                                                                  \
+        PIPE2_GROUP(0, FP4_) PIPE2_GROUP(1, FP4_) PIPE2_GROUP(2, FP4_) PIPE2_GROUP(3, FP4_)            \
+        PIPE2_ADVANCE                                                                                  \
+        buf ^= 1;                                                                                      \
+    }
+
+#pragma unroll 1
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
+        // the load cursor is at stage 2 of this tile; it will cross into the next one (if any)
+        hasnext = ctile + step < last;
+        if (hasnext) PIPE2_TILE_POS(ctile + step, nm0, nn0)
+#pragma unroll 1
+        for (int T = 0; T < nTA; ++T) PIPE2_STAGE(1)
+#pragma unroll 1
+        for (int T = nTA; T < nT; ++T) PIPE2_STAGE(0)
+        const bool done = !hasnext;
+        if (done) wait_vmcnt<0>();  // the idle re-fetches of the last stage still target LDS
+        TilePos ctp;
+        PIPE2_TILE_POS(ctile, ctp.m0, ctp.n0)
+        ctp.row_begin = 0;
+        ctp.row_end = a.M;
+        ctp.wp = a.Wpack;
+        ctp.valid = true;
+        store_result<MODE_DUAL, TM, TN>(a, ctp, acc);
+        if (done) break;
+        ctile += step;
+    }
+#undef PIPE2_STAGE
+#undef PIPE2_GROUP
+#undef PIPE2_FENCE
+}
+
+template <int TM, int TN>
+static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
+    a.tiles_n = (int)((a.N + BN - 1) / BN);
+    int64_t tiles_m = (rows_total + BM - 1) / BM;
+    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs
+    const int64_t ntiles = tiles_m * a.tiles_n;
+    if (ntiles <= 0) return OSC_OK;
+    if (ntiles > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
+        ncu = n;
+    }
+    const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;  // workgroups that fit one CU's LDS
+    const int64_t grid = ntiles < (int64_t)ncu * per_cu ? ntiles : (int64_t)ncu * per_cu;
+    auto kern = gemm_pipe2_kernel<TM, TN>;
+    if (smem > 64 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), smem, st, a, (int)ntiles);
+    return check_launch("gemm_pipe2_kernel");
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Skinny kernel (dual path, M <= 64: decode batches).  The work is streaming the weights once,
+// so the grid is as wide as it can be without splitting the reduction over workgroups: one
+// workgroup per 32 output channels; its four wavefronts take the 128-byte lines of the
+// reduction axis in turn (FP4 lines, then bf16 branch lines) and never synchronise until the end:
+// each wavefront moves its lines global -> LDS with the DMA path into a strip of its own (whole
+// 128-byte lines per row, so every request is a full cache line), reads them back in the
+// matrix-core layout, and the four partial 32x32 results are summed through LDS in a fixed order.
+// Inside a line, lanes of block q take bytes [64q, 64q+64): four 16-byte pieces, one MFMA each,
+// and for FP4 exactly the four groups of scale word 2*line + q.
+// MT = number of 32-row tiles of X per workgroup (blockIdx.y selects the group of MT tiles).
+// ------------------------------------------------------------------------------------------
+template <int MT>
+__global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
+    constexpr int ROWS = 32 + 32 * MT;      // rows of a line image: 32 weight rows, then the X rows
+    constexpr int IMG = ROWS * 128;          // bytes of a line image
+    constexpr int NDMA = ROWS / 8;           // DMA instructions per line (8 rows each)
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];  // [4 waves][2 images], later the partial sums
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int q = lane >> 5, r = lane & 31;
+    const int n0 = blockIdx.x * 32;
+    const int mb = blockIdx.y * (32 * MT);  // first X row of this workgroup
+    const int Kg4 = ((a.K >> 5) + 3) >> 2;
+    const int rowbytes = a.K >> 1;
+    const int nL = rowbytes >> 7;
+    const int nLB = (a.K_o * 2 + 127) >> 7;
+    const int nLT = nL + nLB;
+    uint8_t* const strip = lds + wave * (2 * IMG);
+
+    // DMA instruction i moves rows 8i .. 8i+7 of the image: lane -> row 8i + lane/8, piece position
+    // lane%8, which holds piece (lane%8) ^ swz8(row) of the row
+    uint32_t o_fp4[NDMA], o_br[NDMA];  // byte offset of this lane's 16 bytes in line 0, per phase
+#pragma unroll
+    for (int i = 0; i < NDMA; ++i) {
+        const int row = 8 * i + (lane >> 3);
+        const uint32_t piece = (uint32_t)((lane & 7) ^ swz8(row)) * 16u;
+        if (row < 32) {
+            const uint32_t g = (uint32_t)min(n0 + row, a.N - 1);
+            o_fp4[i] = g * (uint32_t)rowbytes + piece;
+            o_br[i] = g * (uint32_t)a.wlpitch + piece;
+        } else {
+            const uint32_t g = (uint32_t)min(mb + row - 32, a.M - 1);
+            o_fp4[i] = g * (uint32_t)rowbytes + piece;
+            o_br[i] = g * (uint32_t)a.bpitch + piece;
+        }
+    }
+    const uint8_t* const wq = a.Wpack + a.off_q;
+    const uint8_t* const wl = a.Wpack + a.off_l;
+    // scale words of this lane's rows (weight row n0 + r, X rows 32m + r), word 2*line + q
+    const int rowB = min(n0 + r, a.N - 1);
+    const uint8_t* const ws = a.Wpack + a.off_s + (size_t)(rowB >> 5) * Kg4 * 128 + (rowB & 31) * 4 + q * 128;
+    const uint8_t* xs[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int rowA = min(mb + 32 * m + r, a.M - 1);
+        xs[m] = a.Xs + (size_t)(rowA >> 5) * Kg4 * 128 + (rowA & 31) * 4 + q * 128;
+    }
+    v16f acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[m][k] = 0.0f;
+
+    // line L of the whole sequence into image IMG_ of this wave's strip (nothing past the end)
+#define SKINNY_FETCH(L_, IMG_)                                                                          \
+    {                                                                                                   \
+        uint8_t* dst__ = strip + (IMG_)*IMG;                                                            \
+        if ((L_) < nL) {                                                                                \
+            _Pragma("unroll") for (int i = 0; i < NDMA; ++i)                                            \
+                load_to_lds16((i < 4 ? wq : a.Xq) + ((size_t)(L_)*128 + o_fp4[i]), dst__ + i * 1024);   \
+        } else if ((L_) < nLT) {                                                                        \
+            _Pragma("unroll") for (int i = 0; i < NDMA; ++i)                                            \
+                load_to_lds16((i < 4 ? wl : a.B) + ((size_t)((L_)-nL) * 128 + o_br[i]), dst__ + i * 1024); \
+        }                                                                                               \
+    }
+    // consume line L from image IMG_
+#define SKINNY_COMPUTE(L_, IMG_)                                                                        \
+    {                                                                                                   \
+        const uint8_t* src__ = strip + (IMG_)*IMG;                                                      \
+        u32x4 fb__[4], fx__[MT][4];                                                                     \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+            fb__[i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(r, 4 * q + i));                 \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
+                fx__[m][i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(32 + 32 * m + r, 4 * q + i)); \
+        }                                                                                               \
+        if ((L_) < nL) {                                                                                \
+            const int sb__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*256);                      \
+            int sx__[MT];                                                                               \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
+                sx__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*256);                      \
+            SKINNY_FP4(0) SKINNY_FP4(1) SKINNY_FP4(2) SKINNY_FP4(3)                                     \
+        } else {                                                                                        \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
+                _Pragma("unroll") for (int m = 0; m < MT; ++m)                                          \
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fx__[m][i]), \
+                                                                     __builtin_bit_cast(v8bf, fb__[i]), acc[m], 0, 0, 0); \
+        }                                                                                               \
+    }
+#define SKINNY_FP4(I_)                                                                                  \
+    {                                                                                                   \
+        const v8i bv__ = {(int)fb__[I_].x, (int)fb__[I_].y, (int)fb__[I_].z, (int)fb__[I_].w, 0, 0, 0, 0}; \
+        _Pragma("unroll") for (int m = 0; m < MT; ++m) {                                                \
+            const v8i av__ = {(int)fx__[m][I_].x, (int)fx__[m][I_].y, (int)fx__[m][I_].z, (int)fx__[m][I_].w, 0, 0, 0, 0}; \
+            acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 4, 4, I_, sx__[m], I_, sb__); \
+        }                                                                                               \
+    }
+    // lines wave, wave+4, ...; the next line is in flight while one is consumed.  Everything a wave
+    // reads from LDS it wrote itself, so "my loads have landed" is all the synchronisation needed.
+    int L = wave, img = 0;
+    SKINNY_FETCH(L, 0)
+#pragma unroll 1
+    for (; L < nLT; L += 4) {
+        SKINNY_FETCH(L + 4, img ^ 1)
+        if (L + 4 < nLT) wait_vmcnt<NDMA>(); else wait_vmcnt<0>();
+        SKINNY_COMPUTE(L, img)
+        img ^= 1;
+    }
+#undef SKINNY_FP4
+#undef SKINNY_COMPUTE
+#undef SKINNY_FETCH
+
+    // ---- sum the four partial results in a fixed order, store -----------------------------------
+    __syncthreads();  // every wave is done with its strip
+    float* const red = reinterpret_cast<float*>(lds);  // [4 waves][MT][16][64]
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) red[((wave * MT + m) * 16 + k) * 64 + lane] = acc[m][k];
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = 4 * wave + i;  // result register k of lane (q, r): row 8*(k/4) + 4q + k%4, column r
+            float v = red[((0 * MT + m) * 16 + k) * 64 + lane];
+            v += red[((1 * MT + m) * 16 + k) * 64 + lane];
+            v += red[((2 * MT + m) * 16 + k) * 64 + lane];
+            v += red[((3 * MT + m) * 16 + k) * 64 + lane];
+            const int row = mb + 32 * m + 8 * wave + 4 * q + i, col = n0 + r;
+            if (row < a.M && col < a.N) {
+                if (a.y_bf16)
+                    reinterpret_cast<uint16_t*>(a.Y)[(int64_t)row * a.ldy + col] = f32_to_bf16_rne(v);
+                else
+                    reinterpret_cast<float*>(a.Y)[(int64_t)row * a.ldy + col] = v;
+            }
+        }
+    }
+}
+
+static int launch_skinny(KArgs a, hipStream_t st) {
+    const int64_t grid = (a.N + 31) / 32;
+    if (grid <= 0) return OSC_OK;
+    // LDS: four strips of two line images (64 KB, two workgroups per CU); the partial sums reuse
+    // the space.  33..64 rows: two workgroups per 32 output channels, one per 32-row tile of X (the
+    // second pass over a weight row is an L2 hit; one workgroup with both tiles would need 96 KB).
+    const unsigned mtiles = a.M <= 32 ? 1u : 2u;
+    hipLaunchKernelGGL(gemm_skinny_kernel<1>, dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
+    return check_launch("gemm_skinny_kernel");
+}
+
 template <int MODE, int TM, int TN, bool RAGGED>
 static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const size_t smem = (size_t)(BM + BN) * 64 * 3;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
-    if (grouped) tiles_m += a.E;  // upper bound: every expert may add one ragged tile
+    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs  // upper bound: every expert may add one ragged tile
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
@@ -774,7 +1337,7 @@ static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st
     const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
-    if (grouped) tiles_m += a.E;
+    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
@@ -843,13 +1406,41 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
                        (MODE != MODE_DUAL || p.K_o == 0 || a.bpitch % 128 == 0);
     const bool ragged = rowbytes % 64 != 0 || (MODE == MODE_DUAL && p.K_o > 0 && a.bpitch % 64 != 0);
     int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : 2;
-    int kind = (lines && tm > 1) ? 1 : 0;  // 1 = DMA kernel
+    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
+    // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
+    // past the last whole tile go to a second launch of the DMA kernel
+    const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
+                         (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
+    if (kind == 1 && pipe_ok && tm == 4) kind = 2;
+    if (pipe_ok && p.M >= 1 && p.M <= 64) kind = 3;  // decode-sized problems: the weight-streaming kernel
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
-        if (sscanf(ov, "%d,%d", &tm, &k2) == 2 && k2 == 1 && !(lines && tm > 1)) k2 = 0;
+        if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
+            if (tm != 1 && tm != 2 && tm != 4) tm = 2;
+            if ((k2 == 1 || k2 == 2) && !(lines && tm > 1)) k2 = 0;
+            if (k2 == 2 && !pipe_ok) k2 = 1;
+            if (k2 == 3 && !(pipe_ok && p.M >= 1 && p.M <= 64)) k2 = 0;
+        }
         kind = k2;
     }
-    if (kind == 1) {
+    if (kind == 3) return launch_skinny(a, st);
+    if (kind == 2 && p.N % (64 * tm) == 0 && p.M >= 64 * tm) {
+        const int64_t m_full = p.M / (64 * tm) * (64 * tm);
+        if (m_full < p.M) {  // ragged tail: rows m_full .. M-1 as a problem of their own
+            GemmProblem tail = p;
+            tail.M = p.M - m_full;
+            tail.Xq = p.Xq + m_full * rowbytes;
+            tail.Xs = p.Xs + (m_full / 32) * ((p.K / 32 + 3) / 4) * 128;
+            tail.B = p.B ? p.B + m_full * p.ldb : nullptr;
+            tail.Y = static_cast<uint8_t*>(p.Y) + m_full * p.ldy * (p.y_dtype == OSC_DT_BF16 ? 2 : 4);
+            const int rc = launch_gemm<MODE>(tail, st);
+            if (rc != OSC_OK) return rc;
+        }
+        a.M = (int)m_full;
+        if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
+        return launch_pipe2<2, 2>(a, m_full, grouped, st);
+    }
+    if (kind >= 1) {
         if (tm == 4) return launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
         return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
     }

@@ -1152,7 +1152,7 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
 
 
 // ------------------------------------------------------------------------------------------
-// Skinny kernel (dual path, M <= 64: decode batches).  The work is streaming the weights once,
+// Skinny kernel (M <= 64: decode batches), dual path and FP8.  The work is streaming the weights once,
 // so the grid is as wide as it can be without splitting the reduction over workgroups: one
 // workgroup per 32 output channels; its four wavefronts take the 128-byte lines of the
 // reduction axis in turn (FP4 lines, then bf16 branch lines) and never synchronise until the end:
@@ -1163,7 +1163,7 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
 // and for FP4 exactly the four groups of scale word 2*line + q.
 // MT = number of 32-row tiles of X per workgroup (blockIdx.y selects the group of MT tiles).
 // ------------------------------------------------------------------------------------------
-template <int MT>
+template <int MODE, int MT>
 __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
     constexpr int ROWS = 32 + 32 * MT;      // rows of a line image: 32 weight rows, then the X rows
     constexpr int IMG = ROWS * 128;          // bytes of a line image
@@ -1174,9 +1174,9 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
     const int n0 = blockIdx.x * 32;
     const int mb = blockIdx.y * (32 * MT);  // first X row of this workgroup
     const int Kg4 = ((a.K >> 5) + 3) >> 2;
-    const int rowbytes = a.K >> 1;
+    const int rowbytes = (MODE == MODE_DUAL) ? (a.K >> 1) : a.K;
     const int nL = rowbytes >> 7;
-    const int nLB = (a.K_o * 2 + 127) >> 7;
+    const int nLB = (MODE == MODE_DUAL) ? ((a.K_o * 2 + 127) >> 7) : 0;
     const int nLT = nL + nLB;
     uint8_t* const strip = lds + wave * (2 * IMG);
 
@@ -1236,7 +1236,18 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
             _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
                 fx__[m][i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(32 + 32 * m + r, 4 * q + i)); \
         }                                                                                               \
-        if ((L_) < nL) {                                                                                \
+        if (MODE == MODE_FP8) {                                                                         \
+            /* 128 channels = two MFMAs: pieces 4q, 4q+1 and 4q+2, 4q+3 */                              \
+            _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                             \
+                const v8i bv__ = {(int)fb__[2 * h].x, (int)fb__[2 * h].y, (int)fb__[2 * h].z, (int)fb__[2 * h].w, \
+                                  (int)fb__[2 * h + 1].x, (int)fb__[2 * h + 1].y, (int)fb__[2 * h + 1].z, (int)fb__[2 * h + 1].w}; \
+                _Pragma("unroll") for (int m = 0; m < MT; ++m) {                                        \
+                    const v8i av__ = {(int)fx__[m][2 * h].x, (int)fx__[m][2 * h].y, (int)fx__[m][2 * h].z, (int)fx__[m][2 * h].w, \
+                                      (int)fx__[m][2 * h + 1].x, (int)fx__[m][2 * h + 1].y, (int)fx__[m][2 * h + 1].z, (int)fx__[m][2 * h + 1].w}; \
+                    acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f); \
+                }                                                                                       \
+            }                                                                                           \
+        } else if ((L_) < nL) {                                                                         \
             const int sb__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*256);                      \
             int sx__[MT];                                                                               \
             _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
@@ -1290,6 +1301,8 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
             v += red[((2 * MT + m) * 16 + k) * 64 + lane];
             v += red[((3 * MT + m) * 16 + k) * 64 + lane];
             const int row = mb + 32 * m + 8 * wave + 4 * q + i, col = n0 + r;
+            if (MODE == MODE_FP8)  // per-token and per-channel scales
+                v *= a.xs[min(row, a.M - 1)] * reinterpret_cast<const float*>(a.Wpack + a.off_s)[min(col, a.N - 1)];
             if (row < a.M && col < a.N) {
                 if (a.y_bf16)
                     reinterpret_cast<uint16_t*>(a.Y)[(int64_t)row * a.ldy + col] = f32_to_bf16_rne(v);
@@ -1300,6 +1313,7 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
     }
 }
 
+template <int MODE>
 static int launch_skinny(KArgs a, hipStream_t st) {
     const int64_t grid = (a.N + 31) / 32;
     if (grid <= 0) return OSC_OK;
@@ -1307,7 +1321,7 @@ static int launch_skinny(KArgs a, hipStream_t st) {
     // the space.  33..64 rows: two workgroups per 32 output channels, one per 32-row tile of X (the
     // second pass over a weight row is an L2 hit; one workgroup with both tiles would need 96 KB).
     const unsigned mtiles = a.M <= 32 ? 1u : 2u;
-    hipLaunchKernelGGL(gemm_skinny_kernel<1>, dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1>), dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
     return check_launch("gemm_skinny_kernel");
 }
 
@@ -1412,18 +1426,19 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
     if (kind == 1 && pipe_ok && tm == 4) kind = 2;
-    if (pipe_ok && p.M >= 1 && p.M <= 64) kind = 3;  // decode-sized problems: the weight-streaming kernel
+    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && p.M <= 64;
+    if (skinny_ok) kind = 3;  // decode-sized problems: the weight-streaming kernel
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
         if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
             if (tm != 1 && tm != 2 && tm != 4) tm = 2;
             if ((k2 == 1 || k2 == 2) && !(lines && tm > 1)) k2 = 0;
             if (k2 == 2 && !pipe_ok) k2 = 1;
-            if (k2 == 3 && !(pipe_ok && p.M >= 1 && p.M <= 64)) k2 = 0;
+            if (k2 == 3 && !skinny_ok) k2 = 0;
         }
         kind = k2;
     }
-    if (kind == 3) return launch_skinny(a, st);
+    if (kind == 3) return launch_skinny<MODE>(a, st);
     if (kind == 2 && p.N % (64 * tm) == 0 && p.M >= 64 * tm) {
         const int64_t m_full = p.M / (64 * tm) * (64 * tm);
         if (m_full < p.M) {  // ragged tail: rows m_full .. M-1 as a problem of their own

@@ -17,13 +17,16 @@
 // bytes [32q, 32q+32) of the 64-byte step, i.e. 16-byte pieces 2q and 2q+1, and piece I feeds
 // MFMA I; the FP4 scale word is shifted right by 16q bits so that byte I is the scale of piece I.
 //
-// Data path.  global --16-byte loads--> registers --ds_write_b128--> LDS --ds_read_b128--> MFMA.
-// (The direct global->LDS path of gfx950 was measured at half the throughput of plain loads for
-// data that misses L2, and this kernel lives on L2 misses served by the Infinity Cache.)  Loads
-// for step s+2 are issued during step s and rest in registers for more than a step; they are
-// written to LDS late in step s+1, into one of three stages; one barrier per step.  Loads, LDS
-// writes and LDS reads are spread between the MFMAs of a step.  Rows past the end of an operand
-// and pieces past the end of a row are zero-filled in registers, so any legal shape runs here.
+// Four kernels share these conventions; the host picks one per call (launch_gemm):
+//   gemm_kernel        register-staged (global -> VGPR -> LDS -> MFMA), 64-byte steps, any legal
+//                      shape (ragged rows through a block of zeros), grouped and row-mapped problems;
+//   gemm_dma2_kernel   global -> LDS by DMA in whole 128-byte lines, two LDS stages; dual path and
+//                      FP8, grouped and row-mapped problems; needs 128-byte row pitches;
+//   gemm_pipe2_kernel  the same data path, persistent workgroups, slot-pinned instruction order,
+//                      early buffer release; dual path, one problem of whole 256x256 tiles (a ragged
+//                      row tail goes to the DMA kernel);
+//   gemm_skinny_kernel M <= 64 (decode): one workgroup per 32 output channels streams the weights
+//                      once, its wavefronts split the reduction axis.
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
@@ -38,6 +41,7 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef float v2f __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int GT = 256;  // 4 wavefronts, arranged 2 x 2 over the workgroup tile
 enum { MODE_DUAL = 0, MODE_FP8 = 1 };
@@ -175,8 +179,11 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
     const float* wsc = (MODE == MODE_FP8) ? reinterpret_cast<const float*>(wp + a.off_s) : nullptr;
     const int odd = r & 1;
     const int wu_m = __builtin_amdgcn_readfirstlane(wm), wu_n = __builtin_amdgcn_readfirstlane(wn);
-    // byte offset of this lane's pair inside a 32x32 result tile: row 4q + odd, columns r - odd, r - odd + 1
-    const uint32_t yoff = 2u * (uint32_t)((4 * q + odd) * (int)a.ldy + r - odd);
+    // byte offset of this lane's four columns inside a 32x32 result tile: row 4q + r%4, columns 4(r/4) ..
+    const uint32_t yoff8 = 2u * (uint32_t)((4 * q + (r & 3)) * (int)a.ldy + (r & ~3));
+    const bool hi2 = (r & 2) != 0;
+    // byte selector of step 2: even lanes [own.lo, other.lo], odd lanes [other.hi, own.hi]
+    const uint32_t sel12 = odd ? 0x03020706u : 0x05040100u;
     auto store_tile = [&](auto kind_tag) __attribute__((always_inline)) {
         // 2: tile entirely inside Y, no bounds tests; 1: all columns inside, rows tested (ragged
         // last tile of a problem or an expert); 0: everything tested, 2-byte stores
@@ -203,20 +210,35 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
                 for (int k = 0; k < 16; ++k)
                     v[k] = (MODE == MODE_FP8) ? acc[i][j][k] * (xr[k] * cs) : acc[i][j][k];
                 if (a.y_bf16 && KIND >= 1) {
-                    // whole tile, 4-byte stores: uniform base per (tile, register pair) + one per-lane offset;
-                    // the pair is rounded to bf16 (nearest even) by one packed conversion
+                    // 8-byte stores: two rounds of exchanges inside each quad of lanes turn "one column,
+                    // sixteen rows per lane" into "four adjacent columns of one row per lane".
+                    //  1. pairs of result registers (rows R, R+1 of column c) are rounded to packed bf16;
+                    //  2. lanes c, c^1 swap halves: even lanes get row R, odd lanes row R+1, columns c&~1, +1;
+                    //  3. lanes l, l^2 swap words of register pairs (k, k+2): lanes 0,1 of a quad complete
+                    //     rows R, R+1, lanes 2,3 rows R+2, R+3, columns 4b .. 4b+3.
+                    // Each step runs over all registers of the tile before the next one starts, so the
+                    // single wavefront of a SIMD always has independent instructions to issue.
                     uint8_t* const ybase = reinterpret_cast<uint8_t*>(a.Y) +
                         2 * ((int64_t)(m0 + wu_m * (TM * 32) + i * 32) * a.ldy + n0 + wu_n * (TN * 32) + j * 32);
+                    uint32_t P[8], W[8];
 #pragma unroll
-                    for (int k = 0; k < 16; k += 2) {
-                        const float send = odd ? v[k] : v[k + 1];
-                        const float recv = __builtin_bit_cast(
-                            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, false));
-                        const v2f pair = {odd ? recv : v[k], odd ? v[k + 1] : recv};
-                        const uint32_t word = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, v2bf));
-                        uint8_t* const kbase = ybase + 2 * (int64_t)(8 * (k >> 2) + (k & 3)) * a.ldy;
-                        if (FULL || rbase + 8 * (k >> 2) + (k & 3) + odd < row_end)
-                            *reinterpret_cast<uint32_t*>(kbase + yoff) = word;
+                    for (int k = 0; k < 8; ++k) {
+                        const v2f pair = {v[2 * k], v[2 * k + 1]};
+                        P[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, v2bf));
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const uint32_t Q = (uint32_t)__builtin_amdgcn_update_dpp((int)P[k], (int)P[k], 0xB1, 0xF, 0xF, false);
+                        W[k] = __builtin_amdgcn_perm(Q, P[k], sel12);
+                    }
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        const uint32_t send = hi2 ? W[2 * h] : W[2 * h + 1];
+                        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp((int)send, (int)send, 0x4E, 0xF, 0xF, false);
+                        const u32x2 out = {hi2 ? recv : W[2 * h], hi2 ? W[2 * h + 1] : recv};
+                        uint8_t* const hbase = ybase + 2 * (int64_t)(8 * h) * a.ldy;
+                        if (FULL || rbase + 8 * h + (r & 3) < row_end)
+                            __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(hbase + yoff8));
                     }
                 } else if (a.y_bf16) {
                     uint16_t* Y = reinterpret_cast<uint16_t*>(a.Y);
@@ -250,7 +272,7 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
     };
     // 32-bit stores of bf16 pairs need an even leading dimension and a 4-byte aligned Y
     const bool cols = (n0 + BN <= a.N) &&
-                      (!a.y_bf16 || (((a.ldy & 1) == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 3) == 0)));
+                      (!a.y_bf16 || (((a.ldy & 3) == 0) && ((reinterpret_cast<uintptr_t>(a.Y) & 7) == 0)));
     if (cols && m0 + BM <= row_end)
         store_tile(std::integral_constant<int, 2>{});
     else if (cols)
@@ -1411,10 +1433,11 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         return fail(OSC_ERR_UNSUPPORTED, "gemm: an operand of 4 GiB or more");
     const int64_t rows = grouped && p.E > 0 ? (p.M + p.E - 1) / p.E : p.M;  // rows per problem
     // Kernel and tile choice.
-    //  - operand rows that are whole 128-byte lines: the DMA kernel; 256x256 tiles when they give
-    //    every CU at least one tile, else 128x128;
-    //  - short problems (<= 64 rows) and everything else: the staged kernel, 64x128 or 128x128
-    //    tiles, with per-lane zero fill when rows are not whole 64-byte steps.
+    //  - operand rows that are whole 128-byte lines: M <= 64 -> the skinny kernel; else 256x256 tiles
+    //    when they give every CU at least one tile (dual path, one problem: the persistent kernel;
+    //    otherwise the DMA kernel), else the DMA kernel with 128x128 tiles;
+    //  - everything else: the staged kernel, 64x128 or 128x128 tiles, with per-lane zero fill when
+    //    rows are not whole 64-byte steps.
     const int64_t t256 = ((rows + 255) / 256) * ((p.N + 255) / 256) * (grouped ? p.E : 1);
     const bool lines = rowbytes > 0 && rowbytes % 128 == 0 &&
                        (MODE != MODE_DUAL || p.K_o == 0 || a.bpitch % 128 == 0);

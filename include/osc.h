@@ -69,7 +69,9 @@ int osc_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oid
  *   oidx   int32 [K_o] ascending protected channel ids (device; may be NULL iff K_o == 0)
  *   Wpack  osc_packed_weight_bytes(N, K, K_o) bytes, 256-byte aligned; receives the
  *          MXFP4 codes and E8M0 scales of every row of W (nothing zeroed) and
- *          W_L[o][n] = W[n][oidx[o]] in the layout the GEMM kernels read.
+ *          W_L[o][n] = W[n][oidx[o]] in the layout the GEMM kernels read, followed by
+ *          256 bytes of zeros (what the kernels read in place of anything past the
+ *          end of an operand row).  Opaque: use osc_unpack_weight to look inside.
  * osc_unpack_weight writes the plain forms back out: Wq uint8 [N, K/2]
  * (channel 2i in bits 3:0 of byte i, 2i+1 in bits 7:4), Ws uint8 [N, K/32]
  * (E8M0, plain row-major), WL bf16 [K_o, N]; any of the three may be NULL to skip it.
@@ -104,8 +106,9 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  * floor(log2(amax)) - 2 (code 0 when amax is zero or below 2^-124) and E2M1
  * elements rounded to nearest, ties to even, saturating at +-6; an element's sign
  * bit is kept even when it rounds to zero.
- *   X     bf16 [M, ldx], ldx >= K, K % 32 == 0, 16-byte aligned rows (ldx % 8 == 0)
- *   oidx  int32 [K_o], ascending, distinct, each in [0, K); NULL iff K_o == 0
+ *   X     bf16 [M, ldx], ldx >= K, K % 32 == 0, K <= 65536, 16-byte aligned rows (ldx % 8 == 0)
+ *   oidx  int32 [K_o], ascending, distinct, each in [0, K) (as osc_table_to_index writes
+ *         it; the contents are not checked on the device); NULL iff K_o == 0
  *   Xq    uint8 [M, K/2]   channel 2i -> bits 3:0 of byte i, 2i+1 -> bits 7:4
  *   Xs    E8M0 codes, row-block-major, osc_act_scale_bytes(M, K) bytes, 4-byte aligned
  *   B     bf16 [M, ldb], ldb >= K_o, ldb % 8 == 0; columns K_o..ldb-1 are set to +0.
@@ -142,7 +145,10 @@ int osc_unpack_act_scales(const uint8_t *Xs, int64_t M, int64_t K, uint8_t *out,
  *   Xq, Xs, B, ldb   as written by osc_quantize_act(fmt = MXFP4_OSC) with the same K, K_o
  *   Wpack            from osc_pack_weight with the same N, K, K_o
  *   Y                [M, ldy] of y_dtype, ldy >= N
- * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (y_dtype, ldb % 8), OSC_ERR_HIP.
+ * Limits: every operand (Xq, Xs, B, one packed weight) must be smaller than 4 GiB
+ * (OSC_ERR_UNSUPPORTED otherwise).  Results do not depend on which kernel the library
+ * picks for a shape and are identical from run to run.
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (y_dtype, ldb % 8, size), OSC_ERR_HIP.
  */
 int osc_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, int64_t ldb,
                   const void *Wpack, int64_t M, int64_t N, int64_t K, int32_t K_o, void *Y,

@@ -85,6 +85,20 @@ def test_config2_attention_m8192(osc):
             dual_sampled(osc, qd, qr, Wp, wr, N, K, 256, rows[:16], osc.OSC_DT_F32, f"cfg2 N={N} f32")
 
 
+def test_persistent_kernel_with_ragged_row_tail(osc):
+    """M is not a multiple of the 256-row tile: the whole tiles and the tail rows go to different
+    kernels; rows on both sides of the seam and the last rows are checked."""
+    M, K, N = 8192 + 100, 4096, 4096
+    X, table = wl.activations_persistent(2001, M, K, 2)
+    oidx = oracle.table_to_index(table)
+    qd, qr = quant_full(osc, X, oidx)
+    W = wl.weights(2100, N, K)
+    Wp, wr = pack_full(osc, W, oidx)
+    rows = np.array([0, 255, 256, 4095, 8190, 8191, 8192, 8193, 8255, 8256, 8290, 8291], np.int64)
+    dual_sampled(osc, qd, qr, Wp, wr, N, K, 256, rows, osc.OSC_DT_BF16, "ragged tail bf16")
+    dual_sampled(osc, qd, qr, Wp, wr, N, K, 256, rows, osc.OSC_DT_F32, "ragged tail f32")
+
+
 @pytest.mark.parametrize("M", [1, 16, 128, 2048])
 def test_config2_attention_small_m(osc, M):
     K = 4096

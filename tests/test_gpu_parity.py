@@ -201,7 +201,8 @@ def test_dual_gemm_all_channels_is_bf16_gemm(osc):
 
 @pytest.mark.parametrize("M,N,K,r", [(1, 256, 4096, 2), (16, 1024, 4096, 2), (128, 512, 4096, 2),
                                      (200, 384, 2048, 1), (129, 130, 256, 1), (70, 1000, 96, 1),
-                                     (257, 136, 4096, 4), (64, 128, 512, 0), (300, 300, 1536, 3)])
+                                     (257, 136, 4096, 4), (64, 128, 512, 0), (300, 300, 1536, 3),
+                                     (40, 200, 512, 2), (33, 96, 256, 1), (64, 72, 768, 4), (5, 40, 256, 0)])
 def test_dual_gemm_shapes(osc, M, N, K, r):
     X, table = wl.activations_persistent(1000 + M + N, M, K, r)
     W = wl.weights(2000 + N + K, N, K)

@@ -63,6 +63,10 @@ struct KArgs {
     int y_bf16;
     int64_t ldy;
     int tiles_n;
+    // grouped problems, which rows of an expert this launch covers: 0 = all of them; 1 = its first
+    // (n + BM/2) / BM tiles (an expert whose last tile would be less than half full leaves those rows
+    // out); 2 = the rows that a mode-1 launch with tiles of grp_bm rows left out
+    int grp_mode, grp_bm;
 };
 
 // 16-byte piece `c` (0..7) of row `r` sits at piece c ^ swz(r): lanes of one LDS access
@@ -122,8 +126,15 @@ __device__ __forceinline__ TilePos tile_at(const KArgs& a, int tile) {
         int before = 0, e_found = -1, j_in = 0;
         for (int e0 = 0; e0 < a.E; e0 += 64) {
             const int e = e0 + lane;
-            const int b = e < a.E ? a.off[e] : 0;
-            const int n = e < a.E ? a.off[e + 1] - b : 0;
+            int b = e < a.E ? a.off[e] : 0;
+            int n = e < a.E ? a.off[e + 1] - b : 0;
+            if (a.grp_mode == 1) {
+                n = min(n, (n + BM / 2) / BM * BM);
+            } else if (a.grp_mode == 2) {
+                const int skip = min(n, (n + a.grp_bm / 2) / a.grp_bm * a.grp_bm);
+                b += skip;
+                n -= skip;
+            }
             const int te = (n + BM - 1) / BM;
             int ps = te;
 #pragma unroll
@@ -1148,7 +1159,11 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
     const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
-    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs
+    if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
+        if (a.grp_mode == 2) tiles_m = (int64_t)a.E * ((a.grp_bm / 2 + BM - 1) / BM);  // less than half a main tile each
+        else tiles_m += a.E;                                                          // one ragged tile each
+        tiles_m = (tiles_m + 7) / 8 * 8;
+    }
     const int64_t ntiles = tiles_m * a.tiles_n;
     if (ntiles <= 0) return OSC_OK;
     if (ntiles > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
@@ -1353,7 +1368,11 @@ static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st)
     const size_t smem = (size_t)(BM + BN) * 64 * 3;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
-    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs  // upper bound: every expert may add one ragged tile
+    if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
+        if (a.grp_mode == 2) tiles_m = (int64_t)a.E * ((a.grp_bm / 2 + BM - 1) / BM);  // less than half a main tile each
+        else tiles_m += a.E;                                                          // one ragged tile each
+        tiles_m = (tiles_m + 7) / 8 * 8;
+    }
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
@@ -1373,7 +1392,11 @@ static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st
     const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
-    if (grouped) tiles_m = (tiles_m + a.E + 7) / 8 * 8;  // upper bound, whole rounds of the 8 XCDs
+    if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
+        if (a.grp_mode == 2) tiles_m = (int64_t)a.E * ((a.grp_bm / 2 + BM - 1) / BM);  // less than half a main tile each
+        else tiles_m += a.E;                                                          // one ragged tile each
+        tiles_m = (tiles_m + 7) / 8 * 8;
+    }
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
@@ -1423,6 +1446,8 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     a.y_bf16 = p.y_dtype == OSC_DT_BF16;
     a.ldy = p.ldy;
     a.tiles_n = 0;
+    a.grp_mode = 0;
+    a.grp_bm = 0;
     const bool grouped = p.expert_offsets != nullptr;
     const int64_t rowbytes = (MODE == MODE_DUAL) ? p.K / 2 : p.K;
     // the kernel addresses operand rows through 32-bit byte offsets (with a row_map the caller
@@ -1477,6 +1502,18 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         a.M = (int)m_full;
         if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
         return launch_pipe2<2, 2>(a, m_full, grouped, st);
+    }
+    if (kind >= 1 && grouped && tm == 4) {
+        // experts in 256-row tiles, and what is left of an expert whose last tile would be less than
+        // half full in 64-row tiles (an expert of 270 rows: one big tile and one small one, not two
+        // big ones)
+        a.grp_mode = 1;
+        const int rc = launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
+        if (rc != OSC_OK) return rc;
+        a.grp_mode = 2;
+        a.grp_bm = 256;
+        return ragged ? launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st)
+                      : launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
     }
     if (kind >= 1) {
         if (tm == 4) return launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);

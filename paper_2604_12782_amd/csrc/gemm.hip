@@ -239,14 +239,16 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
                     }
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        const uint32_t Q = (uint32_t)__builtin_amdgcn_update_dpp((int)P[k], (int)P[k], 0xB1, 0xF, 0xF, false);
+                        const uint32_t Q = (uint32_t)__builtin_amdgcn_mov_dpp((int)P[k], 0xB1, 0xF, 0xF, true);
                         W[k] = __builtin_amdgcn_perm(Q, P[k], sel12);
                     }
 #pragma unroll
                     for (int h = 0; h < 4; ++h) {
-                        const uint32_t send = hi2 ? W[2 * h] : W[2 * h + 1];
-                        const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp((int)send, (int)send, 0x4E, 0xF, 0xF, false);
-                        const u32x2 out = {hi2 ? recv : W[2 * h], hi2 ? W[2 * h + 1] : recv};
+                        // both words cross to lane l^2; each lane keeps one of its own and one of the other's
+                        // (every crossing has a single use, so it folds into the select that consumes it)
+                        const uint32_t ra = (uint32_t)__builtin_amdgcn_mov_dpp((int)W[2 * h], 0x4E, 0xF, 0xF, true);
+                        const uint32_t rb = (uint32_t)__builtin_amdgcn_mov_dpp((int)W[2 * h + 1], 0x4E, 0xF, 0xF, true);
+                        const u32x2 out = {hi2 ? rb : W[2 * h], hi2 ? W[2 * h + 1] : ra};
                         uint8_t* const hbase = ybase + 2 * (int64_t)(8 * h) * a.ldy;
                         if (FULL || rbase + 8 * h + (r & 3) < row_end)
                             __builtin_nontemporal_store(out, reinterpret_cast<u32x2*>(hbase + yoff8));

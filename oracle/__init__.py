@@ -38,6 +38,7 @@ def lib():
         _lib.ref_e2m1_decode.argtypes = [C.c_int]
         _lib.ref_e2m1_encode.argtypes = [C.c_double, C.c_int]
         _lib.ref_e8m0_code_for_amax.argtypes = [C.c_double]
+        _lib.ref_e8m0_code_for_amax_e4m3.argtypes = [C.c_double]
         _lib.ref_e4m3_decode.restype = C.c_double
         _lib.ref_e4m3_decode.argtypes = [C.c_int]
         _lib.ref_e4m3_encode.argtypes = [C.c_float]
@@ -80,6 +81,11 @@ def e2m1_encode(v, negative=None):
 
 def e8m0_code_for_amax(amax):
     return lib().ref_e8m0_code_for_amax(float(amax))
+
+
+def e8m0_code_for_amax_e4m3(amax):
+    """E8M0 code of an MXFP8 (E4M3 elements) block whose largest magnitude is amax."""
+    return lib().ref_e8m0_code_for_amax_e4m3(float(amax))
 
 
 def e4m3_decode(code):
@@ -145,6 +151,16 @@ def quantize_fp8_rows(X):
     return X8, xs
 
 
+def quantize_mxfp8(X):
+    """X uint16[M, K] -> (Xq uint8[M, K] e4m3 codes, Xs uint8[M, K/32] E8M0 codes)."""
+    X = _c(X, np.uint16)
+    M, K = X.shape
+    Xq = np.empty((M, K), np.uint8)
+    Xs = np.empty((M, K // 32), np.uint8)
+    _check(lib().ref_quantize_mxfp8(_p(X), i64(M), i64(K), i64(K), _p(Xq), _p(Xs)), "ref_quantize_mxfp8")
+    return Xq, Xs
+
+
 # ---- GEMMs -------------------------------------------------------------------
 
 
@@ -197,6 +213,17 @@ def fp8_gemm(X8, xs, W8, ws):
     Y = np.empty((M, N), np.float64)
     _check(lib().ref_fp8_gemm(_p(X8), _p(xs), _p(W8), _p(ws), i64(M), i64(N), i64(K), _p(Y),
                               i64(N)), "ref_fp8_gemm")
+    return Y
+
+
+def mxfp8_gemm(Xq, Xs, Wq, Ws):
+    Xq, Xs, Wq, Ws = (_c(a, np.uint8) for a in (Xq, Xs, Wq, Ws))
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    assert Wq.shape[1] == K and Xs.shape == (M, K // 32) and Ws.shape == (N, K // 32)
+    Y = np.empty((M, N), np.float64)
+    _check(lib().ref_mxfp8_gemm(_p(Xq), _p(Xs), _p(Wq), _p(Ws), i64(M), i64(N), i64(K), _p(Y), i64(N)),
+           "ref_mxfp8_gemm")
     return Y
 
 

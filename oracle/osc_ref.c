@@ -24,6 +24,14 @@
  *   ref_fp8_gemm            the W8A8 linear layer on those operands
  *   ref_grouped_*           the same two GEMMs for E independent experts
  *                           (MoE model of Section 4.1)
+ *   ref_quantize_mxfp8      the 8-bit micro-scaling form of the fallback
+ *                           (Section 3.4 "or equivalent 8-bit micro-scaling
+ *                           formats"; Section 4.1 implementation details:
+ *                           MXFP8 for the W_2 inputs), read as OCP MX v1.0
+ *                           MXFP8 with E4M3 elements: one E8M0 scale per 32
+ *                           elements, shared exponent floor(log2 amax) - 8,
+ *                           elements rounded to nearest even, saturating
+ *   ref_mxfp8_gemm          the linear layer on two MXFP8 operands
  *
  * Floating point: every GEMM accumulates in double.  The FP8 quantiser's
  * scale arithmetic is IEEE single precision (one division, one multiply),
@@ -84,19 +92,22 @@ static int e2m1_nearest_mag_code(double a) {
     return best;
 }
 
-/* Shared exponent of one MX block: floor(log2(amax)) - emax(E2M1), emax = 2,
- * clamped to the E8M0 range [-127, 127]; amax == 0 takes the lower clamp. */
-static int mx_shared_exponent(double amax) {
+/* Shared exponent of one MX block: floor(log2(amax)) - emax of the element
+ * format (2 for E2M1, 8 for E4M3), clamped to the E8M0 range [-127, 127];
+ * amax == 0 takes the lower clamp. */
+static int mx_shared_exponent_for(double amax, int emax_elem) {
     if (amax == 0.0) return -127;
     int ex;
     (void)frexp(amax, &ex); /* amax = m * 2^ex, m in [0.5, 1) */
-    int e = (ex - 1) - 2;
+    int e = (ex - 1) - emax_elem;
     if (e < -127) e = -127;
     if (e > 127) e = 127;
     return e;
 }
+static int mx_shared_exponent(double amax) { return mx_shared_exponent_for(amax, 2); }
 
 int ref_e8m0_code_for_amax(double amax) { return mx_shared_exponent(amax) + 127; }
+int ref_e8m0_code_for_amax_e4m3(double amax) { return mx_shared_exponent_for(amax, 8) + 127; }
 
 int ref_e2m1_encode(double v, int negative) {
     return e2m1_nearest_mag_code(fabs(v)) | (negative ? 8 : 0);
@@ -360,6 +371,68 @@ int ref_grouped_fp8_gemm(const uint8_t *X8, const float *xs, const int32_t *off,
         int rc = ref_fp8_gemm(X8 + t0 * K, xs + t0, W8 + (int64_t)e * N * K, ws + (int64_t)e * N,
                               Me, N, K, Y + t0 * ldy, ldy);
         if (rc) return rc;
+    }
+    return REF_OK;
+}
+
+/* ---- MXFP8 form of the fallback (Section 3.4; Section 4.1) --------------- */
+
+/* R[rows, K] (bf16 bits) -> E4M3 codes [rows, K] and E8M0 scales [rows, K/32].
+ * Per group of 32: amax = max |x|; shared exponent e = floor(log2 amax) - 8
+ * (8 = exponent of the largest E4M3 binade), clamped to [-127, 127];
+ * element = e4m3(x / 2^e), nearest even, saturating at +-448.  x / 2^e is
+ * exact in double, and ref_e4m3_encode takes a float: the quotient of a bf16
+ * by a power of two is a float unless it underflows the float range, where it
+ * is below half the smallest E4M3 step anyway and rounds to zero either way. */
+int ref_quantize_mxfp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
+                       uint8_t *Xs) {
+    if (M < 0 || K < 0 || K % G || ldx < K) return REF_ERR_ARG;
+    if (M == 0 || K == 0) return REF_OK;
+    if (!X || !Xq || !Xs) return REF_ERR_ARG;
+    const int64_t Kg = K / G;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        for (int64_t g = 0; g < Kg; ++g) {
+            double amax = 0.0;
+            for (int j = 0; j < G; ++j) {
+                uint16_t h = x[g * G + j];
+                if ((h & 0x7F80) == 0x7F80) bad = 1;
+                double a = fabs((double)bf16_to_float(h));
+                if (a > amax) amax = a;
+            }
+            const int e = mx_shared_exponent_for(amax, 8);
+            Xs[m * Kg + g] = (uint8_t)(e + 127);
+            for (int j = 0; j < G; ++j) {
+                double v = ldexp((double)bf16_to_float(x[g * G + j]), -e);
+                Xq[m * K + g * G + j] = (uint8_t)ref_e4m3_encode((float)v);
+            }
+        }
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* Y[m, n] = sum_g 2^(Xs[m,g] + Ws[n,g] - 254) * sum_{j<32} e4m3(Xq[m,32g+j]) * e4m3(Wq[n,32g+j])
+ * in double. */
+int ref_mxfp8_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint8_t *Wq, const uint8_t *Ws,
+                   int64_t M, int64_t N, int64_t K, double *Y, int64_t ldy) {
+    if (M < 0 || N < 0 || K < 0 || K % G || ldy < N) return REF_ERR_ARG;
+    if (M == 0 || N == 0) return REF_OK;
+    if (!Y || (K && (!Xq || !Xs || !Wq || !Ws))) return REF_ERR_ARG;
+    const int64_t Kg = K / G;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double y = 0.0;
+            for (int64_t g = 0; g < Kg; ++g) {
+                double s = 0.0;
+                for (int j = 0; j < G; ++j)
+                    s += ref_e4m3_decode(Xq[m * K + g * G + j]) * ref_e4m3_decode(Wq[n * K + g * G + j]);
+                y += ldexp(s, (int)Xs[m * Kg + g] + (int)Ws[n * Kg + g] - 254);
+            }
+            Y[m * ldy + n] = y;
+        }
     }
     return REF_OK;
 }

@@ -42,7 +42,7 @@ enum {
 };
 
 enum { OSC_DT_F32 = 0, OSC_DT_BF16 = 1 };                   /* dtype of Y */
-enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1 }; /* activation quantiser format */
+enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1, OSC_FMT_MXFP8 = 2 }; /* activation quantiser format */
 
 const char *osc_last_error(void);
 int osc_version(void);
@@ -122,6 +122,15 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  * must be a multiple of 8.
  *   Xq    uint8 [M, K] e4m3 codes;  Xs  float [M] scales
  *
+ * fmt = OSC_FMT_MXFP8: the 8-bit micro-scaling form of the same fallback (Section 3.4:
+ * "FP8 or equivalent 8-bit micro-scaling formats"; Section 4.1, implementation
+ * details: MXFP8 for the W_2 inputs).  Every 32-channel group gets an E8M0 scale with
+ * exponent floor(log2(amax)) - 8 (code 0 when amax is zero or below 2^-118) and E4M3
+ * elements X / 2^exponent rounded to nearest even, saturating at +-448, sign kept.
+ * oidx, K_o, B, ldb are ignored; K % 32 == 0.
+ *   Xq    uint8 [M, K] e4m3 codes, 8-byte aligned
+ *   Xs    E8M0 codes, row-block-major, osc_act_scale_bytes(M, K) bytes, 4-byte aligned
+ *
  * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (fmt, alignment), OSC_ERR_HIP.
  */
 int osc_quantize_act(const void *X, int64_t M, int64_t K, int64_t ldx, const int32_t *oidx,
@@ -168,6 +177,25 @@ int osc_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, int64_t l
 int osc_fp8_gemm(const uint8_t *X8, const float *xs, const void *W8pack, int64_t M, int64_t N,
                  int64_t K, const int32_t *expert_offsets, int32_t E, void *Y, int y_dtype,
                  int64_t ldy, void *stream);
+
+/*
+ * MXFP8 weights and GEMM (Section 3.4 / Section 4.1: the W_2 layers in MXFP8):
+ *   Y[m,n] = sum_g 2^(Xs[m,g] + Ws[n,g] - 254) * sum_{j<32} e4m3(X8[m,32g+j]) * e4m3(W8[n,32g+j])
+ * osc_pack_weight_mxfp8 quantises W bf16 [N, ldw] row by row as osc_quantize_act(fmt = MXFP8)
+ * does and lays codes and scales out for the kernels (Wpack: osc_packed_weight_mxfp8_bytes(N, K)
+ * bytes, 256-byte aligned); osc_unpack_weight_mxfp8 writes W8 uint8 [N, K] and Ws uint8
+ * [N, K/32] (plain row-major), either may be NULL.
+ *   X8, Xs          from osc_quantize_act(fmt = MXFP8) with the same K
+ *   expert_offsets  as in osc_fp8_gemm (E packs osc_packed_weight_mxfp8_bytes(N, K) apart)
+ *   K % 128 == 0 (OSC_ERR_UNSUPPORTED otherwise: only whole 128-channel lines are implemented)
+ */
+size_t osc_packed_weight_mxfp8_bytes(int64_t N, int64_t K);
+int osc_pack_weight_mxfp8(const void *W, int64_t N, int64_t K, int64_t ldw, void *Wpack, void *stream);
+int osc_unpack_weight_mxfp8(const void *Wpack, int64_t N, int64_t K, uint8_t *W8, uint8_t *Ws,
+                            void *stream);
+int osc_mxfp8_gemm(const uint8_t *X8, const uint8_t *Xs, const void *Wpack, int64_t M, int64_t N,
+                   int64_t K, const int32_t *expert_offsets, int32_t E, void *Y, int y_dtype,
+                   int64_t ldy, void *stream);
 
 /*
  * Grouped dual-path GEMM for mixture-of-experts layers (the MoE model of

@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 OSC_DT_F32, OSC_DT_BF16 = 0, 1
-OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN = 0, 1
+OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP8 = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libosc.so")
@@ -27,6 +27,10 @@ _SIGS = {
     "osc_packed_weight_fp8_bytes": (sz, [i64, i64]),
     "osc_pack_weight_fp8": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_unpack_weight_fp8": (C.c_int, [vp, i64, i64, vp, vp, vp]),
+    "osc_packed_weight_mxfp8_bytes": (sz, [i64, i64]),
+    "osc_pack_weight_mxfp8": (C.c_int, [vp, i64, i64, i64, vp, vp]),
+    "osc_unpack_weight_mxfp8": (C.c_int, [vp, i64, i64, vp, vp, vp]),
+    "osc_mxfp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
     "osc_act_scale_bytes": (sz, [i64, i64]),
     "osc_unpack_act_scales": (C.c_int, [vp, i64, i64, vp, vp]),
     "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
@@ -143,6 +147,27 @@ def osc_unpack_weight_fp8(W8pack, N, K):
     return W8, ws
 
 
+def osc_packed_weight_mxfp8_bytes(N, K):
+    return lib().osc_packed_weight_mxfp8_bytes(N, K)
+
+
+def osc_pack_weight_mxfp8(W, out=None):
+    W = _rows16(W)
+    N, K = W.shape
+    if out is None:
+        out = torch.empty(osc_packed_weight_mxfp8_bytes(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib().osc_pack_weight_mxfp8(_ptr(W), N, K, W.stride(0), _ptr(out), _stream()))
+    return out
+
+
+def osc_unpack_weight_mxfp8(Wpack, N, K):
+    dev = Wpack.device
+    W8 = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    Ws = torch.empty((N, K // 32), dtype=torch.uint8, device=dev)
+    _check(lib().osc_unpack_weight_mxfp8(_ptr(Wpack), N, K, _ptr(W8), _ptr(Ws), _stream()))
+    return W8, Ws
+
+
 def osc_act_scale_bytes(M, K):
     return lib().osc_act_scale_bytes(M, K)
 
@@ -157,10 +182,17 @@ def osc_unpack_act_scales(Xs, M, K):
 def osc_quantize_act(X, oidx=None, fmt=OSC_FMT_MXFP4_OSC, ldb=None, out=None):
     """X bf16 [M, K] (device).  MXFP4_OSC -> (Xq uint8 [M,K/2], Xs uint8 row-block-major scales,
     B uint16 [M,ldb]);
-    FP8_E4M3_TOKEN -> (X8 uint8 [M,K], xs float32 [M]).  `out` may hold preallocated outputs."""
+    FP8_E4M3_TOKEN -> (X8 uint8 [M,K], xs float32 [M]);
+    MXFP8 -> (X8 uint8 [M,K], Xs uint8 row-block-major scales).  `out` may hold preallocated outputs."""
     X = _rows16(X)
     M, K = X.shape
     dev = X.device
+    if fmt == OSC_FMT_MXFP8:
+        X8, Xs = out if out is not None else (torch.empty((M, K), dtype=torch.uint8, device=dev),
+                                              torch.empty(osc_act_scale_bytes(M, K), dtype=torch.uint8, device=dev))
+        _check(lib().osc_quantize_act(_ptr(X), M, K, X.stride(0), None, 0, fmt, _ptr(X8), _ptr(Xs),
+                                      None, 0, _stream()))
+        return X8, Xs
     if fmt == OSC_FMT_FP8_E4M3_TOKEN:
         X8, xs = out if out is not None else (torch.empty((M, K), dtype=torch.uint8, device=dev),
                                               torch.empty(M, dtype=torch.float32, device=dev))
@@ -204,6 +236,15 @@ def osc_fp8_gemm(X8, xs, W8pack, N, K, expert_offsets=None, y_dtype=OSC_DT_F32, 
     E = 0 if expert_offsets is None else int(expert_offsets.numel()) - 1
     _check(lib().osc_fp8_gemm(_ptr(X8), _ptr(xs), _ptr(W8pack), M, N, K, _ptr(expert_offsets), E,
                               _ptr(Y), y_dtype, Y.stride(0) if M else N, _stream()))
+    return Y
+
+
+def osc_mxfp8_gemm(X8, Xs, Wpack, N, K, expert_offsets=None, y_dtype=OSC_DT_F32, out=None):
+    M = X8.shape[0]
+    Y = _y(M, N, y_dtype, X8.device, out)
+    E = 0 if expert_offsets is None else int(expert_offsets.numel()) - 1
+    _check(lib().osc_mxfp8_gemm(_ptr(X8), _ptr(Xs), _ptr(Wpack), M, N, K, _ptr(expert_offsets), E,
+                                _ptr(Y), y_dtype, Y.stride(0) if M else N, _stream()))
     return Y
 
 

@@ -43,6 +43,15 @@ Pack8Layout pack8_layout(int64_t N, int64_t K) {
     return L;
 }
 
+PackM8Layout packm8_layout(int64_t N, int64_t K) {
+    PackM8Layout L;
+    L.off_w = 0;
+    L.off_s = align_up((size_t)N * (size_t)K, 256);
+    L.off_z = align_up(L.off_s + scale_bytes(N, K), 256);
+    L.total = L.off_z + 256;
+    return L;
+}
+
 }  // namespace osc
 
 using namespace osc;
@@ -187,10 +196,54 @@ int osc_unpack_weight_fp8(const void* W8pack, int64_t N, int64_t K, uint8_t* W8,
     return OSC_OK;
 }
 
+size_t osc_packed_weight_mxfp8_bytes(int64_t N, int64_t K) {
+    if (N < 0 || K < 0 || K % 32) return 0;
+    return packm8_layout(N, K).total;
+}
+
+int osc_pack_weight_mxfp8(const void* W, int64_t N, int64_t K, int64_t ldw, void* Wpack, void* stream) {
+    int rc = check_mx_shape("osc_pack_weight_mxfp8", N, K, ldw, 0);
+    if (rc) return rc;
+    if (N == 0 || K == 0) return OSC_OK;
+    REQUIRE(W && Wpack, OSC_ERR_NULL, "osc_pack_weight_mxfp8: null pointer");
+    REQUIRE(ldw % 8 == 0 && aligned(W, 16) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_pack_weight_mxfp8: W rows must be 16-byte aligned and Wpack 256-byte aligned");
+    PackM8Layout L = packm8_layout(N, K);
+    uint8_t* base = static_cast<uint8_t*>(Wpack);
+    if (hipMemsetAsync(base + L.off_z, 0, 256, as_stream(stream)) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_pack_weight_mxfp8: cannot clear the zero block");
+    return launch_quant_mxfp8(static_cast<const uint16_t*>(W), N, K, ldw, base + L.off_w, base + L.off_s,
+                              as_stream(stream));
+}
+
+int osc_unpack_weight_mxfp8(const void* Wpack, int64_t N, int64_t K, uint8_t* W8, uint8_t* Ws, void* stream) {
+    int rc = check_mx_shape("osc_unpack_weight_mxfp8", N, K, K, 0);
+    if (rc) return rc;
+    if (N == 0 || K == 0) return OSC_OK;
+    REQUIRE(Wpack, OSC_ERR_NULL, "osc_unpack_weight_mxfp8: null pointer");
+    PackM8Layout L = packm8_layout(N, K);
+    const uint8_t* base = static_cast<const uint8_t*>(Wpack);
+    hipStream_t st = as_stream(stream);
+    if (W8 && hipMemcpyAsync(W8, base + L.off_w, (size_t)N * K, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight_mxfp8: copy of codes failed");
+    if (Ws) return launch_scales_to_rowmajor(base + L.off_s, N, K, Ws, st);
+    return OSC_OK;
+}
+
 int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx, int32_t K_o,
                      int fmt, uint8_t* Xq, void* Xs, void* B, int64_t ldb, void* stream) {
-    REQUIRE(fmt == OSC_FMT_MXFP4_OSC || fmt == OSC_FMT_FP8_E4M3_TOKEN, OSC_ERR_UNSUPPORTED,
+    REQUIRE(fmt == OSC_FMT_MXFP4_OSC || fmt == OSC_FMT_FP8_E4M3_TOKEN || fmt == OSC_FMT_MXFP8, OSC_ERR_UNSUPPORTED,
             "osc_quantize_act: unknown format %d", fmt);
+    if (fmt == OSC_FMT_MXFP8) {
+        int rc8 = check_mx_shape("osc_quantize_act", M, K, ldx, 0);
+        if (rc8) return rc8;
+        if (M == 0 || K == 0) return OSC_OK;
+        REQUIRE(X && Xq && Xs, OSC_ERR_NULL, "osc_quantize_act: null pointer");
+        REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 8) && aligned(Xs, 4), OSC_ERR_UNSUPPORTED,
+                "osc_quantize_act: misaligned pointer or ldx %% 8 != 0");
+        return launch_quant_mxfp8(static_cast<const uint16_t*>(X), M, K, ldx, Xq, static_cast<uint8_t*>(Xs),
+                                  as_stream(stream));
+    }
     if (fmt == OSC_FMT_FP8_E4M3_TOKEN) {
         REQUIRE(M >= 0 && K >= 0, OSC_ERR_SHAPE, "osc_quantize_act: negative extent");
         REQUIRE(ldx >= K, OSC_ERR_SHAPE, "osc_quantize_act: ldx < K");
@@ -281,6 +334,35 @@ int osc_grouped_dual_gemm(const uint8_t* Xq, const uint8_t* Xs, const void* B, i
     if (E == 0) return OSC_OK;
     return dual_common("osc_grouped_dual_gemm", Xq, Xs, B, ldb, row_map, expert_offsets, E, T, Wpack, N, K, K_o,
                        Y, y_dtype, ldy, stream);
+}
+
+int osc_mxfp8_gemm(const uint8_t* X8, const uint8_t* Xs, const void* Wpack, int64_t M, int64_t N, int64_t K,
+                   const int32_t* expert_offsets, int32_t E, void* Y, int y_dtype, int64_t ldy, void* stream) {
+    int rc = check_gemm_common("osc_mxfp8_gemm", M, N, K, Y, y_dtype, ldy);
+    if (rc) return rc;
+    REQUIRE(K % 32 == 0, OSC_ERR_SHAPE, "osc_mxfp8_gemm: K=%lld is not a multiple of 32", (long long)K);
+    REQUIRE(!expert_offsets || E >= 0, OSC_ERR_SHAPE, "osc_mxfp8_gemm: E=%d", E);
+    if (M == 0 || N == 0 || (expert_offsets && E == 0)) return OSC_OK;
+    REQUIRE(Wpack && (K == 0 || (X8 && Xs)), OSC_ERR_NULL, "osc_mxfp8_gemm: null pointer");
+    REQUIRE(K % 128 == 0, OSC_ERR_UNSUPPORTED,
+            "osc_mxfp8_gemm: K=%lld: only whole 128-channel lines are implemented", (long long)K);
+    REQUIRE(aligned(X8, 16) && aligned(Xs, 4) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_mxfp8_gemm: X8 must be 16-byte, Xs 4-byte and Wpack 256-byte aligned");
+    GemmProblem p{};
+    p.Xq = X8;
+    p.Xs = Xs;
+    p.expert_offsets = expert_offsets;
+    p.E = expert_offsets ? E : 0;
+    p.Wpack = static_cast<const uint8_t*>(Wpack);
+    p.pack_stride = packm8_layout(N, K).total;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.K_o = 0;
+    p.Y = Y;
+    p.y_dtype = y_dtype;
+    p.ldy = ldy;
+    return launch_mxfp8_gemm(p, as_stream(stream));
 }
 
 int osc_fp8_gemm(const uint8_t* X8, const float* xs, const void* W8pack, int64_t M, int64_t N, int64_t K,

@@ -44,7 +44,7 @@ typedef float v2f __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int GT = 256;  // 4 wavefronts, arranged 2 x 2 over the workgroup tile
-enum { MODE_DUAL = 0, MODE_FP8 = 1 };
+enum { MODE_DUAL = 0, MODE_FP8 = 1, MODE_MX8 = 2 };  // MX8: E4M3 codes with E8M0 block scales on both operands
 
 struct KArgs {
     const uint8_t* Xq;
@@ -678,8 +678,9 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     // wait for "all vector memory", which includes the DMA loads just issued).  Wave w moves blocks
     // w*NSB .. w*NSB+NSB-1: lanes 0-31 fetch the word of the first half step of their row, lanes
     // 32-63 that of the second.
+    // (MXFP8: one scale word per row and 128-byte stage; both lane halves fetch that word.)
     uint32_t sco[NSB];
-    if (MODE == MODE_DUAL) {
+    if (MODE == MODE_DUAL || MODE == MODE_MX8) {
 #pragma unroll
         for (int k = 0; k < NSB; ++k) {
             const int b = wave * NSB + k;
@@ -690,7 +691,7 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
             } else {
                 g = min(n0 + 32 * (b - BM / 32) + r, a.N - 1);
             }
-            sco[k] = (uint32_t)(g >> 5) * (uint32_t)Kg4 * 128u + (g & 31) * 4 + q * 128;
+            sco[k] = (uint32_t)(g >> 5) * (uint32_t)Kg4 * 128u + (g & 31) * 4 + (MODE == MODE_DUAL ? q * 128 : 0);
         }
     }
     const uint8_t* wsb = wp + a.off_s;
@@ -739,7 +740,7 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     // scale words of stage T_ (half steps 2T_, 2T_+1) into scale buffer BUF_
 #define OSC_D2_SCALES(T_, BUF_)                                                                       \
     {                                                                                                 \
-        const uint32_t o__ = (uint32_t)min(2 * (T_), Kg4 - 2) * 128u;                                 \
+        const uint32_t o__ = (MODE == MODE_DUAL ? (uint32_t)min(2 * (T_), Kg4 - 2) : (uint32_t)min((T_), Kg4 - 1)) * 128u; \
         _Pragma("unroll") for (int k = 0; k < NSB; ++k) {                                             \
             const int b__ = wave * NSB + k;                                                           \
             const uint8_t* src__ = (b__ < BM / 32 ? a.Xs : wsb) + (o__ + sco[k]);                     \
@@ -753,13 +754,13 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     {                                                                                                 \
         const uint8_t* sc__ = scl + (BUF_)*SCL + (H_)*128 + r * 4;                                    \
         _Pragma("unroll") for (int i = 0; i < TM; ++i) SA_[i] =                                       \
-            *reinterpret_cast<const uint32_t*>(sc__ + (wm * TM + i) * 256) >> (16 * q);               \
+            *reinterpret_cast<const uint32_t*>(sc__ + (wm * TM + i) * 256) >> ((MODE == MODE_MX8 ? 8 : 16) * q); \
         _Pragma("unroll") for (int j = 0; j < TN; ++j) SB_[j] =                                       \
-            *reinterpret_cast<const uint32_t*>(sc__ + (BM / 32 + wn * TN + j) * 256) >> (16 * q);     \
+            *reinterpret_cast<const uint32_t*>(sc__ + (BM / 32 + wn * TN + j) * 256) >> ((MODE == MODE_MX8 ? 8 : 16) * q); \
     }
 
     // ---- prologue ---------------------------------------------------------------------------------
-    if (MODE == MODE_DUAL && nTA > 0) OSC_D2_SCALES(0, 0)
+    if ((MODE == MODE_DUAL || MODE == MODE_MX8) && nTA > 0) OSC_D2_SCALES(0, 0)
     OSC_D2_ANY(0, 0, 0, LA, 0, LB)
     wait_vmcnt<0>();
     __syncthreads();
@@ -836,7 +837,54 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
         buf ^= 1;                                                                              \
     }
 
-    if (MODE == MODE_FP8) {
+    // MXFP8 stage.  With 8-bit operands the 32x32x64 instruction takes, from lane half q, elements
+    // 16q .. 16q+15 of each of its two 32-element scale blocks (registers 0-3: block 0, registers
+    // 4-7: block 1), and the scale of block b from the lanes of half b.  So the MFMA that handles
+    // groups 2h and 2h+1 of the line gets, in lane half q, piece 4h+q (first registers) and piece
+    // 4h+2+q (last registers), and the scale word shifted right by 8q bits has the scale this half
+    // must supply (group 2h+q) in byte 2h.
+#define OSC_MFMA_MX8(I_, FA_, GA_, FB_, GB_, SA_, SB_)                                                \
+    {                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                              \
+            const v8i av__ = {(int)FA_[i].x, (int)FA_[i].y, (int)FA_[i].z, (int)FA_[i].w,             \
+                              (int)GA_[i].x, (int)GA_[i].y, (int)GA_[i].z, (int)GA_[i].w};            \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                          \
+                const v8i bv__ = {(int)FB_[j].x, (int)FB_[j].y, (int)FB_[j].z, (int)FB_[j].w,         \
+                                  (int)GB_[j].x, (int)GB_[j].y, (int)GB_[j].z, (int)GB_[j].w};        \
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i][j], 0, 0, I_, \
+                                                                            SA_[i], I_, SB_[j]);      \
+            }                                                                                         \
+        }                                                                                             \
+    }
+#define OSC_D2_STAGE_MX8(T_)                                                                   \
+    {                                                                                          \
+        u32x4 ga0[TM], gb0[TN], ga1[TM], gb1[TN];                                              \
+        int sa[TM], sb[TN];                                                                    \
+        OSC_F2(buf, q, fa0, fb0)                                                               \
+        OSC_F2(buf, 2 + q, ga0, gb0)                                                           \
+        OSC_D2_READ_SCALES(buf, 0, sa, sb)                                                     \
+        if ((T_) + 1 < nT) {                                                                   \
+            OSC_D2_SCALES((T_) + 1, buf ^ 1)                                                   \
+            OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, LA, 0, LB / 2)                                   \
+        }                                                                                      \
+        OSC_F2(buf, 4 + q, fa1, fb1)                                                           \
+        OSC_F2(buf, 6 + q, ga1, gb1)                                                           \
+        OSC_MFMA_MX8(0, fa0, ga0, fb0, gb0, sa, sb)                                            \
+        spread_hint<TM * TN, 2 * (TM + TN), 0, NSB + LA + LB / 2>();                           \
+        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, 0, LB / 2, LB)                    \
+        OSC_MFMA_MX8(2, fa1, ga1, fb1, gb1, sa, sb)                                            \
+        spread_hint<TM * TN, 0, 0, LB - LB / 2>();                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        buf ^= 1;                                                                              \
+    }
+
+    if (MODE == MODE_MX8) {
+#pragma unroll 1
+        for (int T = 0; T < nT; ++T) OSC_D2_STAGE_MX8(T)
+    } else if (MODE == MODE_FP8) {
 #pragma unroll 1
         for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8(T)
     } else {
@@ -1240,12 +1288,16 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
     const uint8_t* const wl = a.Wpack + a.off_l;
     // scale words of this lane's rows (weight row n0 + r, X rows 32m + r), word 2*line + q
     const int rowB = min(n0 + r, a.N - 1);
-    const uint8_t* const ws = a.Wpack + a.off_s + (size_t)(rowB >> 5) * Kg4 * 128 + (rowB & 31) * 4 + q * 128;
+    // scale word of this lane's row: FP4 word 2*line + q (groups 4q .. 4q+3 of the line's eight);
+    // MXFP8 word `line` of the row (four groups), shifted so that byte 2h is the scale of group 2h+q
+    const int sq = (MODE == MODE_MX8) ? 0 : q * 128;
+    const int sstep = (MODE == MODE_MX8) ? 128 : 256;  // bytes between the words of consecutive lines
+    const uint8_t* const ws = a.Wpack + a.off_s + (size_t)(rowB >> 5) * Kg4 * 128 + (rowB & 31) * 4 + sq;
     const uint8_t* xs[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int rowA = min(mb + 32 * m + r, a.M - 1);
-        xs[m] = a.Xs + (size_t)(rowA >> 5) * Kg4 * 128 + (rowA & 31) * 4 + q * 128;
+        xs[m] = a.Xs + (size_t)(rowA >> 5) * Kg4 * 128 + (rowA & 31) * 4 + sq;
     }
     v16f acc[MT];
 #pragma unroll
@@ -1271,32 +1323,45 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
         const uint8_t* src__ = strip + (IMG_)*IMG;                                                      \
         u32x4 fb__[4], fx__[MT][4];                                                                     \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
-            fb__[i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(r, 4 * q + i));                 \
+            /* FP4 / bf16: pieces 4q .. 4q+3; 8-bit: pieces q, 2+q, 4+q, 6+q */                         \
+            const int pc__ = (MODE == MODE_DUAL) ? 4 * q + i : 2 * i + q;                               \
+            fb__[i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(r, pc__));                      \
             _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
-                fx__[m][i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(32 + 32 * m + r, 4 * q + i)); \
+                fx__[m][i] = *reinterpret_cast<const u32x4*>(src__ + st128_off(32 + 32 * m + r, pc__)); \
         }                                                                                               \
-        if (MODE == MODE_FP8) {                                                                         \
-            /* 128 channels = two MFMAs: pieces 4q, 4q+1 and 4q+2, 4q+3 */                              \
-            _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                             \
-                const v8i bv__ = {(int)fb__[2 * h].x, (int)fb__[2 * h].y, (int)fb__[2 * h].z, (int)fb__[2 * h].w, \
-                                  (int)fb__[2 * h + 1].x, (int)fb__[2 * h + 1].y, (int)fb__[2 * h + 1].z, (int)fb__[2 * h + 1].w}; \
-                _Pragma("unroll") for (int m = 0; m < MT; ++m) {                                        \
-                    const v8i av__ = {(int)fx__[m][2 * h].x, (int)fx__[m][2 * h].y, (int)fx__[m][2 * h].z, (int)fx__[m][2 * h].w, \
-                                      (int)fx__[m][2 * h + 1].x, (int)fx__[m][2 * h + 1].y, (int)fx__[m][2 * h + 1].z, (int)fx__[m][2 * h + 1].w}; \
-                    acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f); \
-                }                                                                                       \
+        if (MODE == MODE_FP8 || MODE == MODE_MX8) {                                                     \
+            /* 128 channels = two MFMAs; MFMA h: registers 0-3 = piece 4h+q, registers 4-7 = piece      \
+               4h+2+q (for 8-bit operands lane half q supplies elements 16q..16q+15 of both scale      \
+               blocks, and the scale of block q) */                                                     \
+            int sbm__ = 0x7f7f7f7f, sxm__[MT];                                                          \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m) sxm__[m] = 0x7f7f7f7f;                       \
+            if (MODE == MODE_MX8) {                                                                     \
+                sbm__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*sstep) >> (8 * q);              \
+                _Pragma("unroll") for (int m = 0; m < MT; ++m)                                          \
+                    sxm__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*sstep) >> (8 * q);    \
             }                                                                                           \
+            SKINNY_F8(0) SKINNY_F8(1)                                                                   \
         } else if ((L_) < nL) {                                                                         \
-            const int sb__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*256);                      \
+            const int sb__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*sstep);                    \
             int sx__[MT];                                                                               \
             _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
-                sx__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*256);                      \
+                sx__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*sstep);                    \
             SKINNY_FP4(0) SKINNY_FP4(1) SKINNY_FP4(2) SKINNY_FP4(3)                                     \
         } else {                                                                                        \
             _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
                 _Pragma("unroll") for (int m = 0; m < MT; ++m)                                          \
                     acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fx__[m][i]), \
                                                                      __builtin_bit_cast(v8bf, fb__[i]), acc[m], 0, 0, 0); \
+        }                                                                                               \
+    }
+#define SKINNY_F8(H_)                                                                                   \
+    {                                                                                                   \
+        const v8i bv__ = {(int)fb__[2 * (H_)].x, (int)fb__[2 * (H_)].y, (int)fb__[2 * (H_)].z, (int)fb__[2 * (H_)].w, \
+                          (int)fb__[2 * (H_) + 1].x, (int)fb__[2 * (H_) + 1].y, (int)fb__[2 * (H_) + 1].z, (int)fb__[2 * (H_) + 1].w}; \
+        _Pragma("unroll") for (int m = 0; m < MT; ++m) {                                                \
+            const v8i av__ = {(int)fx__[m][2 * (H_)].x, (int)fx__[m][2 * (H_)].y, (int)fx__[m][2 * (H_)].z, (int)fx__[m][2 * (H_)].w, \
+                              (int)fx__[m][2 * (H_) + 1].x, (int)fx__[m][2 * (H_) + 1].y, (int)fx__[m][2 * (H_) + 1].z, (int)fx__[m][2 * (H_) + 1].w}; \
+            acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 0, 0, 2 * (H_), sxm__[m], 2 * (H_), sbm__); \
         }                                                                                               \
     }
 #define SKINNY_FP4(I_)                                                                                  \
@@ -1319,6 +1384,7 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
         img ^= 1;
     }
 #undef SKINNY_FP4
+#undef SKINNY_F8
 #undef SKINNY_COMPUTE
 #undef SKINNY_FETCH
 
@@ -1432,6 +1498,13 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         a.off_l = L.off_l;
         a.off_z = L.off_z;
         a.wlpitch = L.ldwl * 2;
+    } else if (MODE == MODE_MX8) {
+        PackM8Layout L = packm8_layout(p.N, p.K);
+        a.off_q = L.off_w;
+        a.off_s = L.off_s;
+        a.off_l = 0;
+        a.off_z = L.off_z;
+        a.wlpitch = 0;
     } else {
         Pack8Layout L = pack8_layout(p.N, p.K);
         a.off_q = L.off_w;
@@ -1470,6 +1543,10 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
                        (MODE != MODE_DUAL || p.K_o == 0 || a.bpitch % 128 == 0);
     const bool ragged = rowbytes % 64 != 0 || (MODE == MODE_DUAL && p.K_o > 0 && a.bpitch % 64 != 0);
     int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : 2;
+    if (MODE == MODE_MX8) {  // implemented in the DMA and skinny kernels only
+        if (!lines) return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
+        if (tm == 1) tm = 2;
+    }
     int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
@@ -1505,7 +1582,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
         return launch_pipe2<2, 2>(a, m_full, grouped, st);
     }
-    if (kind >= 1 && grouped && tm == 4) {
+    if (kind >= 1 && grouped && tm == 4 && MODE != MODE_MX8) {
         // experts in 256-row tiles, and what is left of an expert whose last tile would be less than
         // half full in 64-row tiles (an expert of 270 rows: one big tile and one small one, not two
         // big ones)
@@ -1514,22 +1591,28 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (rc != OSC_OK) return rc;
         a.grp_mode = 2;
         a.grp_bm = 256;
-        return ragged ? launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st)
-                      : launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
+        if constexpr (MODE != MODE_MX8)
+            return ragged ? launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st)
+                          : launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
     }
     if (kind >= 1) {
         if (tm == 4) return launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
         return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
     }
+    if constexpr (MODE == MODE_MX8) {
+        return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: no kernel for this shape");
+    } else {
     if (ragged) {
         if (tm == 1) return launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st);
         return launch_cfg<MODE, 2, 2, true>(a, p.M, grouped, st);
     }
     if (tm == 1) return launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
     return launch_cfg<MODE, 2, 2, false>(a, p.M, grouped, st);
+    }
 }
 
 int launch_dual_gemm(const GemmProblem& p, hipStream_t st) { return launch_gemm<MODE_DUAL>(p, st); }
 int launch_fp8_gemm(const GemmProblem& p, hipStream_t st) { return launch_gemm<MODE_FP8>(p, st); }
+int launch_mxfp8_gemm(const GemmProblem& p, hipStream_t st) { return launch_gemm<MODE_MX8>(p, st); }
 
 }  // namespace osc

@@ -40,12 +40,23 @@ struct Pack8Layout {
 };
 Pack8Layout pack8_layout(int64_t N, int64_t K);
 
+// Layout of a packed MXFP8 weight.
+struct PackM8Layout {
+    size_t off_w;  // uint8 [N, K] E4M3 codes
+    size_t off_s;  // E8M0 scales, row-block-major (scale_bytes(N, K) bytes)
+    size_t off_z;  // 256 bytes of zeros
+    size_t total;
+};
+PackM8Layout packm8_layout(int64_t N, int64_t K);
+
 // kernels' host launchers (each enqueues on `st`, returns OSC_OK / OSC_ERR_HIP)
 int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx,
                        int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
                        hipStream_t st);
 int launch_quant_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* X8, float* xs,
                      hipStream_t st);
+int launch_quant_mxfp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, uint8_t* Xs,
+                       hipStream_t st);
 int launch_gather_wl(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
                      int32_t K_o, uint16_t* WLt, int64_t ldwl, hipStream_t st);
 int launch_unpack_wl(const uint16_t* WLt, int64_t ldwl, int64_t N, int32_t K_o, uint16_t* WL,
@@ -53,8 +64,8 @@ int launch_unpack_wl(const uint16_t* WLt, int64_t ldwl, int64_t N, int32_t K_o, 
 
 struct GemmProblem {
     // activations
-    const uint8_t* Xq;   // dual: codes [*, K/2]; fp8: codes [*, K]
-    const uint8_t* Xs;   // dual: E8M0 [*, K/32]
+    const uint8_t* Xq;   // dual: codes [*, K/2]; fp8, mxfp8: codes [*, K]
+    const uint8_t* Xs;   // dual, mxfp8: E8M0 scales, row-block-major
     const float* xs;     // fp8: per-row scale
     const uint16_t* B;   // dual: gathered bf16 [*, ldb]
     int64_t ldb;
@@ -72,5 +83,6 @@ struct GemmProblem {
 };
 int launch_dual_gemm(const GemmProblem& p, hipStream_t st);
 int launch_fp8_gemm(const GemmProblem& p, hipStream_t st);
+int launch_mxfp8_gemm(const GemmProblem& p, hipStream_t st);
 
 }  // namespace osc

@@ -310,6 +310,80 @@ int launch_quant_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8
 }
 
 // ------------------------------------------------------------------------------------------
+// MXFP8 (E4M3 elements, one E8M0 scale per 32 channels): the 8-bit micro-scaling form of the W_2
+// fallback (Section 3.4; Section 4.1, implementation details).  Same work split as the MXFP4
+// kernel (one wavefront per 1024-channel segment of a row, no barriers), no table.  Scale
+// exponent floor(log2 amax) - 8 in integer arithmetic on the bf16 exponent field; elements are
+// x * 2^-e (exact), clamped to +-448 (the conversion instruction does not saturate) and rounded to
+// nearest even by v_cvt_pk_fp8_f32.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(QT) quant_mxfp8_kernel(const uint16_t* __restrict__ X, int M, int K,
+                                                         int64_t ldx, uint8_t* __restrict__ Xq,
+                                                         uint8_t* __restrict__ Xs, int nseg, int total_wg) {
+    const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
+    const int nchunk = K >> 3;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
+        const QItem it = quant_item(wg, wave, nseg, M);
+        if (it.m < 0) continue;  // uniform over the wavefront
+        const int m = it.m;
+        const u32x4* src = reinterpret_cast<const u32x4*>(X + (int64_t)m * ldx);
+        const int c0 = it.seg * SEG_CHUNKS + lane;
+        u32x4 v[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+        if (c0 < nchunk) v[0] = __builtin_nontemporal_load(src + c0);
+        if (c0 + 64 < nchunk) v[1] = __builtin_nontemporal_load(src + c0 + 64);
+        u32x2* dst = reinterpret_cast<u32x2*>(Xq + (int64_t)m * K);
+        uint8_t* sdst = Xs + (int64_t)(m >> 5) * Kg4 * 128 + (m & 31) * 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = c0 + 64 * i;
+            const u32x4 w = v[i];
+            const u32x4 ab = w & 0x7fff7fffu;
+            uint32_t a = max(max(ab.x & 0xffffu, ab.x >> 16), max(ab.y & 0xffffu, ab.y >> 16));
+            a = max(a, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true));  // lane ^ 1
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true));  // lane ^ 2
+            const uint32_t code = (uint32_t)max((int)(a >> 7) - 8, 0);  // E8M0 code = max(E - 8, 0)
+            uint32_t word = code;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;   // lane + 4
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;  // lane + 8
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;  // lane + 12
+            if ((lane & 15) == 0 && c < nchunk) *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+            // 2^-(code - 127): exponent field 254 - code (8 .. 254)
+            const float inv = __builtin_bit_cast(float, (254u - code) << 23);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+            float p[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float lo = __builtin_bit_cast(float, ww[k] << 16);
+                const float hi = __builtin_bit_cast(float, ww[k] & 0xffff0000u);
+                p[2 * k] = fminf(fmaxf(__fmul_rn(lo, inv), -448.0f), 448.0f);
+                p[2 * k + 1] = fminf(fmaxf(__fmul_rn(hi, inv), -448.0f), 448.0f);
+            }
+            int r0 = 0, r1 = 0;
+            r0 = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], r0, false);
+            r0 = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], r0, true);
+            r1 = __builtin_amdgcn_cvt_pk_fp8_f32(p[4], p[5], r1, false);
+            r1 = __builtin_amdgcn_cvt_pk_fp8_f32(p[6], p[7], r1, true);
+            if (c < nchunk) __builtin_nontemporal_store((u32x2){(uint32_t)r0, (uint32_t)r1}, dst + c);
+        }
+    }
+}
+
+int launch_quant_mxfp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, uint8_t* Xs,
+                       hipStream_t st) {
+    const int64_t nchunk = K / 8;
+    const int nseg = (int)((nchunk + SEG_CHUNKS - 1) / SEG_CHUNKS);
+    const int64_t blocks = (M + 31) / 32;
+    const int64_t total_wg = (blocks + 7) / 8 * 8 * (8 * nseg);
+    if (total_wg > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "quantize: M=%lld too large", (long long)M);
+    const int grid = (int)(total_wg < 4096 ? total_wg : 4096);
+    hipLaunchKernelGGL(quant_mxfp8_kernel, dim3(grid), dim3(QT), 0, st, X, (int)M, (int)K, ldx, Xq, Xs, nseg,
+                       (int)total_wg);
+    return check_launch("quant_mxfp8_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
 // Offline: W_L gather.  WLt[n][o] = W[n][oidx[o]], zero padded to ldwl columns.
 // ------------------------------------------------------------------------------------------
 __global__ void gather_wl_kernel(const uint16_t* __restrict__ W, int64_t N, int64_t ldw,

@@ -144,6 +144,25 @@ def test_config3_ffn_w2_fp8(osc):
     check_close(host(Y[torch.from_numpy(rows).cuda()].float()), ref, "cfg3 W2 fp8", bf16_out=True)
 
 
+def test_config3_ffn_w2_mxfp8(osc):
+    """The same W_2 shape through the MXFP8 form of the fallback (Section 4.1, implementation details)."""
+    M, K, N = 8192, 12288, 4096
+    X = wl.activations_diffuse(3003, M, K)
+    W = wl.weights(3004, N, K)
+    X8, Xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+    r8, rs = oracle.quantize_mxfp8(X)
+    assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, M, K)), rs), "mxfp8 scales differ"
+    assert np.array_equal(host(X8), r8), "e4m3 codes differ"
+    Wp = osc.osc_pack_weight_mxfp8(dev(W))
+    w8, wsc = oracle.quantize_mxfp8(W)
+    u8, us = osc.osc_unpack_weight_mxfp8(Wp, N, K)
+    assert np.array_equal(host(u8), w8) and np.array_equal(host(us), wsc)
+    Y = osc.osc_mxfp8_gemm(X8, Xs, Wp, N, K, y_dtype=osc.OSC_DT_BF16)
+    rows = sample_rows(4, M, 16)
+    ref = oracle.mxfp8_gemm(r8[rows], rs[rows], w8, wsc)
+    check_close(host(Y[torch.from_numpy(rows).cuda()].float()), ref, "cfg3 W2 mxfp8", bf16_out=True)
+
+
 # ---- configs[3]: Qwen3-30B-A3B MoE layer ---------------------------------------------------------
 
 

@@ -272,3 +272,74 @@ def test_empty_problems_are_noops(osc):
     Wp = osc.osc_pack_weight(dev(wl.weights(1, 64, 256)), None)
     Y = osc.osc_dual_gemm(Xq, Xs, None, Wp, 64, 256, 0)
     assert Y.shape == (0, 64)
+
+
+# ---- MXFP8 form of the fallback -----------------------------------------------------------------
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (33, 768), (64, 12288), (7, 4096), (300, 2048), (130, 96)])
+def test_quant_mxfp8(osc, M, K):
+    X = wl.activations_diffuse(700 + M + K, M, K)
+    X[0, : min(K, 32)] = 0
+    if M > 2:
+        X[2] = 0x8000  # a row of negative zeros
+    X8, Xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+    r8, rs = oracle.quantize_mxfp8(X)
+    assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, M, K)), rs), "E8M0 scales differ"
+    assert np.array_equal(host(X8), r8), "e4m3 codes differ"
+
+
+def test_quant_mxfp8_edge_values(osc):
+    gen = wl.rng(98)
+    x = gen.standard_normal((64, 256)).astype(np.float32) * np.exp(gen.uniform(-60, 60, (64, 256))).astype(np.float32)
+    x = np.clip(x, -3e38, 3e38)
+    x[1, :32] = 1e-38  # bf16 subnormals
+    x[2, :8] = [31.5, 28, 27, 26, 25, -27, 0.001, 2 ** -14]  # saturation and exact ties
+    x[3, 32:64] = 3.3e38
+    bits = wl.to_bf16_bits(x)
+    allpat = np.arange(65536, dtype=np.uint32)
+    allpat = allpat[((allpat >> 7) & 0xFF) != 0xFF].astype(np.uint16)  # every finite bf16 pattern
+    gen.shuffle(allpat)
+    allpat = np.concatenate([allpat, allpat[: (-len(allpat)) % 256]]).reshape(-1, 256)
+    bits = np.concatenate([bits, allpat])
+    X8, Xs = osc.osc_quantize_act(dev(bits), None, osc.OSC_FMT_MXFP8)
+    r8, rs = oracle.quantize_mxfp8(bits)
+    assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, *bits.shape)), rs)
+    assert np.array_equal(host(X8), r8)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 256, 768), (33, 130, 768), (64, 2048, 768), (128, 512, 12288),
+                                   (200, 96, 128), (300, 300, 1536), (257, 136, 4096)])
+def test_mxfp8_gemm_shapes(osc, M, N, K):
+    X = wl.activations_diffuse(3100 + M + K, M, K)
+    W = wl.weights(3101 + N, N, K)
+    X8, Xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+    Wp = osc.osc_pack_weight_mxfp8(dev(W))
+    W8, Ws = osc.osc_unpack_weight_mxfp8(Wp, N, K)
+    r8, rs = oracle.quantize_mxfp8(X)
+    w8, wsc = oracle.quantize_mxfp8(W)
+    assert np.array_equal(host(X8), r8) and np.array_equal(host(W8), w8) and np.array_equal(host(Ws), wsc)
+    Y = osc.osc_mxfp8_gemm(X8, Xs, Wp, N, K)
+    Y2 = osc.osc_mxfp8_gemm(X8, Xs, Wp, N, K)
+    assert torch.equal(Y, Y2)
+    check_close(host(Y), oracle.mxfp8_gemm(r8, rs, w8, wsc), f"mxfp8 gemm {M}x{N}x{K}")
+
+
+def test_mxfp8_grouped(osc):
+    E, N, K, T = 5, 256, 384, 700
+    off = np.array([0, 150, 150, 400, 690, 700], np.int32)
+    X = wl.activations_diffuse(45, T, K)
+    X8, Xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+    r8, rs = oracle.quantize_mxfp8(X)
+    stride = osc.osc_packed_weight_mxfp8_bytes(N, K)
+    Wp = torch.empty(E * stride, dtype=torch.uint8, device="cuda")
+    ref = np.zeros((T, N))
+    for e in range(E):
+        W = wl.weights(70 + e, N, K)
+        osc.osc_pack_weight_mxfp8(dev(W), out=Wp[e * stride:(e + 1) * stride])
+        w8, wsc = oracle.quantize_mxfp8(W)
+        lo, hi = off[e], off[e + 1]
+        if hi > lo:
+            ref[lo:hi] = oracle.mxfp8_gemm(r8[lo:hi], rs[lo:hi], w8, wsc)
+    Y = osc.osc_mxfp8_gemm(X8, Xs, Wp, N, K, expert_offsets=dev(off))
+    check_close(host(Y), ref, "grouped mxfp8 gemm")

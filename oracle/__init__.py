@@ -240,5 +240,43 @@ def grouped_fp8_gemm(X8, xs, offsets, W8, ws):
     return Y
 
 
+def profile_threshold(X, alpha=5.0):
+    """Eq. 1: alpha * mean |X| over the whole [S, H] activation tensor (bf16 bits), in double."""
+    X = _c(X, np.uint16)
+    S, H = X.shape
+    T = C.c_double(0.0)
+    lib().ref_profile_threshold.argtypes = [C.c_void_p, i64, i64, i64, C.c_double, C.c_void_p]
+    _check(lib().ref_profile_threshold(_p(X), S, H, H, float(alpha), C.byref(T)), "ref_profile_threshold")
+    return T.value
+
+
+def profile_hist(X, T, G=32, hist=None):
+    """Eq. 2-3: counts [H/G, G] of the per-token group argmax positions whose magnitude exceeds T.
+    Adds into ``hist`` when given."""
+    X = _c(X, np.uint16)
+    S, H = X.shape
+    if hist is None:
+        hist = np.zeros((H // G, G), np.uint32)
+    assert hist.dtype == np.uint32 and hist.flags.c_contiguous and hist.shape == (H // G, G)
+    lib().ref_profile_hist.argtypes = [C.c_void_p, i64, i64, i64, i32, C.c_double, C.c_void_p]
+    _check(lib().ref_profile_hist(_p(X), S, H, H, G, float(T), _p(hist)), "ref_profile_hist")
+    return hist
+
+
+def profile_table(hist, R=1):
+    """Alg. 1 table + Eq. 4 statistics from counts [Kg, G].
+    Returns (table int16 [Kg, R], n_total, n_hit, density float64 [Kg], cbar)."""
+    hist = _c(hist, np.uint32)
+    Kg, G = hist.shape
+    table = np.full((Kg, max(R, 0)), -1, np.int16)
+    n_total, n_hit = np.zeros(Kg, np.uint32), np.zeros(Kg, np.uint32)
+    density = np.zeros(Kg, np.float64)
+    cbar = C.c_double(0.0)
+    lib().ref_profile_table.argtypes = [C.c_void_p, i32, i32, i32] + [C.c_void_p] * 5
+    _check(lib().ref_profile_table(_p(hist), Kg, G, R, _p(table), _p(n_total), _p(n_hit), _p(density),
+                                   C.byref(cbar)), "ref_profile_table")
+    return table, n_total, n_hit, density, cbar.value
+
+
 def num_threads():
     return int(lib().ref_num_threads())

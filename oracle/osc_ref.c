@@ -32,6 +32,16 @@
  *                           elements, shared exponent floor(log2 amax) - 8,
  *                           elements rounded to nearest even, saturating
  *   ref_mxfp8_gemm          the linear layer on two MXFP8 operands
+ *   ref_profile_threshold   layer-wise outlier threshold T_l = alpha * mean|X| (Eq. 1)
+ *   ref_profile_hist        per group and local index: number of tokens whose
+ *                           largest-magnitude element of the group sits at that
+ *                           index and exceeds T_l (Eq. 2, Eq. 3; the candidate
+ *                           sets of Alg. 1 kept as counts)
+ *   ref_profile_table       suppression table entry = mode of the candidate set,
+ *                           -1 when it is empty (Alg. 1); N_total, N_hit,
+ *                           clustering density C_k and its mean (Eq. 4 and the
+ *                           paragraph after it); extended to the R most frequent
+ *                           indices per group
  *
  * Floating point: every GEMM accumulates in double.  The FP8 quantiser's
  * scale arithmetic is IEEE single precision (one division, one multiply),
@@ -434,6 +444,94 @@ int ref_mxfp8_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint8_t *Wq, cons
             Y[m * ldy + n] = y;
         }
     }
+    return REF_OK;
+}
+
+/* ---- offline profiling (Section 2, Alg. 1) ------------------------------- */
+
+/* Eq. 1: T = alpha / (S*H) * sum |x|, accumulated in double in row-major order. */
+int ref_profile_threshold(const uint16_t *X, int64_t S, int64_t H, int64_t ldx, double alpha,
+                          double *T) {
+    if (!X || !T || S <= 0 || H <= 0 || ldx < H) return REF_ERR_ARG;
+    double sum = 0.0;
+    for (int64_t s = 0; s < S; ++s)
+        for (int64_t j = 0; j < H; ++j) {
+            const uint16_t h = X[s * ldx + j];
+            if ((h & 0x7F80u) == 0x7F80u) return REF_ERR_NONFINITE;
+            sum += fabs((double)bf16_to_float(h));
+        }
+    *T = alpha * (sum / ((double)S * (double)H));
+    return REF_OK;
+}
+
+/* Eq. 2 and Eq. 3 for every token s and group k of Gp channels: j* = argmax_j |x[s, k*Gp + j]|
+ * (the lowest j among equal magnitudes); when |x[s, k*Gp + j*]| > T the token belongs to S_k and
+ * hist[k][j*] grows by one.  Counts are added to what hist already holds, so a calibration set
+ * can be fed in pieces. */
+int ref_profile_hist(const uint16_t *X, int64_t S, int64_t H, int64_t ldx, int32_t Gp, double T,
+                     uint32_t *hist) {
+    if (!X || !hist || S < 0 || H < 0 || Gp <= 0 || H % Gp || ldx < H) return REF_ERR_ARG;
+    for (int64_t s = 0; s < S; ++s)
+        for (int64_t k = 0; k < H / Gp; ++k) {
+            int jstar = 0;
+            double best = -1.0;
+            for (int j = 0; j < Gp; ++j) {
+                const uint16_t h = X[s * ldx + k * Gp + j];
+                if ((h & 0x7F80u) == 0x7F80u) return REF_ERR_NONFINITE;
+                const double a = fabs((double)bf16_to_float(h));
+                if (a > best) {
+                    best = a;
+                    jstar = j;
+                }
+            }
+            if (best > T) hist[k * Gp + jstar] += 1;
+        }
+    return REF_OK;
+}
+
+/* Alg. 1's table entry and Eq. 4 from the counts of one layer and position.
+ *   table[k][0..R-1]  the R local indices with the largest counts, most frequent first (equal
+ *                     counts: lower index first); only indices with a count above zero; the
+ *                     rest -1.  R = 1 is the table of Alg. 1: the mode, or -1 for an empty set.
+ *   n_total[k] = |S_k|, n_hit[k] = the largest count, density[k] = n_hit / n_total (0 when the
+ *   set is empty); *cbar = mean of density over the groups whose set is not empty (0 when all
+ *   are empty). */
+int ref_profile_table(const uint32_t *hist, int32_t Kg, int32_t Gp, int32_t R, int16_t *table,
+                      uint32_t *n_total, uint32_t *n_hit, double *density, double *cbar) {
+    if (!hist || Kg < 0 || Gp <= 0 || R < 0 || (R && !table)) return REF_ERR_ARG;
+    double dsum = 0.0;
+    int64_t nonempty = 0;
+    for (int32_t k = 0; k < Kg; ++k) {
+        const uint32_t *h = hist + (int64_t)k * Gp;
+        uint64_t total = 0;
+        uint32_t top = 0;
+        for (int j = 0; j < Gp; ++j) {
+            total += h[j];
+            if (h[j] > top) top = h[j];
+        }
+        if (n_total) n_total[k] = (uint32_t)total;
+        if (n_hit) n_hit[k] = top;
+        const double c = total ? (double)top / (double)total : 0.0;
+        if (density) density[k] = c;
+        if (total) {
+            dsum += c;
+            ++nonempty;
+        }
+        /* selection of the R most frequent indices, one at a time */
+        for (int32_t r = 0; r < R; ++r) {
+            int pick = -1;
+            for (int j = 0; j < Gp; ++j) {
+                if (h[j] == 0) continue;
+                int taken = 0;
+                for (int32_t q = 0; q < r; ++q)
+                    if (table[(int64_t)k * R + q] == j) taken = 1;
+                if (taken) continue;
+                if (pick < 0 || h[j] > h[pick]) pick = j;
+            }
+            table[(int64_t)k * R + r] = (int16_t)pick;
+        }
+    }
+    if (cbar) *cbar = nonempty ? dsum / (double)nonempty : 0.0;
     return REF_OK;
 }
 

@@ -212,6 +212,59 @@ int osc_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, i
                           int64_t T, const void *Wpack, int64_t N, int64_t K, int32_t K_o,
                           void *Y, int y_dtype, int64_t ldy, void *stream);
 
+/* ---- offline profiling (calibration) ------------------------------------------ */
+
+/*
+ * Layer-wise outlier threshold (Section 2.1, Eq. 1): T = alpha * mean |x| over all
+ * tokens and channels of one activation interface (alpha = 5 in the paper).
+ * Two calls, so that a calibration set can be fed in pieces:
+ *   osc_profile_abs_sum    *abs_sum += sum of |x| over X.  The caller zeroes *abs_sum
+ *                          before the first piece.  Added with floating-point atomics:
+ *                          the order of the additions, and so the last bits of the
+ *                          double, can differ from run to run.
+ *   osc_profile_threshold  *T = (float)(alpha * *abs_sum / count), count = the number
+ *                          of elements summed (tokens x channels over all pieces)
+ *   X        bf16 [S, ldx] (device), ldx >= H, H % 8 == 0, rows 16-byte aligned; finite values
+ *   abs_sum  double (device), T float (device)
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (alignment), OSC_ERR_HIP.
+ */
+int osc_profile_abs_sum(const void *X, int64_t S, int64_t H, int64_t ldx, double *abs_sum,
+                        void *stream);
+int osc_profile_threshold(const double *abs_sum, int64_t count, float alpha, float *T,
+                          void *stream);
+
+/*
+ * Candidate sets of Alg. 1 as counts (Section 2.2, Eq. 2 and Eq. 3).  For every token s
+ * and every group k of G consecutive channels: j* = the local index of the largest
+ * magnitude in the group (the lowest index among equal magnitudes); when that magnitude
+ * is strictly above *T, hist[k*G + j*] grows by one.  Counts are added to what hist
+ * holds (zero it before the first piece); integer atomics, so the result is exact and
+ * independent of any ordering.
+ *   G     16, 32 or 64 (the group sizes of Section 2.2); H % G == 0
+ *   T     float (device): the threshold; a negative value admits every token, NaN none
+ *   hist  uint32 [H/G, G] (device) -- one counter per channel
+ */
+int osc_profile_hist(const void *X, int64_t S, int64_t H, int64_t ldx, int32_t G, const float *T,
+                     uint32_t *hist, void *stream);
+
+/*
+ * Suppression table entries and clustering density from the counts (Alg. 1; Section 2.2,
+ * Eq. 4 and the definition of the density after it).
+ *   table    int16 [Kg, R] (device): the R local indices with the largest counts, most
+ *            frequent first, the lower index first among equal counts; only indices
+ *            whose count is above zero, -1 otherwise.  Column 0 is the table of Alg. 1
+ *            (the mode of the candidate set, -1 when the set is empty).  Copied to the
+ *            host it is what osc_table_to_index takes (for G = 32).
+ *   n_total  uint32 [Kg] or NULL: tokens in the group's candidate set (N_total)
+ *   n_hit    uint32 [Kg] or NULL: the largest count (N_hit)
+ *   density  float [Kg] or NULL: C_k = N_hit / N_total, 0 for an empty set
+ *   cbar     float or NULL: mean of C_k over the groups whose set is not empty (0 if none)
+ *   G in [1, 64].  All pointers are device pointers.
+ */
+int osc_profile_table(const uint32_t *hist, int32_t Kg, int32_t G, int32_t R, int16_t *table,
+                      uint32_t *n_total, uint32_t *n_hit, float *density, float *cbar,
+                      void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     osc_dual_gemm, osc_fp8_gemm, osc_grouped_dual_gemm, osc_last_error, osc_pack_weight,
     osc_pack_weight_fp8, osc_packed_weight_bytes, osc_packed_weight_fp8_bytes, osc_quantize_act,
     osc_table_to_index, osc_unpack_weight, osc_unpack_weight_fp8, osc_version,
-    osc_mxfp8_gemm, osc_pack_weight_mxfp8, osc_packed_weight_mxfp8_bytes, osc_unpack_weight_mxfp8)
+    osc_mxfp8_gemm, osc_pack_weight_mxfp8, osc_packed_weight_mxfp8_bytes, osc_unpack_weight_mxfp8,
+    osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table)

@@ -36,6 +36,10 @@ _SIGS = {
     "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
     "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
+    "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
+    "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
+    "osc_profile_hist": (C.c_int, [vp, i64, i64, i64, i32, vp, vp, vp]),
+    "osc_profile_table": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
     "osc_grouped_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, vp, i32, i64, vp, i64, i64, i32, vp,
                                         C.c_int, i64, vp]),
 }
@@ -256,3 +260,44 @@ def osc_grouped_dual_gemm(Xq, Xs, B, row_map, expert_offsets, T, Wpack, N, K, K_
                                        _ptr(row_map), _ptr(expert_offsets), E, T, _ptr(Wpack), N, K,
                                        K_o, _ptr(Y), y_dtype, Y.stride(0) if T else N, _stream()))
     return Y
+
+
+def osc_profile_abs_sum(X, abs_sum=None):
+    """abs_sum (float64 [1], device) += sum |X|; a zeroed accumulator is made when none is given."""
+    X = _rows16(X)
+    if abs_sum is None:
+        abs_sum = torch.zeros(1, dtype=torch.float64, device=X.device)
+    _check(lib().osc_profile_abs_sum(_ptr(X), X.shape[0], X.shape[1], X.stride(0), _ptr(abs_sum), _stream()))
+    return abs_sum
+
+
+def osc_profile_threshold(abs_sum, count, alpha=5.0, out=None):
+    """T (float32 [1], device) = alpha * abs_sum / count."""
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=abs_sum.device)
+    _check(lib().osc_profile_threshold(_ptr(abs_sum), count, alpha, _ptr(out), _stream()))
+    return out
+
+
+def osc_profile_hist(X, T, G=32, hist=None):
+    """hist (uint32 as int32 [H/G, G], device) += per-token group-argmax counts above T (device float)."""
+    X = _rows16(X)
+    S, H = X.shape
+    if hist is None:
+        hist = torch.zeros((H // G, G), dtype=torch.int32, device=X.device)
+    _check(lib().osc_profile_hist(_ptr(X), S, H, X.stride(0), G, _ptr(T), _ptr(hist), _stream()))
+    return hist
+
+
+def osc_profile_table(hist, R=1):
+    """-> (table int16 [Kg, R], n_total int32 [Kg], n_hit int32 [Kg], density float32 [Kg], cbar float32 [1])."""
+    Kg, G = hist.shape
+    dev = hist.device
+    table = torch.empty((Kg, R), dtype=torch.int16, device=dev)
+    n_total = torch.empty(Kg, dtype=torch.int32, device=dev)
+    n_hit = torch.empty(Kg, dtype=torch.int32, device=dev)
+    density = torch.empty(Kg, dtype=torch.float32, device=dev)
+    cbar = torch.empty(1, dtype=torch.float32, device=dev)
+    _check(lib().osc_profile_table(_ptr(hist), Kg, G, R, _ptr(table), _ptr(n_total), _ptr(n_hit), _ptr(density),
+                                   _ptr(cbar), _stream()))
+    return table, n_total, n_hit, density, cbar

@@ -392,4 +392,54 @@ int osc_fp8_gemm(const uint8_t* X8, const float* xs, const void* W8pack, int64_t
     return launch_fp8_gemm(p, as_stream(stream));
 }
 
+// ---- offline profiling -------------------------------------------------------------------
+
+static int check_profile_x(const char* who, const void* X, int64_t S, int64_t H, int64_t ldx) {
+    REQUIRE(S >= 0 && H >= 0, OSC_ERR_SHAPE, "%s: negative extent", who);
+    REQUIRE(H % 8 == 0, OSC_ERR_SHAPE, "%s: H=%lld is not a multiple of 8", who, (long long)H);
+    REQUIRE(ldx >= H, OSC_ERR_SHAPE, "%s: ldx=%lld < H=%lld", who, (long long)ldx, (long long)H);
+    REQUIRE(H <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "%s: H above 2^31-1", who);
+    if (S == 0 || H == 0) return OSC_OK;
+    REQUIRE(X, OSC_ERR_NULL, "%s: null pointer", who);
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16), OSC_ERR_UNSUPPORTED, "%s: X rows must be 16-byte aligned", who);
+    return OSC_OK;
+}
+
+int osc_profile_abs_sum(const void* X, int64_t S, int64_t H, int64_t ldx, double* abs_sum, void* stream) {
+    int rc = check_profile_x("osc_profile_abs_sum", X, S, H, ldx);
+    if (rc) return rc;
+    REQUIRE(abs_sum, OSC_ERR_NULL, "osc_profile_abs_sum: null pointer");
+    REQUIRE(aligned(abs_sum, 8), OSC_ERR_UNSUPPORTED, "osc_profile_abs_sum: misaligned abs_sum");
+    if (S == 0 || H == 0) return OSC_OK;
+    return launch_profile_abs_sum(static_cast<const uint16_t*>(X), S, H, ldx, abs_sum, as_stream(stream));
+}
+
+int osc_profile_threshold(const double* abs_sum, int64_t count, float alpha, float* T, void* stream) {
+    REQUIRE(abs_sum && T, OSC_ERR_NULL, "osc_profile_threshold: null pointer");
+    REQUIRE(count > 0, OSC_ERR_SHAPE, "osc_profile_threshold: count=%lld", (long long)count);
+    REQUIRE(aligned(abs_sum, 8) && aligned(T, 4), OSC_ERR_UNSUPPORTED, "osc_profile_threshold: misaligned pointer");
+    return launch_profile_threshold(abs_sum, count, alpha, T, as_stream(stream));
+}
+
+int osc_profile_hist(const void* X, int64_t S, int64_t H, int64_t ldx, int32_t G, const float* T,
+                     uint32_t* hist, void* stream) {
+    int rc = check_profile_x("osc_profile_hist", X, S, H, ldx);
+    if (rc) return rc;
+    REQUIRE(G == 16 || G == 32 || G == 64, OSC_ERR_UNSUPPORTED, "osc_profile_hist: group size %d (16, 32 or 64)", G);
+    REQUIRE(H % G == 0, OSC_ERR_SHAPE, "osc_profile_hist: H=%lld is not a multiple of G=%d", (long long)H, G);
+    if (S == 0 || H == 0) return OSC_OK;
+    REQUIRE(T && hist, OSC_ERR_NULL, "osc_profile_hist: null pointer");
+    REQUIRE(aligned(T, 4) && aligned(hist, 4), OSC_ERR_UNSUPPORTED, "osc_profile_hist: misaligned pointer");
+    return launch_profile_hist(static_cast<const uint16_t*>(X), S, H, ldx, G, T, hist, as_stream(stream));
+}
+
+int osc_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, int16_t* table,
+                      uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar, void* stream) {
+    REQUIRE(Kg >= 0 && R >= 0, OSC_ERR_SHAPE, "osc_profile_table: Kg=%d R=%d", Kg, R);
+    REQUIRE(G >= 1 && G <= 64, OSC_ERR_UNSUPPORTED, "osc_profile_table: group size %d (1..64)", G);
+    REQUIRE((Kg == 0 || hist) && (Kg == 0 || R == 0 || table), OSC_ERR_NULL, "osc_profile_table: null pointer");
+    if (Kg == 0 && !cbar) return OSC_OK;
+    return launch_profile_table(hist, Kg, G, R, table, n_total, n_hit, density, cbar, as_stream(stream));
+}
+
 }  // extern "C"

@@ -62,6 +62,14 @@ int launch_gather_wl(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, const
 int launch_unpack_wl(const uint16_t* WLt, int64_t ldwl, int64_t N, int32_t K_o, uint16_t* WL,
                      hipStream_t st);
 
+int launch_profile_abs_sum(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, double* abs_sum,
+                           hipStream_t st);
+int launch_profile_threshold(const double* abs_sum, int64_t count, float alpha, float* T, hipStream_t st);
+int launch_profile_hist(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, const float* T,
+                        uint32_t* hist, hipStream_t st);
+int launch_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, int16_t* table,
+                         uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar, hipStream_t st);
+
 struct GemmProblem {
     // activations
     const uint8_t* Xq;   // dual: codes [*, K/2]; fp8, mxfp8: codes [*, K]

@@ -97,6 +97,28 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert p(FAKE, 4, 40, 40, None, 0, FAKE, None) == -2
     assert p(None, 4, 64, 64, None, 0, FAKE, None) == -1
     assert p(FAKE, 4, 64, 64, None, 0, FAKE + 16, None) == -4  # Wpack alignment
+    m8 = lib.osc_mxfp8_gemm
+    assert m8(FAKE, FAKE, FAKE, 4, 64, 96, None, 0, FAKE, 0, 64, None) == -4  # K % 128
+    assert m8(FAKE, None, FAKE, 4, 64, 128, None, 0, FAKE, 0, 64, None) == -1
+    assert q(FAKE, 4, 48, 48, None, 0, 2, FAKE, FAKE, None, 0, None) == -2  # MXFP8 quantiser, K % 32
+    # offline profiling
+    a = lib.osc_profile_abs_sum
+    assert a(None, 4, 64, 64, FAKE, None) == -1 and a(FAKE, 4, 64, 64, None, None) == -1
+    assert a(FAKE, 4, 60, 64, FAKE, None) == -2 and a(FAKE, 4, 64, 32, FAKE, None) == -2
+    assert a(FAKE + 2, 4, 64, 64, FAKE, None) == -4
+    assert a(None, 0, 64, 64, FAKE, None) == 0
+    th = lib.osc_profile_threshold
+    assert th(FAKE, 0, 5.0, FAKE, None) == -2 and th(None, 8, 5.0, FAKE, None) == -1
+    h = lib.osc_profile_hist
+    assert h(FAKE, 4, 64, 64, 8, FAKE, FAKE, None) == -4     # group size
+    assert h(FAKE, 4, 96, 96, 64, FAKE, FAKE, None) == -2    # H % G
+    assert h(FAKE, 4, 64, 64, 32, None, FAKE, None) == -1
+    assert h(None, 0, 64, 64, 32, None, None, None) == 0
+    t = lib.osc_profile_table
+    assert t(None, 4, 32, 1, FAKE, None, None, None, None, None) == -1
+    assert t(FAKE, 4, 65, 1, FAKE, None, None, None, None, None) == -4
+    assert t(FAKE, -1, 32, 1, FAKE, None, None, None, None, None) == -2
+    assert t(None, 0, 32, 1, None, None, None, None, None, None) == 0
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch):

@@ -239,3 +239,22 @@ def test_config5_sweep(osc, r):
         wr = (wq, wsc, oracle.gather_wl(W, oidx) if r else None)
         rows = sample_rows(5 + M, M, 8)
         dual_sampled(osc, qd, qr, Wp, wr, N, K, len(oidx), rows, osc.OSC_DT_BF16, f"cfg5 M={M} r={r}")
+
+
+# ---- offline profiling at the headline shape (Section 2; Alg. 1) --------------------------------
+def test_profile_config1_shape(osc):
+    M, K = 8192, 4096
+    X, planted = wl.activations_persistent(6001, M, K, 2, jitter=0.3)
+    Xd = dev(X)
+    acc = osc.osc_profile_abs_sum(Xd)
+    T = osc.osc_profile_threshold(acc, M * K, 5.0)
+    ref_T = oracle.profile_threshold(X, 5.0)
+    assert abs(T.item() - ref_T) <= 1e-6 * ref_T
+    for G in (16, 32, 64):
+        hist = osc.osc_profile_hist(Xd, T, G)
+        assert np.array_equal(host(hist).view(np.uint32), oracle.profile_hist(X, T.item(), G)), G
+    hist = osc.osc_profile_hist(Xd, T, 32)
+    table = osc.osc_profile_table(hist, 2)[0]
+    ref_table = oracle.profile_table(oracle.profile_hist(X, T.item(), 32), 2)[0]
+    assert np.array_equal(host(table), ref_table)
+    assert np.array_equal(np.sort(host(table), axis=1), np.sort(planted, axis=1))

@@ -30,7 +30,7 @@ K_HID = 4096
 # K_o=256, bf16 out), from rocprofv3 FETCH_SIZE/WRITE_SIZE runs of this script scaled by a 1 GiB
 # plain copy (summary: profiles/configs1_M8192_step__hbm_traffic.txt).  A profiler reading, not
 # something this script can measure itself.
-DOMINANT_TRAFFIC_BYTES = {8192: 226.6e6}
+DOMINANT_TRAFFIC_BYTES = {8192: 245.6e6}
 PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
 
 
@@ -164,7 +164,36 @@ def main():
 
     ms_quant = time_one(lambda: quant_ring(osc.OSC_FMT_MXFP4_OSC, oidx1, ringQ), reps=4 * nring)
     ms_quant8 = time_one(lambda: quant_ring(osc.OSC_FMT_FP8_E4M3_TOKEN, None, ringF), reps=4 * nring)
+    # offline profiling kernels (Section 2, Alg. 1) over the same ring: read-only streams of X
+    p_acc = torch.zeros(1, dtype=torch.float64, device=dev)
+    p_T = osc.osc_profile_threshold(osc.osc_profile_abs_sum(dX1), M * K_HID, 5.0)
+    p_hist = torch.zeros((K_HID // 32, 32), dtype=torch.int32, device=dev)
+
+    def prof_ring(which):
+        i = turn[0] = (turn[0] + 1) % nring
+        if which == 0:
+            osc.osc_profile_abs_sum(ringX[i], p_acc)
+        else:
+            osc.osc_profile_hist(ringX[i], p_T, 32, p_hist)
+
+    ms_psum = time_one(lambda: prof_ring(0), reps=4 * nring)
+    ms_phist = time_one(lambda: prof_ring(1), reps=4 * nring)
     del ringX, ringQ, ringF
+
+    # the W_2 fallback at the down-projection shape of configs[2] (K = 12288 -> N = 4096), MXFP8
+    # (Section 4.1) next to the per-token FP8 form
+    K_FF = 12288
+    dXf = torch.from_numpy(wl.activations_diffuse(3003, 64, K_FF)).to(dev).repeat(-(-M // 64), 1)[:M].contiguous()
+    Wf = up(wl.weights(3004, 4096, K_FF))
+    wm8, wf8 = osc.osc_pack_weight_mxfp8(Wf), osc.osc_pack_weight_fp8(Wf)
+    del Wf
+    m8 = osc.osc_quantize_act(dXf, None, osc.OSC_FMT_MXFP8)
+    t8 = osc.osc_quantize_act(dXf, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    ms_m8q = time_one(lambda: osc.osc_quantize_act(dXf, None, osc.OSC_FMT_MXFP8, out=m8), reps=10)
+    ms_m8g = time_one(lambda: osc.osc_mxfp8_gemm(*m8, wm8, 4096, K_FF, y_dtype=ydt, out=Y["o"]), reps=10)
+    ms_t8q = time_one(lambda: osc.osc_quantize_act(dXf, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=t8), reps=10)
+    ms_t8g = time_one(lambda: osc.osc_fp8_gemm(*t8, wf8, 4096, K_FF, y_dtype=ydt, out=Y["o"]), reps=10)
+    del dXf, wm8, wf8, m8, t8
     per = {}
     for n, N in PROJ:
         qq = q2 if n == "o" else q1
@@ -200,6 +229,28 @@ def main():
         "quant_roofline": {"bound": "hbm", "achieved": round(quant_bytes / (ms_quant * 1e-3) / 1e9, 1),
                            "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": round(quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+    ff_flops = 2.0 * M * 4096 * K_FF
+    xbytes = M * K_HID * 2
+    out["w2_fallback"] = {
+        "shape": f"M={M} K={K_FF} N=4096, Y bf16",
+        "mxfp8": {"quant_ms": round(ms_m8q, 4), "gemm_ms": round(ms_m8g, 4),
+                  "quant_gbs": round(M * K_FF * (3 + 1 / 32) / (ms_m8q * 1e-3) / 1e9, 1),
+                  "gemm_tflops": round(ff_flops / (ms_m8g * 1e-3) / 1e12, 1),
+                  "gemm_frac_fp8_peak": round(ff_flops / (ms_m8g * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4)},
+        "fp8_per_token": {"quant_ms": round(ms_t8q, 4), "gemm_ms": round(ms_t8g, 4),
+                          "gemm_tflops": round(ff_flops / (ms_t8g * 1e-3) / 1e12, 1),
+                          "gemm_frac_fp8_peak": round(ff_flops / (ms_t8g * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4)},
+    }
+    out["profiling"] = {
+        "shape": f"S={M} H={K_HID} G=32",
+        "abs_sum_ms": round(ms_psum, 4), "hist_ms": round(ms_phist, 4),
+        "abs_sum_roofline": {"bound": "hbm", "achieved": round(xbytes / (ms_psum * 1e-3) / 1e9, 1),
+                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(xbytes / (ms_psum * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        "hist_roofline": {"bound": "hbm", "achieved": round(xbytes / (ms_phist * 1e-3) / 1e9, 1),
+                          "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                          "frac": round(xbytes / (ms_phist * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }
     if args.detail:
         for k, v in out["kernels_ms"].items():

@@ -175,11 +175,11 @@ __device__ __forceinline__ TilePos tile_at(const KArgs& a, int tile) {
     return p;
 }
 
-template <int MODE, int TM, int TN>
+template <int MODE, int TM, int TN, int WN = 2>
 __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, v16f (&acc)[TM][TN]) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
     const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
     const uint8_t* wp = tp.wp;
     // ---- epilogue ---------------------------------------------------------------------------
@@ -637,19 +637,24 @@ __device__ __forceinline__ void load_to_lds16(const uint8_t* src, uint8_t* lds_w
 __device__ __forceinline__ int swz8(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 __device__ __forceinline__ int st128_off(int row, int piece) { return row * 128 + ((piece ^ swz8(row)) << 4); }
 
-template <int MODE, int TM, int TN>
-__global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+template <int MODE, int TM, int TN, int WN>
+__global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
+    // 2 x WN wavefronts; WN = 4 puts two wavefronts on every SIMD: while one waits for its LDS
+    // reads or sits between two dependent MFMAs the other keeps the matrix core busy
+    constexpr int NWV = 2 * WN;                // wavefronts
+    constexpr int RPP = NWV * 8;               // stage rows that one DMA pass of the workgroup fills
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     constexpr int STG = (BM + BN) * 128;
-    constexpr int LA = BM / 32, LB = BN / 32;  // DMA loads per thread and stage
+    constexpr int LA = BM / RPP, LB = BN / RPP;  // DMA loads per thread and stage
     constexpr int NBLK = (BM + BN) / 32;      // 32-row blocks of a stage
-    constexpr int NSB = NBLK / 4;              // scale DMA loads per wave and stage (one block each)
+    constexpr int NSB = NBLK / NWV;            // scale DMA loads per wave and stage (one block each)
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
     constexpr int SCL = NBLK * 256;            // bytes of scale words per stage: [block][half step][32 rows][4]
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* const scl = lds + 2 * STG;        // scale words of the two stages
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
     const TilePos tp = locate_tile<BM, BN>(a);
     if (!tp.valid) return;
     const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
@@ -661,17 +666,17 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
     const int nTB = (MODE == MODE_DUAL) ? ((a.K_o * 2 + 127) >> 7) : 0;  // stages of the bf16 branch
     const int nT = nTA + nTB;
 
-    // thread t fills stage position (row (t >> 3) + 32 i, piece position t & 7)
+    // thread t fills stage position (row (t >> 3) + RPP i, piece position t & 7)
     const int c8 = (t & 7) ^ swz8(t >> 3);
     uint32_t oa[LA], ob[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        int g = min(m0 + (t >> 3) + 32 * i, row_end - 1);
+        int g = min(m0 + (t >> 3) + RPP * i, row_end - 1);
         if (MODE == MODE_DUAL && a.row_map) g = a.row_map[g];
         oa[i] = (uint32_t)g;
     }
 #pragma unroll
-    for (int i = 0; i < LB; ++i) ob[i] = (uint32_t)min(n0 + (t >> 3) + 32 * i, a.N - 1);
+    for (int i = 0; i < LB; ++i) ob[i] = (uint32_t)min(n0 + (t >> 3) + RPP * i, a.N - 1);
     const uint8_t* wq = wp + a.off_q;
     const uint8_t* wl = wp + a.off_l;
     // Scale words travel through LDS as well (a register load in the loop would make the compiler
@@ -711,9 +716,9 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
         uint8_t* st__ = lds + (BUF_)*STG + wave * 1024;                                              \
         const uint32_t o__ = (uint32_t)(T_)*128u + c8 * 16;                                          \
         _Pragma("unroll") for (int i = (ALO_); i < (AHI_); ++i)                                      \
-            load_to_lds16((ABASE_) + (oa[i] * (uint32_t)(APITCH_) + o__), st__ + i * 4096);          \
+            load_to_lds16((ABASE_) + (oa[i] * (uint32_t)(APITCH_) + o__), st__ + i * (RPP * 128));          \
         _Pragma("unroll") for (int i = (BLO_); i < (BHI_); ++i)                                      \
-            load_to_lds16((BBASE_) + (ob[i] * (uint32_t)(BPITCH_) + o__), st__ + BM * 128 + i * 4096); \
+            load_to_lds16((BBASE_) + (ob[i] * (uint32_t)(BPITCH_) + o__), st__ + BM * 128 + i * (RPP * 128)); \
     }
     // stage S_ of the whole sequence (main phase, then bf16 branch); nothing past the end
 #define OSC_D2_ANY(S_, BUF_, ALO_, AHI_, BLO_, BHI_)                                                  \
@@ -769,25 +774,29 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
 
     // One FP4 stage = two half steps x two pieces.  REFILL_(stage, buffer, alo, ahi, blo, bhi)
     // issues part of the next stage's loads.
+#define D2_R1A ((LA * 3 + 7) / 8)
+#define D2_R1B ((LB * 3 + 7) / 8)
+#define D2_R2A ((LA * 6 + 7) / 8)
+#define D2_R2B ((LB * 6 + 7) / 8)
 #define OSC_D2_STAGE_FP4(T_, REFILL_)                                                          \
     {                                                                                          \
         int sa[TM], sb[TN], ta[TM], tb[TN];                                                    \
         OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
         OSC_D2_READ_SCALES(buf, 0, sa, sb)                                                     \
         if ((T_) + 1 < nTA) OSC_D2_SCALES((T_) + 1, buf ^ 1)                                   \
-        REFILL_((T_) + 1, buf ^ 1, 0, (LA * 3 + 7) / 8, 0, (LB * 3 + 7) / 8)                    \
+        REFILL_((T_) + 1, buf ^ 1, 0, D2_R1A, 0, D2_R1B)                                       \
         OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
         OSC_MFMA_FP4(0, fa0, fb0, sa, sb)                                                      \
-        spread_hint<TM * TN, TM + TN, 0, NSB + (LA * 3 + 7) / 8 + (LB * 3 + 7) / 8>();         \
-        REFILL_((T_) + 1, buf ^ 1, (LA * 3 + 7) / 8, (LA * 6 + 7) / 8, (LB * 3 + 7) / 8, (LB * 6 + 7) / 8) \
+        spread_hint<TM * TN, TM + TN, 0, NSB + D2_R1A + D2_R1B>();                             \
+        REFILL_((T_) + 1, buf ^ 1, D2_R1A, D2_R2A, D2_R1B, D2_R2B)                             \
         OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
         OSC_D2_READ_SCALES(buf, 1, ta, tb)                                                     \
         OSC_MFMA_FP4(1, fa1, fb1, sa, sb)                                                      \
-        spread_hint<TM * TN, 2 * (TM + TN), 0, (LA * 6 + 7) / 8 - (LA * 3 + 7) / 8 + (LB * 6 + 7) / 8 - (LB * 3 + 7) / 8>(); \
-        REFILL_((T_) + 1, buf ^ 1, (LA * 6 + 7) / 8, LA, (LB * 6 + 7) / 8, LB)                 \
+        spread_hint<TM * TN, 2 * (TM + TN), 0, D2_R2A - D2_R1A + D2_R2B - D2_R1B>();           \
+        REFILL_((T_) + 1, buf ^ 1, D2_R2A, LA, D2_R2B, LB)                                     \
         OSC_F2(buf, 4 + 2 * q + 1, fa1, fb1)                                                   \
         OSC_MFMA_FP4(0, fa0, fb0, ta, tb)                                                      \
-        spread_hint<TM * TN, TM + TN, 0, LA - (LA * 6 + 7) / 8 + LB - (LB * 6 + 7) / 8>();     \
+        spread_hint<TM * TN, TM + TN, 0, LA - D2_R2A + LB - D2_R2B>();                         \
         OSC_MFMA_FP4(1, fa1, fb1, ta, tb)                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                     \
         wait_vmcnt<0>();                                                                       \
@@ -898,7 +907,7 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
 #pragma unroll 1
         for (; T < nT; ++T) OSC_D2_STAGE_BF16(T)
     }
-    store_result<MODE, TM, TN>(a, tp, acc);
+    store_result<MODE, TM, TN, WN>(a, tp, acc);
 }
 
 
@@ -929,12 +938,14 @@ __global__ void __launch_bounds__(GT) gemm_dma2_kernel(KArgs a) {
 // (= workgroup % 8) owns the x-th eighth of the tile list; its workgroups take neighbouring tiles
 // at any time (8 m-tiles x 4 n-tiles with 32 workgroups).
 // ------------------------------------------------------------------------------------------
-template <int TM, int TN>
-__global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+template <int TM, int TN, int WN>
+__global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntiles) {
+    constexpr int NWV = 2 * WN, RPP = NWV * 8;  // wavefronts (2 x WN); stage rows per DMA pass
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     constexpr int STG = (BM + BN) * 128;
-    constexpr int LA = BM / 32, LB = BN / 32;
-    constexpr int NBLK = (BM + BN) / 32, NSB = NBLK / 4, SCL = NBLK * 256;
+    constexpr int LA = BM / RPP, LB = BN / RPP;
+    constexpr int NBLK = (BM + BN) / 32, NSB = NBLK / NWV, SCL = NBLK * 256;
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
     constexpr int NT = TM * TN, NSLOT = 4 * NT, NRD = 2 * (TM + TN), NLD = NSB + LA + LB;
     // Three register sets: X holds piece 2q, then 4+2q, then piece 2q of the next stage; Y holds piece
     // 2q+1; Z holds piece 4+2q+1.  Reads: Z in group 0, X again in group 1 (after group 0 consumed
@@ -958,7 +969,7 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
     uint8_t* const scl = lds + 2 * STG;
 
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave >> 1, wn = wave & 1, q = lane >> 5, r = lane & 31;
+    const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
     const int Kg4 = ((a.K >> 5) + 3) >> 2;
     const int rowbytes = a.K >> 1;
     const int nTA = rowbytes >> 7;
@@ -975,7 +986,7 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
     int ctile = xcd * per + (blockIdx.x >> 3);    // compute cursor
     if (ctile >= last) return;
 
-    // per-thread parts of the addresses: row (t >> 3) of a 32-row block, 16-byte piece c8
+    // per-thread parts of the addresses: row (t >> 3) of a block of RPP rows, 16-byte piece c8
     const uint32_t c8 = (uint32_t)((t & 7) ^ swz8(t >> 3)) * 16u;
     const uint32_t vo_main = (uint32_t)(t >> 3) * (uint32_t)rowbytes + c8;       // FP4 phase, both operands
     const uint32_t vo_ba = (uint32_t)(t >> 3) * (uint32_t)a.bpitch + c8;         // branch phase, B rows
@@ -990,7 +1001,7 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
     int nm0 = 0, nn0 = 0;      // position of this workgroup's tile after the one under the load cursor
     bool hasnext;
     const uint8_t *pa, *pb, *psa, *psb;  // A rows, B rows, A scale block, B scale block at this stage
-    uint32_t sa32, sb32;                 // bytes between consecutive 32-row blocks
+    uint32_t sa32, sb32;                 // bytes between consecutive blocks of RPP rows
     uint32_t voa, vob;                   // per-thread offsets in use
 #define PIPE2_TILE_POS(TILE_, M0_, N0_)                                                              \
     {                                                                                                \
@@ -1007,8 +1018,8 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
         const uint32_t ko__ = (uint32_t)(fp4__ ? lT : lT - nTA) * 128u;                              \
         const uint32_t pitcha__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.bpitch;                   \
         const uint32_t pitchb__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.wlpitch;                  \
-        sa32 = 32u * pitcha__;                                                                       \
-        sb32 = 32u * pitchb__;                                                                       \
+        sa32 = (uint32_t)RPP * pitcha__;                                                                       \
+        sb32 = (uint32_t)RPP * pitchb__;                                                                       \
         pa = (fp4__ ? a.Xq : a.B) + ((size_t)lm0 * pitcha__ + ko__);                                 \
         pb = (fp4__ ? wq : wl) + ((size_t)ln0 * pitchb__ + ko__);                                    \
         voa = fp4__ ? vo_main : vo_ba;                                                               \
@@ -1040,11 +1051,11 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
                                              4, 0, 0);                                               \
         } else if ((L_) < NSB + LA) {                                                                \
             const int i__ = (L_)-NSB;                                                                \
-            load_to_lds16(pa + (size_t)i__ * sa32 + voa, lds + (BUF_)*STG + wave * 1024 + i__ * 4096); \
+            load_to_lds16(pa + (size_t)i__ * sa32 + voa, lds + (BUF_)*STG + wave * 1024 + i__ * (RPP * 128)); \
         } else {                                                                                     \
             const int i__ = (L_)-NSB - LA;                                                           \
             load_to_lds16(pb + (size_t)i__ * sb32 + vob,                                             \
-                          lds + (BUF_)*STG + wave * 1024 + BM * 128 + i__ * 4096);                   \
+                          lds + (BUF_)*STG + wave * 1024 + BM * 128 + i__ * (RPP * 128));                   \
         }                                                                                            \
     }
 
@@ -1194,7 +1205,7 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
         ctp.row_end = a.M;
         ctp.wp = a.Wpack;
         ctp.valid = true;
-        store_result<MODE_DUAL, TM, TN>(a, ctp, acc);
+        store_result<MODE_DUAL, TM, TN, WN>(a, ctp, acc);
         if (done) break;
         ctile += step;
     }
@@ -1203,9 +1214,9 @@ __global__ void __launch_bounds__(GT) gemm_pipe2_kernel(KArgs a, int ntiles) {
 #undef PIPE2_FENCE
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int WN = 2>
 static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
@@ -1227,13 +1238,13 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
     }
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;  // workgroups that fit one CU's LDS
     const int64_t grid = ntiles < (int64_t)ncu * per_cu ? ntiles : (int64_t)ncu * per_cu;
-    auto kern = gemm_pipe2_kernel<TM, TN>;
+    auto kern = gemm_pipe2_kernel<TM, TN, WN>;
     if (smem > 64 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), smem, st, a, (int)ntiles);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a, (int)ntiles);
     return check_launch("gemm_pipe2_kernel");
 }
 
@@ -1454,9 +1465,9 @@ static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st)
     return check_launch("gemm_kernel");
 }
 
-template <int MODE, int TM, int TN>
+template <int MODE, int TM, int TN, int WN = 2>
 static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
@@ -1468,13 +1479,13 @@ static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
-    auto kern = gemm_dma2_kernel<MODE, TM, TN>;
+    auto kern = gemm_dma2_kernel<MODE, TM, TN, WN>;
     if (smem > 64 * 1024) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a);
     return check_launch("gemm_dma2_kernel");
 }
 
@@ -1547,19 +1558,25 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (!lines) return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
         if (tm == 1) tm = 2;
     }
-    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
+    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel,
+                                            // 4 = DMA kernel with eight wavefronts (256-row tiles only)
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
     if (kind == 1 && pipe_ok && tm == 4) kind = 2;
+    // FP8: the DMA kernel with eight wavefronts per workgroup is ~6 % faster than with four (the second
+    // wavefront of a SIMD fills the issue gaps of the first); the MXFP8 form of it does not fit 256 registers
+    if (MODE == MODE_FP8 && kind == 1 && tm == 4 && !grouped) kind = 4;
     const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && p.M <= 64;
     if (skinny_ok) kind = 3;  // decode-sized problems: the weight-streaming kernel
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
         if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
             if (tm != 1 && tm != 2 && tm != 4) tm = 2;
-            if ((k2 == 1 || k2 == 2) && !(lines && tm > 1)) k2 = 0;
+            if (k2 < 0 || k2 > 4) k2 = kind;
+            if ((k2 == 1 || k2 == 2 || k2 == 4) && !(lines && tm > 1)) k2 = 0;
+            if (k2 == 4 && (tm != 4 || MODE == MODE_MX8)) k2 = 1;
             if (k2 == 2 && !pipe_ok) k2 = 1;
             if (k2 == 3 && !skinny_ok) k2 = 0;
         }
@@ -1582,6 +1599,10 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
         return launch_pipe2<2, 2>(a, m_full, grouped, st);
     }
+    if (kind == 4) {  // 256x256 tiles on eight wavefronts (two per SIMD)
+        if constexpr (MODE != MODE_MX8) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
+    }
+
     if (kind >= 1 && grouped && tm == 4 && MODE != MODE_MX8) {
         // experts in 256-row tiles, and what is left of an expert whose last tile would be less than
         // half full in 64-row tiles (an expert of 270 rows: one big tile and one small one, not two

@@ -129,6 +129,21 @@ def quantize_mxfp4_osc(X, oidx=None, ldb=None):
     return Xq, Xs, B
 
 
+def quantize_mxfp4_dynamic(X, ldb=None):
+    """Dynamic protection: X uint16[M, K] -> (Xq, Xs, Bd uint16[M, ldb] dense, idx uint8[M, K/32])."""
+    X = _c(X, np.uint16)
+    M, K = X.shape
+    if ldb is None:
+        ldb = K
+    Xq = np.empty((M, K // 2), np.uint8)
+    Xs = np.empty((M, K // 32), np.uint8)
+    Bd = np.empty((M, ldb), np.uint16)
+    idx = np.empty((M, K // 32), np.uint8)
+    _check(lib().ref_quantize_mxfp4_dynamic(_p(X), i64(M), i64(K), i64(K), _p(Xq), _p(Xs), _p(Bd), i64(ldb),
+                                            _p(idx)), "ref_quantize_mxfp4_dynamic")
+    return Xq, Xs, Bd, idx
+
+
 def gather_wl(W, oidx):
     """W uint16[N, K] -> W_L uint16[K_o, N] (rows of the unquantised weight)."""
     W = _c(W, np.uint16)

@@ -15,6 +15,10 @@
  *                           OCP MX v1.0 MXFP4: one E8M0 scale per 32 elements,
  *                           shared exponent floor(log2 amax) - 2, E2M1 elements
  *                           rounded to nearest, ties to even, saturating.
+ *   ref_quantize_mxfp4_dynamic  the "Dynamic" protection control of Section 4.2 (Table 3,
+ *                           note 3): the protected element of a group is found
+ *                           at run time, per token, as the group's largest
+ *                           magnitude; everything else as in Alg. 2
  *   ref_gather_wl           W_L: rows of the high-precision weight named by
  *                           the same table (Section 3.3.1, second bullet)
  *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
@@ -228,6 +232,58 @@ int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
             for (int j = 0; j < G; ++j) {
                 uint16_t h = removed[g * G + j] ? (uint16_t)0 : x[g * G + j];
                 if ((h & 0x7F80) == 0x7F80) bad = 1;
+                v[j] = (double)bf16_to_float(h);
+                neg[j] = (h >> 15) & 1;
+                if (fabs(v[j]) > amax) amax = fabs(v[j]);
+            }
+            int e = mx_shared_exponent(amax);
+            Xs[m * Kg + g] = (uint8_t)(e + 127);
+            for (int j = 0; j < G; j += 2) {
+                int lo = ref_e2m1_encode(ldexp(v[j], -e), neg[j]);
+                int hi = ref_e2m1_encode(ldexp(v[j + 1], -e), neg[j + 1]);
+                Xq[m * (K / 2) + (g * G + j) / 2] = (uint8_t)(lo | (hi << 4));
+            }
+        }
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* Dynamic protection (Section 4.2: per-group maximum value detection at run time).  For every
+ * token and every group of 32 channels: j* = the position of the largest magnitude (the lowest
+ * position among equal magnitudes); that element is backed up, zeroed and the rest of the group
+ * is quantised as in Alg. 2.  The backed-up values are returned in the dense form of Alg. 2's
+ * buffer: Bd[m, c] = X[m, c] for the protected channel of each group, +0 elsewhere (Bd is
+ * [M, ldb], ldb >= K), and idx[m, g] = j* (may be NULL). */
+int ref_quantize_mxfp4_dynamic(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
+                               uint8_t *Xs, uint16_t *Bd, int64_t ldb, uint8_t *idx) {
+    if (M < 0 || K < 0 || K % G || ldx < K || ldb < K) return REF_ERR_ARG;
+    if (M == 0 || K == 0) return REF_OK;
+    if (!X || !Xq || !Xs || !Bd) return REF_ERR_ARG;
+    int64_t Kg = K / G;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        for (int64_t c = 0; c < ldb; ++c) Bd[m * ldb + c] = 0;
+        for (int64_t g = 0; g < Kg; ++g) {
+            int jstar = 0;
+            double best = -1.0;
+            for (int j = 0; j < G; ++j) {
+                uint16_t h = x[g * G + j];
+                if ((h & 0x7F80) == 0x7F80) bad = 1;
+                double a = fabs((double)bf16_to_float(h));
+                if (a > best) {
+                    best = a;
+                    jstar = j;
+                }
+            }
+            Bd[m * ldb + g * G + jstar] = x[g * G + jstar];
+            if (idx) idx[m * Kg + g] = (uint8_t)jstar;
+            double v[G];
+            int neg[G];
+            double amax = 0.0;
+            for (int j = 0; j < G; ++j) {
+                uint16_t h = j == jstar ? (uint16_t)0 : x[g * G + j];
                 v[j] = (double)bf16_to_float(h);
                 neg[j] = (h >> 15) & 1;
                 if (fabs(v[j]) > amax) amax = fabs(v[j]);

@@ -178,6 +178,24 @@ def main():
 
     ms_psum = time_one(lambda: prof_ring(0), reps=4 * nring)
     ms_phist = time_one(lambda: prof_ring(1), reps=4 * nring)
+    # "Dynamic" protection control (Section 4.2): run-time argmax quantiser, and the q projection
+    # with the bf16 branch over all K channels (what the scheme costs without per-token gathers)
+    dq = osc.osc_quantize_act_dynamic(dX1, want_idx=True)
+    ringD = [tuple(torch.empty_like(t) for t in dq) for _ in range(min(nring, 4))]
+
+    def dyn_ring():
+        i = turn[0] = (turn[0] + 1) % nring
+        osc.osc_quantize_act_dynamic(ringX[i], out=ringD[i % len(ringD)])
+
+    ms_dynq = time_one(dyn_ring, reps=4 * nring)
+    del ringD
+    all_ch = torch.arange(K_HID, dtype=torch.int32, device=dev)
+    Wd = up(wl.weights(2100, 4096, K_HID))
+    pack_dyn = osc.osc_pack_weight(Wd, all_ch)
+    del Wd
+    ms_dyng = time_one(lambda: osc.osc_dual_gemm(dq[0], dq[1], dq[2], pack_dyn, 4096, K_HID, K_HID, ydt,
+                                                 out=Y["q"]), reps=10)
+    del pack_dyn, dq
     del ringX, ringQ, ringF
 
     # the W_2 fallback at the down-projection shape of configs[2] (K = 12288 -> N = 4096), MXFP8
@@ -251,6 +269,14 @@ def main():
         "hist_roofline": {"bound": "hbm", "achieved": round(xbytes / (ms_phist * 1e-3) / 1e9, 1),
                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
                           "frac": round(xbytes / (ms_phist * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+    out["dynamic_control"] = {
+        "shape": f"M={M} K={K_HID} N=4096, one run-time protected element per group, Y bf16",
+        "quant_ms": round(ms_dynq, 4),
+        "quant_gbs": round(M * K_HID * (2 + 0.5 + 1 / 32 + 2 + 1 / 32) / (ms_dynq * 1e-3) / 1e9, 1),
+        "gemm_ms": round(ms_dyng, 4),
+        "osc_static_ms": {"quant": round(ms_quant, 4), "gemm_q": round(per["q"][0], 4)},
+        "slowdown_vs_osc": round((ms_dynq + ms_dyng) / (ms_quant + per["q"][0]), 2),
     }
     if args.detail:
         for k, v in out["kernels_ms"].items():

@@ -212,6 +212,23 @@ int osc_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, i
                           int64_t T, const void *Wpack, int64_t N, int64_t K, int32_t K_o,
                           void *Y, int y_dtype, int64_t ldy, void *stream);
 
+/*
+ * "Dynamic" protection, the control experiment of Section 4.2 (Table 3, note 3: per-group
+ * maximum value detection at run time).  Like osc_quantize_act(fmt = OSC_FMT_MXFP4_OSC) with
+ * one slot per group, except that the protected position is chosen per token: the largest
+ * magnitude of the group (the lowest position among equal magnitudes).
+ *   Bd   bf16 [M, ldb], ldb >= K, ldb % 8 == 0, 16-byte aligned: the backed-up values in
+ *        place (Bd[m, c] = X[m, c] for the protected channel of each group, +0 elsewhere).
+ *        With weights packed for all K channels (oidx = 0..K-1) it is the B operand of
+ *        osc_dual_gemm: on hardware without per-token gathers the scheme costs a full
+ *        bf16 branch, which is the overhead the static table removes.
+ *   idx  uint8 [M, K/32] or NULL: the chosen local positions (4-byte aligned)
+ *   Xq, Xs as for OSC_FMT_MXFP4_OSC.
+ * Errors as osc_quantize_act.
+ */
+int osc_quantize_act_dynamic(const void *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
+                             void *Xs, void *Bd, int64_t ldb, uint8_t *idx, void *stream);
+
 /* ---- offline profiling (calibration) ------------------------------------------ */
 
 /*

@@ -36,6 +36,7 @@ _SIGS = {
     "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
     "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
+    "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
     "osc_profile_hist": (C.c_int, [vp, i64, i64, i64, i32, vp, vp, vp]),
@@ -301,3 +302,22 @@ def osc_profile_table(hist, R=1):
     _check(lib().osc_profile_table(_ptr(hist), Kg, G, R, _ptr(table), _ptr(n_total), _ptr(n_hit), _ptr(density),
                                    _ptr(cbar), _stream()))
     return table, n_total, n_hit, density, cbar
+
+
+def osc_quantize_act_dynamic(X, ldb=None, want_idx=True, out=None):
+    """Dynamic protection -> (Xq, Xs, Bd uint16 [M, ldb] dense, idx uint8 [M, K/32] or None)."""
+    X = _rows16(X)
+    M, K = X.shape
+    dev = X.device
+    if ldb is None:
+        ldb = K
+    if out is not None:
+        Xq, Xs, Bd, idx = out
+    else:
+        Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        Xs = torch.empty(osc_act_scale_bytes(M, K), dtype=torch.uint8, device=dev)
+        Bd = torch.empty((M, ldb), dtype=torch.uint16, device=dev)
+        idx = torch.empty((M, K // 32), dtype=torch.uint8, device=dev) if want_idx else None
+    _check(lib().osc_quantize_act_dynamic(_ptr(X), M, K, X.stride(0), _ptr(Xq), _ptr(Xs), _ptr(Bd), ldb, _ptr(idx),
+                                          _stream()))
+    return Xq, Xs, Bd, idx

@@ -274,6 +274,20 @@ int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int
                               as_stream(stream));
 }
 
+int osc_quantize_act_dynamic(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, void* Xs, void* Bd,
+                             int64_t ldb, uint8_t* idx, void* stream) {
+    int rc = check_mx_shape("osc_quantize_act_dynamic", M, K, ldx, 0);
+    if (rc) return rc;
+    REQUIRE(ldb >= K, OSC_ERR_SHAPE, "osc_quantize_act_dynamic: ldb=%lld < K=%lld", (long long)ldb, (long long)K);
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(X && Xq && Xs && Bd, OSC_ERR_NULL, "osc_quantize_act_dynamic: null pointer");
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 4) && aligned(Xs, 4) && ldb % 8 == 0 && aligned(Bd, 16) &&
+                aligned(idx, 4),
+            OSC_ERR_UNSUPPORTED, "osc_quantize_act_dynamic: misaligned pointer or leading dimension");
+    return launch_quant_mxfp4_dynamic(static_cast<const uint16_t*>(X), M, K, ldx, Xq, static_cast<uint8_t*>(Xs),
+                                      static_cast<uint16_t*>(Bd), ldb, idx, as_stream(stream));
+}
+
 static int check_gemm_common(const char* who, int64_t M, int64_t N, int64_t K, const void* Y, int y_dtype,
                              int64_t ldy) {
     REQUIRE(M >= 0 && N >= 0 && K >= 0, OSC_ERR_SHAPE, "%s: negative extent", who);

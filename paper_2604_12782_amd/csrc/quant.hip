@@ -207,6 +207,118 @@ int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, con
     return check_launch("quant_mxfp4_osc_kernel");
 }
 
+// ------------------------------------------------------------------------------------------
+// "Dynamic" protection (Section 4.2; Table 3, note 3): the protected element of every group is
+// found at run time, token by token.  Same work split as the kernel above, no table: the sort key
+// (magnitude bits << 5) | (31 - position) makes "largest magnitude, lowest position" one unsigned
+// maximum over the group's quad of lanes; the owning lane moves that element into the dense
+// backup row Bd (every lane stores its 16-byte chunk of Bd: zeros but for that element) and
+// zeroes it; the rest is quantised as in Alg. 2.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(QT) quant_mxfp4_dynamic_kernel(const uint16_t* __restrict__ X, int M, int K,
+                                                                 int64_t ldx, uint8_t* __restrict__ Xq,
+                                                                 uint8_t* __restrict__ Xs,
+                                                                 uint16_t* __restrict__ Bd, int64_t ldb,
+                                                                 uint8_t* __restrict__ idx, int nseg,
+                                                                 int total_wg) {
+    const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
+    const int nchunk = K >> 3;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t kbase = 31u - (uint32_t)((lane & 3) * 8);
+    for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
+        const QItem cur = quant_item(wg, wave, nseg, M);
+        if (cur.m < 0) continue;
+        const int m = cur.m;
+        const u32x4* src = reinterpret_cast<const u32x4*>(X + (int64_t)m * ldx);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(Xq + (int64_t)m * (K >> 1));
+        uint8_t* sdst = Xs + (int64_t)(m >> 5) * Kg4 * 128 + (m & 31) * 4;
+        u32x4* bdst = reinterpret_cast<u32x4*>(Bd + (int64_t)m * ldb);
+        u32x4 v[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = cur.seg * SEG_CHUNKS + lane + 64 * i;
+            v[i] = (u32x4){0u, 0u, 0u, 0u};
+            if (c < nchunk) v[i] = __builtin_nontemporal_load(src + c);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = cur.seg * SEG_CHUNKS + lane + 64 * i;
+            uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            // Eq. 2 at run time: position of the group's largest magnitude
+            uint32_t k = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                k = max(k, ((w[e] & 0x7fffu) << 5) | (kbase - 2 * e));
+                k = max(k, (((w[e] >> 16) & 0x7fffu) << 5) | (kbase - 2 * e - 1));
+            }
+            k = max(k, (uint32_t)__builtin_amdgcn_mov_dpp((int)k, 0xB1, 0xF, 0xF, true));  // lane ^ 1
+            k = max(k, (uint32_t)__builtin_amdgcn_mov_dpp((int)k, 0x4E, 0xF, 0xF, true));  // lane ^ 2
+            const int jstar = 31 - (int)(k & 31u);
+            // back-up and zero (steps 2-3 of Section 3.2, with the index of this token)
+            uint32_t b[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int p0 = (lane & 3) * 8 + 2 * e;  // position of the low half of word e
+                const uint32_t mask = jstar == p0 ? 0x0000ffffu : jstar == p0 + 1 ? 0xffff0000u : 0u;
+                b[e] = w[e] & mask;
+                w[e] &= ~mask;
+            }
+            if (c < nchunk) __builtin_nontemporal_store((u32x4){b[0], b[1], b[2], b[3]}, bdst + c);
+            // scale of what is left
+            const uint32_t a0 = w[0] & 0x7fff7fffu, a1 = w[1] & 0x7fff7fffu, a2 = w[2] & 0x7fff7fffu,
+                           a3 = w[3] & 0x7fff7fffu;
+            uint32_t a = max(max(a0 & 0xffffu, a0 >> 16), max(a1 & 0xffffu, a1 >> 16));
+            a = max(a, max(max(a2 & 0xffffu, a2 >> 16), max(a3 & 0xffffu, a3 >> 16)));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true));
+            const uint32_t code = (uint32_t)max((int)(a >> 7) - 2, 0);
+            uint32_t word = code, iword = (uint32_t)jstar;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;
+            iword |= (uint32_t)__builtin_amdgcn_update_dpp(0, jstar, 0x104, 0xF, 0xF, true) << 8;
+            iword |= (uint32_t)__builtin_amdgcn_update_dpp(0, jstar, 0x108, 0xF, 0xF, true) << 16;
+            iword |= (uint32_t)__builtin_amdgcn_update_dpp(0, jstar, 0x10C, 0xF, 0xF, true) << 24;
+            if ((lane & 15) == 0 && c < nchunk) {
+                *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+                if (idx) {
+                    // four positions of four consecutive groups; a row's last word may be partly past Kg
+                    uint8_t* ip = idx + (int64_t)m * Kg + (c >> 2);
+                    const int left = Kg - (c >> 2);
+                    if (left >= 4 && ((Kg & 3) == 0)) *reinterpret_cast<uint32_t*>(ip) = iword;
+                    else
+                        for (int e = 0; e < 4 && e < left; ++e) ip[e] = (uint8_t)(iword >> (8 * e));
+                }
+            }
+            const float scale = __builtin_bit_cast(float, code << 23);
+            uint32_t out = 0;
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[0]), scale, 0);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[1]), scale, 1);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[2]), scale, 2);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w[3]), scale, 3);
+            if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
+        }
+        // padding columns of Bd (ldb > K): +0, written by the wavefront of the last segment
+        if (cur.seg == nseg - 1)
+            for (int64_t o = K + lane; o < ldb; o += 64) Bd[(int64_t)m * ldb + o] = 0;
+    }
+}
+
+int launch_quant_mxfp4_dynamic(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, uint8_t* Xs,
+                               uint16_t* Bd, int64_t ldb, uint8_t* idx, hipStream_t st) {
+    if (K > 65536) return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld exceeds 65536", (long long)K);
+    const int64_t nchunk = K / 8;
+    const int nseg = (int)((nchunk + SEG_CHUNKS - 1) / SEG_CHUNKS);
+    const int64_t blocks = (M + 31) / 32;
+    const int64_t total_wg = (blocks + 7) / 8 * 8 * (8 * nseg);
+    if (total_wg > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "quantize: M=%lld too large", (long long)M);
+    const int64_t cap = 4096;
+    const int grid = (int)(total_wg < cap ? total_wg : cap);
+    hipLaunchKernelGGL(quant_mxfp4_dynamic_kernel, dim3(grid), dim3(QT), 0, st, X, (int)M, (int)K, ldx, Xq, Xs,
+                       Bd, ldb, idx, nseg, (int)total_wg);
+    return check_launch("quant_mxfp4_dynamic_kernel");
+}
+
 // Row-block-major scales -> plain [rows, K/32].
 __global__ void scales_to_rowmajor_kernel(const uint8_t* __restrict__ S, int64_t rows, int Kg,
                                           uint8_t* __restrict__ out) {

@@ -101,6 +101,12 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert m8(FAKE, FAKE, FAKE, 4, 64, 96, None, 0, FAKE, 0, 64, None) == -4  # K % 128
     assert m8(FAKE, None, FAKE, 4, 64, 128, None, 0, FAKE, 0, 64, None) == -1
     assert q(FAKE, 4, 48, 48, None, 0, 2, FAKE, FAKE, None, 0, None) == -2  # MXFP8 quantiser, K % 32
+    dq = lib.osc_quantize_act_dynamic
+    assert dq(FAKE, 4, 64, 64, FAKE, FAKE, FAKE, 32, None, None) == -2   # ldb < K
+    assert dq(FAKE, 4, 48, 48, FAKE, FAKE, FAKE, 48, None, None) == -2   # K % 32
+    assert dq(FAKE, 4, 64, 64, FAKE, FAKE, None, 64, None, None) == -1
+    assert dq(FAKE, 4, 64, 64, FAKE, FAKE, FAKE, 64, FAKE + 1, None) == -4
+    assert dq(None, 0, 64, 64, None, None, None, 64, None, None) == 0
     # offline profiling
     a = lib.osc_profile_abs_sum
     assert a(None, 4, 64, 64, FAKE, None) == -1 and a(FAKE, 4, 64, 64, None, None) == -1

@@ -1,0 +1,68 @@
+"""The hot path under HIP graph capture: no entry point allocates, synchronises or enqueues a
+memset, so a step (quantise+gather, dual GEMM, FP8 quantise, FP8 GEMM) can be captured once and
+replayed.  Every replay is compared with the eager result, with eager work and synchronisations of
+the same entry points between the replays."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def osc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2604_12782_amd as m
+    m.lib()
+    return m
+
+
+@pytest.mark.parametrize("M", [48, 1000])
+def test_step_replays_equal_eager(osc, M):
+    K, N = 1024, 768
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Xa, table = wl.activations_persistent(4001, M, K, 2)
+    Xb = wl.activations_diffuse(4002, M, K)
+    oidx = up(osc.osc_table_to_index(table))
+    K_o = int(oidx.numel())
+    W = up(wl.weights(4003, N, K))
+    Wp, W8 = osc.osc_pack_weight(W, oidx), osc.osc_pack_weight_fp8(W)
+    X = up(Xa)
+    q = osc.osc_quantize_act(X, oidx)
+    f = osc.osc_quantize_act(X, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    Y1 = torch.empty((M, N), dtype=torch.float32, device=dev)
+    Y2 = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+
+    def step():
+        osc.osc_quantize_act(X, oidx, out=q)
+        osc.osc_dual_gemm(*q, Wp, N, K, K_o, osc.OSC_DT_F32, out=Y1)
+        osc.osc_quantize_act(X, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f)
+        osc.osc_fp8_gemm(*f, W8, N, K, y_dtype=osc.OSC_DT_BF16, out=Y2)
+
+    def eager(bits):
+        X.copy_(up(bits))
+        step()
+        torch.cuda.synchronize()
+        return Y1.clone(), Y2.clone(), q[0].clone()
+
+    ref_a, ref_b = eager(Xa), eager(Xb)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i, (bits, ref) in enumerate([(Xa, ref_a), (Xb, ref_b), (Xa, ref_a), (Xb, ref_b)]):
+        X.copy_(up(bits))
+        Y1.zero_(); Y2.zero_(); q[0].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y1, ref[0]) and torch.equal(Y2, ref[1]) and torch.equal(q[0], ref[2]), f"replay {i}"
+        # eager work of the same entry points between replays
+        osc.osc_dual_gemm(*q, Wp, N, K, K_o, osc.OSC_DT_F32, out=torch.empty_like(Y1))
+        torch.cuda.synchronize()

@@ -846,6 +846,25 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
         buf ^= 1;                                                                              \
     }
 
+    // FP8 stage with one pair of fragment sets, for two wavefronts per SIMD (the other wavefront
+    // covers the wait between the two halves; 2 % faster there than the four-set stage)
+#define OSC_D2_STAGE_FP8_LEAN(T_)                                                              \
+    {                                                                                          \
+        OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
+        OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
+        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, LA, 0, LB)                        \
+        OSC_MFMA_FP8(0, TM * TN, fa0, fa1, fb0, fb1)                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
+        OSC_F2(buf, 4 + 2 * q + 1, fa1, fb1)                                                   \
+        OSC_MFMA_FP8(0, TM * TN, fa0, fa1, fb0, fb1)                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        buf ^= 1;                                                                              \
+    }
+
     // MXFP8 stage.  With 8-bit operands the 32x32x64 instruction takes, from lane half q, elements
     // 16q .. 16q+15 of each of its two 32-element scale blocks (registers 0-3: block 0, registers
     // 4-7: block 1), and the scale of block b from the lanes of half b.  So the MFMA that handles
@@ -889,10 +908,39 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
         __builtin_amdgcn_sched_barrier(0);                                                     \
         buf ^= 1;                                                                              \
     }
+    // the same stage with one pair of fragment sets, for two wavefronts per SIMD (the other
+    // wavefront covers the wait between the two halves, and four sets do not fit 256 registers)
+#define OSC_D2_STAGE_MX8_LEAN(T_)                                                              \
+    {                                                                                          \
+        int sa[TM], sb[TN];                                                                    \
+        OSC_F2(buf, q, fa0, fb0)                                                               \
+        OSC_F2(buf, 2 + q, fa1, fb1)                                                           \
+        OSC_D2_READ_SCALES(buf, 0, sa, sb)                                                     \
+        if ((T_) + 1 < nT) {                                                                   \
+            OSC_D2_SCALES((T_) + 1, buf ^ 1)                                                   \
+            OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, LA, 0, LB)                                       \
+        }                                                                                      \
+        OSC_MFMA_MX8(0, fa0, fa1, fb0, fb1, sa, sb)                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        OSC_F2(buf, 4 + q, fa0, fb0)                                                           \
+        OSC_F2(buf, 6 + q, fa1, fb1)                                                           \
+        OSC_MFMA_MX8(2, fa0, fa1, fb0, fb1, sa, sb)                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        wait_vmcnt<0>();                                                                       \
+        __syncthreads();                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        buf ^= 1;                                                                              \
+    }
 
-    if (MODE == MODE_MX8) {
+    if (MODE == MODE_MX8 && WN == 4) {
+#pragma unroll 1
+        for (int T = 0; T < nT; ++T) OSC_D2_STAGE_MX8_LEAN(T)
+    } else if (MODE == MODE_MX8) {
 #pragma unroll 1
         for (int T = 0; T < nT; ++T) OSC_D2_STAGE_MX8(T)
+    } else if (MODE == MODE_FP8 && WN == 4) {
+#pragma unroll 1
+        for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8_LEAN(T)
     } else if (MODE == MODE_FP8) {
 #pragma unroll 1
         for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8(T)
@@ -1558,25 +1606,20 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (!lines) return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
         if (tm == 1) tm = 2;
     }
-    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel,
-                                            // 4 = DMA kernel with eight wavefronts (256-row tiles only)
+    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
     if (kind == 1 && pipe_ok && tm == 4) kind = 2;
-    // FP8: the DMA kernel with eight wavefronts per workgroup is ~6 % faster than with four (the second
-    // wavefront of a SIMD fills the issue gaps of the first); the MXFP8 form of it does not fit 256 registers
-    if (MODE == MODE_FP8 && kind == 1 && tm == 4 && !grouped) kind = 4;
     const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && p.M <= 64;
     if (skinny_ok) kind = 3;  // decode-sized problems: the weight-streaming kernel
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
         if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
             if (tm != 1 && tm != 2 && tm != 4) tm = 2;
-            if (k2 < 0 || k2 > 4) k2 = kind;
-            if ((k2 == 1 || k2 == 2 || k2 == 4) && !(lines && tm > 1)) k2 = 0;
-            if (k2 == 4 && (tm != 4 || MODE == MODE_MX8)) k2 = 1;
+            if (k2 < 0 || k2 > 3) k2 = kind;
+            if ((k2 == 1 || k2 == 2) && !(lines && tm > 1)) k2 = 0;
             if (k2 == 2 && !pipe_ok) k2 = 1;
             if (k2 == 3 && !skinny_ok) k2 = 0;
         }
@@ -1599,16 +1642,13 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
         return launch_pipe2<2, 2>(a, m_full, grouped, st);
     }
-    if (kind == 4) {  // 256x256 tiles on eight wavefronts (two per SIMD)
-        if constexpr (MODE != MODE_MX8) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
-    }
 
     if (kind >= 1 && grouped && tm == 4 && MODE != MODE_MX8) {
         // experts in 256-row tiles, and what is left of an expert whose last tile would be less than
         // half full in 64-row tiles (an expert of 270 rows: one big tile and one small one, not two
         // big ones)
         a.grp_mode = 1;
-        const int rc = launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
+        const int rc = launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
         if (rc != OSC_OK) return rc;
         a.grp_mode = 2;
         a.grp_bm = 256;
@@ -1617,7 +1657,9 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
                           : launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
     }
     if (kind >= 1) {
-        if (tm == 4) return launch_dma2<MODE, 4, 4>(a, p.M, grouped, st);
+        // 256-row tiles run on eight wavefronts (2 x 4, 128x64 each): 6-8 % faster than four, the second
+        // wavefront of a SIMD fills the issue gaps of the first
+        if (tm == 4) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
         return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
     }
     if constexpr (MODE == MODE_MX8) {

@@ -144,6 +144,16 @@ def quantize_mxfp4_dynamic(X, ldb=None):
     return Xq, Xs, Bd, idx
 
 
+def rmsnorm(X, gamma, eps=1e-6):
+    """Order-free RMSNorm (see ref_rmsnorm): X uint16[M, K], gamma uint16[K] -> Y uint16[M, K]."""
+    X, gamma = _c(X, np.uint16), _c(gamma, np.uint16)
+    M, K = X.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().ref_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_double, i64, i64, i64, C.c_void_p]
+    _check(lib().ref_rmsnorm(_p(X), _p(gamma), float(np.float32(eps)), M, K, K, _p(Y)), "ref_rmsnorm")
+    return Y
+
+
 def gather_wl(W, oidx):
     """W uint16[N, K] -> W_L uint16[K_o, N] (rows of the unquantised weight)."""
     W = _c(W, np.uint16)

@@ -19,6 +19,11 @@
  *                           note 3): the protected element of a group is found
  *                           at run time, per token, as the group's largest
  *                           magnitude; everything else as in Alg. 2
+ *   ref_rmsnorm             the normalisation that produces the inputs of the attention
+ *                           and FFN projections (positions 1 and 3 of Section 2.1,
+ *                           Figure 1), in a form whose result does not depend on
+ *                           the order of any summation, so that a producer fused
+ *                           with the quantiser can be compared bit for bit
  *   ref_gather_wl           W_L: rows of the high-precision weight named by
  *                           the same table (Section 3.3.1, second bullet)
  *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
@@ -243,6 +248,55 @@ int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                 int hi = ref_e2m1_encode(ldexp(v[j + 1], -e), neg[j + 1]);
                 Xq[m * (K / 2) + (g * G + j) / 2] = (uint8_t)(lo | (hi << 4));
             }
+        }
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* RMSNorm, y = x / sqrt(mean(x^2) + eps) * gamma, defined so that every step is exact or a single
+ * correctly rounded IEEE operation, none of which depends on an order of summation:
+ *   1. e = the largest biased exponent field of the row (a subnormal counts as 1);
+ *   2. every |x| = m * 2^(E - 134) with an 8-bit integer m (hidden bit included) and E >= 1; its
+ *      square enters a 64-bit fixed-point sum in units of 2^(2e - 298):
+ *      S = sum of floor(m^2 * 2^30 / 2^(2(e - E)))   (terms more than 2^46 below the largest vanish);
+ *   3. mean = (double)S * 2^(2e - 298) / K, r = (float)(1 / sqrt(mean + eps)) in double arithmetic;
+ *   4. t = bf16(x * r) with one single-precision multiplication, y = bf16(t * gamma) (that product
+ *      is exact in single precision); bf16() rounds to nearest, ties to even.
+ * X, Y: bf16 bits [M, K] (row strides ldx, K); gamma: bf16 bits [K]. */
+static uint16_t float_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int ref_rmsnorm(const uint16_t *X, const uint16_t *gamma, double eps, int64_t M, int64_t K, int64_t ldx,
+                uint16_t *Y) {
+    if (M < 0 || K <= 0 || K > 65536 || ldx < K || !X || !gamma || !Y) return REF_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        int e = 1;
+        for (int64_t j = 0; j < K; ++j) {
+            if ((x[j] & 0x7F80) == 0x7F80) bad = 1;
+            int E = (x[j] >> 7) & 0xFF;
+            if (E > e) e = E;
+        }
+        uint64_t S = 0;
+        for (int64_t j = 0; j < K; ++j) {
+            int E = (x[j] >> 7) & 0xFF;
+            uint64_t mant = x[j] & 0x7F;
+            if (E == 0) E = 1; else mant |= 0x80;
+            int sh = 2 * (e - E);
+            if (sh < 64) S += ((mant * mant) << 30) >> sh;
+        }
+        double mean = ldexp((double)S, 2 * e - 298) / (double)K;
+        float r = (float)(1.0 / sqrt(mean + eps));
+        for (int64_t j = 0; j < K; ++j) {
+            if ((gamma[j] & 0x7F80) == 0x7F80) bad = 1;
+            float t = bf16_to_float(float_to_bf16_rne(bf16_to_float(x[j]) * r));
+            Y[m * K + j] = float_to_bf16_rne(t * bf16_to_float(gamma[j]));
         }
     }
     return bad ? REF_ERR_NONFINITE : REF_OK;

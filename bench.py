@@ -178,6 +178,15 @@ def main():
 
     ms_psum = time_one(lambda: prof_ring(0), reps=4 * nring)
     ms_phist = time_one(lambda: prof_ring(1), reps=4 * nring)
+    # producer fusion: RMSNorm + OSC quantiser in one pass (same ring)
+    gam = up(wl.to_bf16_bits((1.0 + 0.1 * wl.rng(2200).standard_normal(K_HID)).astype(np.float32)))
+
+    def fused_ring():
+        i = turn[0] = (turn[0] + 1) % nring
+        osc.osc_rmsnorm_quantize_act(ringX[i], gam, 1e-6, oidx1, out=(ringQ[i][0], ringQ[i][1], ringQ[i][2], None))
+
+    ms_fused = time_one(fused_ring, reps=4 * nring)
+
     # Table 2 of the paper on this machine: one protected channel per group of G = 16, 32, 64
     # (K_o = K/G), a compute-bound GEMM (M tokens, 4096 x 4096) and a decode-sized one (64 tokens,
     # 4096 -> 12288), each against the FP8 W8A8 GEMM of the same shape.  The decode-sized kernels
@@ -322,6 +331,12 @@ def main():
         "hist_roofline": {"bound": "hbm", "achieved": round(xbytes / (ms_phist * 1e-3) / 1e9, 1),
                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
                           "frac": round(xbytes / (ms_phist * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+    }
+    out["fused_rmsnorm_quant"] = {
+        "shape": f"M={M} K={K_HID} K_o={K_o}", "ms": round(ms_fused, 4),
+        "roofline": {"bound": "hbm", "achieved": round(quant_bytes / (ms_fused * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(quant_bytes / (ms_fused * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        "unfused_quant_ms": round(ms_quant, 4),
     }
     out["table2_sweep"] = t2
     out["dynamic_control"] = {

@@ -213,6 +213,25 @@ int osc_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, i
                           void *Y, int y_dtype, int64_t ldy, void *stream);
 
 /*
+ * RMSNorm fused with the OSC-enhanced quantiser: what osc_quantize_act(fmt = OSC_FMT_MXFP4_OSC)
+ * returns for the normalised row y = x / sqrt(mean(x^2) + eps) * gamma, without y passing
+ * through memory (the inputs of the attention and FFN projections, positions 1 and 3 of
+ * Section 2.1, are RMSNorm outputs).  The normalisation is defined so that its result does not
+ * depend on any order of summation:
+ *   e    = the largest biased bf16 exponent field of the row (at least 1);
+ *   S    = sum over the row of floor(m^2 * 2^30 / 4^(e - E)), |x| = m * 2^(E - 134), m an 8-bit
+ *          integer, E >= 1 (64-bit integer; terms 2^46 below the largest vanish);
+ *   r    = (float)(1 / sqrt((double)S * 2^(2e - 298) / K + eps)), double arithmetic;
+ *   y    = bf16(bf16(x * r) * gamma), single-precision products, round to nearest even.
+ *   gamma  bf16 [K] (device), 16-byte aligned;  eps >= 0
+ *   Xn     bf16 [M, K] (device) or NULL: receives y when given
+ *   K <= 12288; everything else as osc_quantize_act.
+ */
+int osc_rmsnorm_quantize_act(const void *X, const void *gamma, float eps, int64_t M, int64_t K,
+                             int64_t ldx, const int32_t *oidx, int32_t K_o, uint8_t *Xq, void *Xs,
+                             void *B, int64_t ldb, void *Xn, void *stream);
+
+/*
  * "Dynamic" protection, the control experiment of Section 4.2 (Table 3, note 3: per-group
  * maximum value detection at run time).  Like osc_quantize_act(fmt = OSC_FMT_MXFP4_OSC) with
  * one slot per group, except that the protected position is chosen per token: the largest

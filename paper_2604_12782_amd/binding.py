@@ -36,6 +36,7 @@ _SIGS = {
     "osc_quantize_act": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, vp, vp, vp, i64, vp]),
     "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
+    "osc_rmsnorm_quantize_act": (C.c_int, [vp, vp, C.c_float, i64, i64, i64, vp, i32, vp, vp, vp, i64, vp, vp]),
     "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
@@ -321,3 +322,24 @@ def osc_quantize_act_dynamic(X, ldb=None, want_idx=True, out=None):
     _check(lib().osc_quantize_act_dynamic(_ptr(X), M, K, X.stride(0), _ptr(Xq), _ptr(Xs), _ptr(Bd), ldb, _ptr(idx),
                                           _stream()))
     return Xq, Xs, Bd, idx
+
+
+def osc_rmsnorm_quantize_act(X, gamma, eps=1e-6, oidx=None, ldb=None, want_norm=False, out=None):
+    """RMSNorm + OSC quantiser in one pass -> (Xq, Xs, B, Xn or None)."""
+    X = _rows16(X)
+    M, K = X.shape
+    dev = X.device
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if out is not None:
+        Xq, Xs, B, Xn = out
+        ldb = 0 if B is None else B.stride(0)
+    else:
+        if ldb is None:
+            ldb = (K_o + 63) // 64 * 64
+        Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        Xs = torch.empty(osc_act_scale_bytes(M, K), dtype=torch.uint8, device=dev)
+        B = torch.empty((M, ldb), dtype=torch.uint16, device=dev) if ldb else None
+        Xn = torch.empty((M, K), dtype=torch.uint16, device=dev) if want_norm else None
+    _check(lib().osc_rmsnorm_quantize_act(_ptr(X), _ptr(gamma), eps, M, K, X.stride(0), _ptr(oidx), K_o, _ptr(Xq),
+                                          _ptr(Xs), _ptr(B), ldb, _ptr(Xn), _stream()))
+    return Xq, Xs, B, Xn

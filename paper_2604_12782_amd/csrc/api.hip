@@ -274,6 +274,24 @@ int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int
                               as_stream(stream));
 }
 
+int osc_rmsnorm_quantize_act(const void* X, const void* gamma, float eps, int64_t M, int64_t K, int64_t ldx,
+                             const int32_t* oidx, int32_t K_o, uint8_t* Xq, void* Xs, void* B, int64_t ldb, void* Xn,
+                             void* stream) {
+    int rc = check_mx_shape("osc_rmsnorm_quantize_act", M, K, ldx, K_o);
+    if (rc) return rc;
+    REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "osc_rmsnorm_quantize_act: ldb=%lld < K_o=%d", (long long)ldb, K_o);
+    REQUIRE(eps >= 0.0f, OSC_ERR_SHAPE, "osc_rmsnorm_quantize_act: negative eps");
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(X && gamma && Xq && Xs, OSC_ERR_NULL, "osc_rmsnorm_quantize_act: null pointer");
+    REQUIRE(K_o == 0 || (oidx && B), OSC_ERR_NULL, "osc_rmsnorm_quantize_act: K_o > 0 needs oidx and B");
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(gamma, 16) && aligned(Xq, 4) && aligned(Xs, 4) && aligned(Xn, 16),
+            OSC_ERR_UNSUPPORTED, "osc_rmsnorm_quantize_act: misaligned pointer or ldx %% 8 != 0");
+    if (B) REQUIRE(ldb >= 0, OSC_ERR_SHAPE, "osc_rmsnorm_quantize_act: negative ldb");
+    return launch_rmsnorm_quant_mxfp4(static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(gamma), eps, M, K,
+                                      ldx, oidx, K_o, Xq, static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(B),
+                                      B ? ldb : 0, static_cast<uint16_t*>(Xn), as_stream(stream));
+}
+
 int osc_quantize_act_dynamic(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, void* Xs, void* Bd,
                              int64_t ldb, uint8_t* idx, void* stream) {
     int rc = check_mx_shape("osc_quantize_act_dynamic", M, K, ldx, 0);

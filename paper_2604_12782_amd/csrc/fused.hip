@@ -1,0 +1,185 @@
+// Producer fusion: RMSNorm (the operation in front of the attention and FFN projections, positions
+// 1 and 3 of Section 2.1) and the OSC-enhanced quantiser (Section 3.2, Alg. 2) in one pass over
+// the row, so that the normalised activations never travel through HBM.
+#include "osc_internal.h"
+#include "wave_util.h"
+
+namespace osc {
+
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int FT = 256;  // four wavefronts, one row each at a time
+
+// bf16(a * r) for the two halves of a packed word, one single-precision multiplication each
+__device__ __forceinline__ uint32_t scale_pair(uint32_t w, float r) {
+    const uint32_t lo = w << 16, hi = w & 0xffff0000u;
+    const v2f p = {__builtin_bit_cast(float, lo) * r, __builtin_bit_cast(float, hi) * r};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, v2bf));
+}
+// bf16(t * g), element by element (the product of two bf16 values is exact in single precision)
+__device__ __forceinline__ uint32_t mul_pair(uint32_t t, uint32_t g) {
+    const uint32_t tl = t << 16, th = t & 0xffff0000u, gl = g << 16, gh = g & 0xffff0000u;
+    const v2f p = {__builtin_bit_cast(float, tl) * __builtin_bit_cast(float, gl),
+                   __builtin_bit_cast(float, th) * __builtin_bit_cast(float, gh)};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, v2bf));
+}
+// one element's term of the fixed-point sum of squares (units of 2^(2e - 298))
+__device__ __forceinline__ uint64_t sq_term(uint32_t h, int e) {
+    int E = (h >> 7) & 0xff;
+    uint32_t m = h & 0x7fu;
+    if (E == 0) E = 1;
+    else m |= 0x80u;
+    const int sh = 2 * (e - E);
+    return sh < 64 ? ((uint64_t)(m * m) << 30) >> sh : 0ull;
+}
+
+// A wavefront owns a whole row: lane l holds the 16-byte chunks l, l + 64, ... (NCI of them), so
+// the two row-wide reductions (largest exponent, sum of squares) are register work plus DPP.
+// The sum of squares is an integer in fixed point relative to the row's largest exponent: exact
+// up to a truncation 2^-46 below the largest term and independent of any order, so the
+// normalised row, and every code derived from it, is reproducible bit for bit.
+// LDS: per-wave strip of the normalised row (for the gather) | keep masks | gamma | channel list.
+template <int NCI>
+__global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ gamma, double eps, int M, int K, int64_t ldx,
+    const int32_t* __restrict__ oidx, int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs,
+    uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ Xn) {
+    extern __shared__ uint32_t smem[];
+    const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
+    const int nchunk = K >> 3;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    u32x4* strip = reinterpret_cast<u32x4*>(smem) + wave * (NCI * 64);
+    uint32_t* keep = smem + 4 * NCI * 64 * 4;
+    u32x4* gam = reinterpret_cast<u32x4*>(keep + (K >> 1));
+    uint16_t* och = reinterpret_cast<uint16_t*>(gam + nchunk);
+
+    for (int i = t; i < (K >> 1); i += FT) keep[i] = 0xffffffffu;
+    for (int i = t; i < nchunk; i += FT) gam[i] = reinterpret_cast<const u32x4*>(gamma)[i];
+    __syncthreads();
+    for (int o = t; o < K_o; o += FT) {
+        const int c = oidx[o];
+        if (c >= 0 && c < K) atomicAnd(&keep[c >> 1], (c & 1) ? 0x0000ffffu : 0xffff0000u);
+        och[o] = (uint16_t)c;
+    }
+    __syncthreads();
+
+    for (int m = blockIdx.x * 4 + wave; m < M; m += gridDim.x * 4) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(X + (int64_t)m * ldx);
+        u32x4 v[NCI];
+#pragma unroll
+        for (int i = 0; i < NCI; ++i) {
+            const int c = lane + 64 * i;
+            v[i] = (u32x4){0u, 0u, 0u, 0u};
+            if (c < nchunk) v[i] = __builtin_nontemporal_load(src + c);
+        }
+        // largest exponent of the row
+        uint32_t amax = 0;
+#pragma unroll
+        for (int i = 0; i < NCI; ++i) {
+            const u32x4 ab = v[i] & 0x7fff7fffu;
+            amax = max(amax, max(max(ab.x & 0xffffu, ab.x >> 16), max(ab.y & 0xffffu, ab.y >> 16)));
+            amax = max(amax, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
+        }
+        const int e = max(1, (int)(wave_max_u32(amax) >> 7));
+        // sum of squares
+        uint64_t s = 0;
+#pragma unroll
+        for (int i = 0; i < NCI; ++i) {
+            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s += sq_term(w[k] & 0xffffu, e) + sq_term(w[k] >> 16, e);
+        }
+        const uint64_t S = wave_sum_u64(s);
+        const double mean = ldexp((double)S, 2 * e - 298) / (double)K;
+        const float r = (float)(1.0 / sqrt(mean + eps));
+
+        uint32_t* dst = reinterpret_cast<uint32_t*>(Xq + (int64_t)m * (K >> 1));
+        uint8_t* sdst = Xs + (int64_t)(m >> 5) * Kg4 * 128 + (m & 31) * 4;
+#pragma unroll
+        for (int i = 0; i < NCI; ++i) {
+            const int c = lane + 64 * i;
+            const u32x4 g = c < nchunk ? gam[c] : (u32x4){0u, 0u, 0u, 0u};
+            uint32_t y[4] = {mul_pair(scale_pair(v[i].x, r), g.x), mul_pair(scale_pair(v[i].y, r), g.y),
+                             mul_pair(scale_pair(v[i].z, r), g.z), mul_pair(scale_pair(v[i].w, r), g.w)};
+            const u32x4 yv = {y[0], y[1], y[2], y[3]};
+            if (Xn && c < nchunk) __builtin_nontemporal_store(yv, reinterpret_cast<u32x4*>(Xn + (int64_t)m * K) + c);
+            if (K_o > 0) {
+                strip[c] = yv;  // back-up (step 2 of Section 3.2)
+                if (c < nchunk) {
+                    const u32x4 kp = *reinterpret_cast<const u32x4*>(keep + 4 * c);
+                    y[0] &= kp.x, y[1] &= kp.y, y[2] &= kp.z, y[3] &= kp.w;  // zero (step 3)
+                }
+            }
+            const uint32_t a0 = y[0] & 0x7fff7fffu, a1 = y[1] & 0x7fff7fffu, a2 = y[2] & 0x7fff7fffu,
+                           a3 = y[3] & 0x7fff7fffu;
+            uint32_t a = max(max(a0 & 0xffffu, a0 >> 16), max(a1 & 0xffffu, a1 >> 16));
+            a = max(a, max(max(a2 & 0xffffu, a2 >> 16), max(a3 & 0xffffu, a3 >> 16)));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true));
+            const uint32_t code = (uint32_t)max((int)(a >> 7) - 2, 0);
+            uint32_t word = code;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;
+            if ((lane & 15) == 0 && c < nchunk) *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+            const float scale = __builtin_bit_cast(float, code << 23);
+            uint32_t out = 0;
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[0]), scale, 0);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[1]), scale, 1);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[2]), scale, 2);
+            out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[3]), scale, 3);
+            if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
+        }
+        if (B) {
+            uint16_t* brow = B + (int64_t)m * ldb;
+            if (K_o > 0) {
+                // the strip was written by this wavefront; LDS runs a wavefront's operations in order
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const uint16_t* raw = reinterpret_cast<const uint16_t*>(strip);
+                for (int o = lane; o < K_o; o += 64) brow[o] = raw[och[o]];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+            for (int o = K_o + lane; o < (int)ldb; o += 64) brow[o] = 0;  // padding columns: +0
+        }
+    }
+}
+
+template <int NCI>
+static int launch_fused_nci(const uint16_t* X, const uint16_t* gamma, double eps, int64_t M, int64_t K, int64_t ldx,
+                            const int32_t* oidx, int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
+                            uint16_t* Xn, hipStream_t st) {
+    const size_t smem = (size_t)4 * NCI * 64 * 16 + (size_t)(K / 2) * 4 + (size_t)K * 2 + (size_t)K_o * 2 + 16;
+    if (smem > 160 * 1024)
+        return fail(OSC_ERR_UNSUPPORTED, "rmsnorm+quantize: K=%lld with K_o=%d needs %zu bytes of LDS", (long long)K,
+                    (int)K_o, smem);
+    auto kern = rmsnorm_quant_mxfp4_kernel<NCI>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return fail(OSC_ERR_HIP, "rmsnorm+quantize: LDS attribute: %s", hipGetErrorString(e));
+    }
+    const int64_t want = (M + 3) / 4;
+    const int grid = (int)(want < 2048 ? want : 2048);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(FT), smem, st, X, gamma, eps, (int)M, (int)K, ldx, oidx, (int)K_o, Xq,
+                       Xs, B, ldb, Xn);
+    return check_launch("rmsnorm_quant_mxfp4_kernel");
+}
+
+int launch_rmsnorm_quant_mxfp4(const uint16_t* X, const uint16_t* gamma, float eps, int64_t M, int64_t K, int64_t ldx,
+                               const int32_t* oidx, int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
+                               uint16_t* Xn, hipStream_t st) {
+    const int64_t nci = (K / 8 + 63) / 64;
+    const double e = (double)eps;
+    if (nci <= 4) return launch_fused_nci<4>(X, gamma, e, M, K, ldx, oidx, K_o, Xq, Xs, B, ldb, Xn, st);
+    if (nci <= 8) return launch_fused_nci<8>(X, gamma, e, M, K, ldx, oidx, K_o, Xq, Xs, B, ldb, Xn, st);
+    if (nci <= 16) return launch_fused_nci<16>(X, gamma, e, M, K, ldx, oidx, K_o, Xq, Xs, B, ldb, Xn, st);
+    if (nci <= 24) return launch_fused_nci<24>(X, gamma, e, M, K, ldx, oidx, K_o, Xq, Xs, B, ldb, Xn, st);
+    return fail(OSC_ERR_UNSUPPORTED, "rmsnorm+quantize: K=%lld exceeds 12288", (long long)K);
+}
+
+}  // namespace osc

@@ -2,6 +2,7 @@
 // threshold, the per-token group-argmax counts and the suppression table built from them.
 // The two kernels that read the activations are HBM-bandwidth-bound, read-only streams.
 #include "osc_internal.h"
+#include "wave_util.h"
 
 namespace osc {
 
@@ -171,39 +172,6 @@ __global__ void __launch_bounds__(PT) profile_hist_kernel(const uint16_t* __rest
 // lane; "largest count, lowest index among equals" is a 64-lane
 // maximum of the key (count << 6) | (63 - index).
 // ------------------------------------------------------------------------------------------
-// 64-lane reductions on the vector ALU alone (DPP inside each row of 16 lanes, then four lane
-// reads).
-__device__ __forceinline__ uint64_t dpp_u64(uint64_t v, const int ctrl_sel) {
-    const int lo = (int)(uint32_t)v, hi = (int)(uint32_t)(v >> 32);
-    int l2, h2;
-    switch (ctrl_sel) {
-        case 0: l2 = __builtin_amdgcn_mov_dpp(lo, 0xB1, 0xF, 0xF, true); h2 = __builtin_amdgcn_mov_dpp(hi, 0xB1, 0xF, 0xF, true); break;    // lane ^ 1
-        case 1: l2 = __builtin_amdgcn_mov_dpp(lo, 0x4E, 0xF, 0xF, true); h2 = __builtin_amdgcn_mov_dpp(hi, 0x4E, 0xF, 0xF, true); break;    // lane ^ 2
-        case 2: l2 = __builtin_amdgcn_mov_dpp(lo, 0x141, 0xF, 0xF, true); h2 = __builtin_amdgcn_mov_dpp(hi, 0x141, 0xF, 0xF, true); break;  // 7 - lane
-        default: l2 = __builtin_amdgcn_mov_dpp(lo, 0x140, 0xF, 0xF, true); h2 = __builtin_amdgcn_mov_dpp(hi, 0x140, 0xF, 0xF, true); break; // 15 - lane
-    }
-    return (uint64_t)(uint32_t)h2 << 32 | (uint32_t)l2;
-}
-__device__ __forceinline__ uint64_t lane_u64(uint64_t v, const int l) {
-    return (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l) << 32 |
-           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
-}
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const uint64_t u = dpp_u64(v, s);
-        v = u > v ? u : v;
-    }
-    const uint64_t a = lane_u64(v, 0), b = lane_u64(v, 16), c = lane_u64(v, 32), d = lane_u64(v, 48);
-    const uint64_t ab = a > b ? a : b, cd = c > d ? c : d;
-    return ab > cd ? ab : cd;
-}
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) v += dpp_u64(v, s);
-    return (lane_u64(v, 0) + lane_u64(v, 16)) + (lane_u64(v, 32) + lane_u64(v, 48));
-}
-
 __global__ void __launch_bounds__(PT) profile_table_kernel(const uint32_t* __restrict__ hist, int Kg, int G,
                                                            int R, int16_t* __restrict__ table,
                                                            uint32_t* __restrict__ n_total,

@@ -101,6 +101,12 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert m8(FAKE, FAKE, FAKE, 4, 64, 96, None, 0, FAKE, 0, 64, None) == -4  # K % 128
     assert m8(FAKE, None, FAKE, 4, 64, 128, None, 0, FAKE, 0, 64, None) == -1
     assert q(FAKE, 4, 48, 48, None, 0, 2, FAKE, FAKE, None, 0, None) == -2  # MXFP8 quantiser, K % 32
+    fq = lib.osc_rmsnorm_quantize_act
+    assert fq(FAKE, None, 1e-6, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -1     # gamma
+    assert fq(FAKE, FAKE, -1.0, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -2     # eps < 0
+    assert fq(FAKE, FAKE, 1e-6, 4, 48, 48, None, 0, FAKE, FAKE, None, 0, None, None) == -2     # K % 32
+    assert fq(FAKE, FAKE + 2, 1e-6, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -4
+    assert fq(None, None, 1e-6, 0, 64, 64, None, 0, None, None, None, 0, None, None) == 0
     dq = lib.osc_quantize_act_dynamic
     assert dq(FAKE, 4, 64, 64, FAKE, FAKE, FAKE, 32, None, None) == -2   # ldb < K
     assert dq(FAKE, 4, 48, 48, FAKE, FAKE, FAKE, 48, None, None) == -2   # K % 32

@@ -258,3 +258,17 @@ def test_profile_config1_shape(osc):
     ref_table = oracle.profile_table(oracle.profile_hist(X, T.item(), 32), 2)[0]
     assert np.array_equal(host(table), ref_table)
     assert np.array_equal(np.sort(host(table), axis=1), np.sort(planted, axis=1))
+
+
+# ---- producer fusion at the headline shape ------------------------------------------------------
+def test_fused_rmsnorm_quant_config1_shape(osc):
+    M, K = 8192, 4096
+    X, table = wl.activations_persistent(6101, M, K, 2, jitter=0.2)
+    gamma = wl.to_bf16_bits((1.0 + 0.2 * wl.rng(6102).standard_normal(K)).astype(np.float32))
+    oidx = oracle.table_to_index(table)
+    Xq, Xs, B, Xn = osc.osc_rmsnorm_quantize_act(dev(X), dev(gamma), 1e-6, dev(oidx.astype(np.int32)), want_norm=True)
+    y = oracle.rmsnorm(X, gamma, 1e-6)
+    rq, rs, rb = oracle.quantize_mxfp4_osc(y, oidx, ldb=B.shape[1])
+    assert np.array_equal(host(Xn), y)
+    assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, M, K)), rs)
+    assert np.array_equal(host(Xq), rq) and np.array_equal(host(B), rb)

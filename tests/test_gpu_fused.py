@@ -1,0 +1,76 @@
+"""GPU parity of the fused RMSNorm + OSC quantiser: the normalised row, the codes, the scales and
+the gathered sub-tensor bit for bit against the oracle's RMSNorm followed by the oracle's quantiser."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from workloads import to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def osc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2604_12782_amd as m
+    m.lib()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check(osc, X, gamma, eps, oidx, ldb=None):
+    M, K = X.shape
+    K_o = len(oidx)
+    if ldb is None:
+        ldb = (K_o + 63) // 64 * 64
+    Xq, Xs, B, Xn = osc.osc_rmsnorm_quantize_act(dev(X), dev(gamma), eps, dev(oidx.astype(np.int32)) if K_o else None,
+                                                 ldb=ldb, want_norm=True)
+    y = oracle.rmsnorm(X, gamma, eps)
+    rq, rs, rb = oracle.quantize_mxfp4_osc(y, oidx, ldb=ldb)
+    assert np.array_equal(Xn.cpu().numpy(), y), "normalised rows differ"
+    assert np.array_equal(osc.osc_unpack_act_scales(Xs, M, K).cpu().numpy(), rs), "scales differ"
+    assert np.array_equal(Xq.cpu().numpy(), rq), "codes differ"
+    if ldb:
+        assert np.array_equal(B.cpu().numpy(), rb), "gathered sub-tensor differs"
+    # and the fused call equals the unfused GPU path on the normalised rows
+    Uq, Us, Ub = osc.osc_quantize_act(Xn, dev(oidx.astype(np.int32)) if K_o else None, ldb=ldb)
+    assert torch.equal(Uq, Xq) and (not ldb or torch.equal(Ub, B))
+    assert torch.equal(osc.osc_unpack_act_scales(Us, M, K), osc.osc_unpack_act_scales(Xs, M, K))
+
+
+@pytest.mark.parametrize("M,K,r", [(1, 32, 1), (5, 96, 0), (33, 1056, 2), (70, 4096, 2), (300, 2048, 1),
+                                   (9, 8192, 1), (6, 12288, 2)])
+def test_fused_matches_oracle(osc, M, K, r):
+    gen = wl.rng(1100 + M)
+    X, table = wl.activations_persistent(1100 + M, M, K, r, jitter=0.3)
+    gamma = to_bf16_bits((1.0 + 0.3 * gen.standard_normal(K)).astype(np.float32))
+    check(osc, X, gamma, 1e-6, oracle.table_to_index(table) if r else np.zeros(0, np.int32))
+
+
+def test_fused_scales_and_edges(osc):
+    gen = wl.rng(1201)
+    K = 256
+    gamma = to_bf16_bits((0.5 + gen.random(K)).astype(np.float32))
+    oidx = np.array([3, 40, 41, 100, 255], np.int32)
+    # rows of very different magnitude, a zero row, a row with one non-zero, wide range inside a row
+    x = gen.standard_normal((8, K)).astype(np.float32)
+    x[0] *= 1e-20
+    x[1] *= 1e20
+    x[2] = 0.0
+    x[3] = 0.0
+    x[3, 40] = -7.0
+    x[4, 0], x[4, 1] = 2.0 ** 90, 2.0 ** -90
+    x[5] = 3.0
+    X = to_bf16_bits(x)
+    X[6, ::3] = 0x8000
+    for eps in (1e-6, 1e-12, 1.0):
+        check(osc, X, gamma, eps, oidx)
+        check(osc, X, gamma, eps, oidx, ldb=8)
+    # eps = 0 on rows without an all-zero row
+    check(osc, X[[0, 1, 3, 4, 5, 7]], gamma, 0.0, oidx)

@@ -219,9 +219,9 @@ int osc_grouped_dual_gemm(const uint8_t *Xq, const uint8_t *Xs, const void *B, i
  * Section 2.1, are RMSNorm outputs).  The normalisation is defined so that its result does not
  * depend on any order of summation:
  *   e    = the largest biased bf16 exponent field of the row (at least 1);
- *   S    = sum over the row of floor(m^2 * 2^30 / 4^(e - E)), |x| = m * 2^(E - 134), m an 8-bit
- *          integer, E >= 1 (64-bit integer; terms 2^46 below the largest vanish);
- *   r    = (float)(1 / sqrt((double)S * 2^(2e - 298) / K + eps)), double arithmetic;
+ *   S    = sum over the row of floor(m^2 * 2^28 / 4^(e - E)), |x| = m * 2^(E - 134), m an 8-bit
+ *          integer, E >= 1 (64-bit integer; terms 2^44 below the largest vanish);
+ *   r    = (float)(1 / sqrt((double)S * 2^(2e - 296) / K + eps)), double arithmetic;
  *   y    = bf16(bf16(x * r) * gamma), single-precision products, round to nearest even.
  *   gamma  bf16 [K] (device), 16-byte aligned;  eps >= 0
  *   Xn     bf16 [M, K] (device) or NULL: receives y when given

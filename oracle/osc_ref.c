@@ -257,9 +257,9 @@ int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
  * correctly rounded IEEE operation, none of which depends on an order of summation:
  *   1. e = the largest biased exponent field of the row (a subnormal counts as 1);
  *   2. every |x| = m * 2^(E - 134) with an 8-bit integer m (hidden bit included) and E >= 1; its
- *      square enters a 64-bit fixed-point sum in units of 2^(2e - 298):
- *      S = sum of floor(m^2 * 2^30 / 2^(2(e - E)))   (terms more than 2^46 below the largest vanish);
- *   3. mean = (double)S * 2^(2e - 298) / K, r = (float)(1 / sqrt(mean + eps)) in double arithmetic;
+ *      square enters a 64-bit fixed-point sum in units of 2^(2e - 296):
+ *      S = sum of floor(m^2 * 2^28 / 2^(2(e - E)))   (terms more than 2^44 below the largest vanish);
+ *   3. mean = (double)S * 2^(2e - 296) / K, r = (float)(1 / sqrt(mean + eps)) in double arithmetic;
  *   4. t = bf16(x * r) with one single-precision multiplication, y = bf16(t * gamma) (that product
  *      is exact in single precision); bf16() rounds to nearest, ties to even.
  * X, Y: bf16 bits [M, K] (row strides ldx, K); gamma: bf16 bits [K]. */
@@ -289,9 +289,9 @@ int ref_rmsnorm(const uint16_t *X, const uint16_t *gamma, double eps, int64_t M,
             uint64_t mant = x[j] & 0x7F;
             if (E == 0) E = 1; else mant |= 0x80;
             int sh = 2 * (e - E);
-            if (sh < 64) S += ((mant * mant) << 30) >> sh;
+            if (sh < 64) S += ((mant * mant) << 28) >> sh;
         }
-        double mean = ldexp((double)S, 2 * e - 298) / (double)K;
+        double mean = ldexp((double)S, 2 * e - 296) / (double)K;
         float r = (float)(1.0 / sqrt(mean + eps));
         for (int64_t j = 0; j < K; ++j) {
             if ((gamma[j] & 0x7F80) == 0x7F80) bad = 1;

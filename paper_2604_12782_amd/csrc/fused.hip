@@ -25,20 +25,21 @@ __device__ __forceinline__ uint32_t mul_pair(uint32_t t, uint32_t g) {
                    __builtin_bit_cast(float, th) * __builtin_bit_cast(float, gh)};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, v2bf));
 }
-// one element's term of the fixed-point sum of squares (units of 2^(2e - 298))
-__device__ __forceinline__ uint64_t sq_term(uint32_t h, int e) {
-    int E = (h >> 7) & 0xff;
-    uint32_t m = h & 0x7fu;
-    if (E == 0) E = 1;
-    else m |= 0x80u;
-    const int sh = 2 * (e - E);
-    return sh < 64 ? ((uint64_t)(m * m) << 30) >> sh : 0ull;
+// one element's term of the fixed-point sum of squares, floor(m^2 * 2^28 / 4^(e - E)) in units of
+// 2^(2e - 296), on the floating-point pipe: |x| * 2^(148 - e) = m * 2^(E - e + 14) is below 2^22, its
+// square (16 significant bits, below 2^44) is exact in single precision, and so is the floor.
+// The power of two is applied in two exact steps (pre * unit) so that neither factor leaves the
+// single-precision range for any e; an element so small that a step underflows has a term of 0.
+__device__ __forceinline__ float sq_term(uint32_t hbits16, float pre, float unit) {
+    const uint32_t b = hbits16 << 16;
+    const float xs = (__builtin_bit_cast(float, b) * pre) * unit;
+    return __builtin_floorf(xs * xs);
 }
 
 // A wavefront owns a whole row: lane l holds the 16-byte chunks l, l + 64, ... (NCI of them), so
 // the two row-wide reductions (largest exponent, sum of squares) are register work plus DPP.
 // The sum of squares is an integer in fixed point relative to the row's largest exponent: exact
-// up to a truncation 2^-46 below the largest term and independent of any order, so the
+// up to a truncation 2^-42 below the largest term and independent of any order, so the
 // normalised row, and every code derived from it, is reproducible bit for bit.
 // LDS: per-wave strip of the normalised row (for the gather) | keep masks | gamma | channel list.
 template <int NCI>
@@ -83,16 +84,23 @@ __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
             amax = max(amax, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
         }
         const int e = max(1, (int)(wave_max_u32(amax) >> 7));
-        // sum of squares
-        uint64_t s = 0;
+        // sum of squares: every term is an integer below 2^44, a lane adds at most 192 of them, so its
+        // double holds the exact sum; the 64 lane sums are added as integers
+        const int ebig = e >= 64 ? 0 : 64;
+        const float pre = __builtin_bit_cast(float, (uint32_t)(127 + ebig) << 23);            // 1 or 2^64
+        const float unit = __builtin_bit_cast(float, (uint32_t)(275 - e - ebig) << 23);       // 2^(148 - e) / pre
+        double s = 0.0;
 #pragma unroll
         for (int i = 0; i < NCI; ++i) {
             const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) s += sq_term(w[k] & 0xffffu, e) + sq_term(w[k] >> 16, e);
+            for (int k = 0; k < 4; ++k) {
+                s += (double)sq_term(w[k] & 0xffffu, pre, unit);
+                s += (double)sq_term(w[k] >> 16, pre, unit);
+            }
         }
-        const uint64_t S = wave_sum_u64(s);
-        const double mean = ldexp((double)S, 2 * e - 298) / (double)K;
+        const uint64_t S = wave_sum_u64((uint64_t)s);
+        const double mean = ldexp((double)S, 2 * e - 296) / (double)K;
         const float r = (float)(1.0 / sqrt(mean + eps));
 
         uint32_t* dst = reinterpret_cast<uint32_t*>(Xq + (int64_t)m * (K >> 1));

@@ -248,6 +248,19 @@ int osc_rmsnorm_quantize_act(const void *X, const void *gamma, float eps, int64_
 int osc_quantize_act_dynamic(const void *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
                              void *Xs, void *Bd, int64_t ldb, uint8_t *idx, void *stream);
 
+/* ---- measurement aid ------------------------------------------------------------ */
+
+/*
+ * Matrix-core probe (no passage of the paper: a yardstick for the measurements).  Runs
+ * `workgroups` workgroups of eight wavefronts, each issuing `iters` x 8 FP4 block-scaled MFMAs
+ * (the instruction of the dual-path GEMM) on pseudo-random register operands with nothing else in
+ * the loop, and reports through *flops (host) how many floating-point operations that is.  Timed by
+ * the caller, it gives the matrix rate this machine sustains at its real clocks, to be set beside
+ * the published peak.
+ *   out  float (device), 4-byte aligned: never written in practice (keeps the result alive)
+ */
+int osc_probe_mfma_fp4(int32_t workgroups, int32_t iters, float *out, double *flops, void *stream);
+
 /* ---- offline profiling (calibration) ------------------------------------------ */
 
 /*

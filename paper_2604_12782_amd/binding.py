@@ -38,6 +38,7 @@ _SIGS = {
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
     "osc_rmsnorm_quantize_act": (C.c_int, [vp, vp, C.c_float, i64, i64, i64, vp, i32, vp, vp, vp, i64, vp, vp]),
     "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
+    "osc_probe_mfma_fp4": (C.c_int, [i32, i32, vp, vp, vp]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
     "osc_profile_hist": (C.c_int, [vp, i64, i64, i64, i32, vp, vp, vp]),
@@ -343,3 +344,12 @@ def osc_rmsnorm_quantize_act(X, gamma, eps=1e-6, oidx=None, ldb=None, want_norm=
     _check(lib().osc_rmsnorm_quantize_act(_ptr(X), _ptr(gamma), eps, M, K, X.stride(0), _ptr(oidx), K_o, _ptr(Xq),
                                           _ptr(Xs), _ptr(B), ldb, _ptr(Xn), _stream()))
     return Xq, Xs, B, Xn
+
+
+def osc_probe_mfma_fp4(workgroups, iters, out=None):
+    """Enqueues the matrix-core probe; returns the number of floating-point operations it performs."""
+    if out is None:
+        out = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = C.c_double(0.0)
+    _check(lib().osc_probe_mfma_fp4(workgroups, iters, _ptr(out), C.addressof(flops), _stream()))
+    return flops.value

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libosc.so")
-SOURCES = ["api.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip"]
+SOURCES = ["api.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -101,6 +101,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert m8(FAKE, FAKE, FAKE, 4, 64, 96, None, 0, FAKE, 0, 64, None) == -4  # K % 128
     assert m8(FAKE, None, FAKE, 4, 64, 128, None, 0, FAKE, 0, 64, None) == -1
     assert q(FAKE, 4, 48, 48, None, 0, 2, FAKE, FAKE, None, 0, None) == -2  # MXFP8 quantiser, K % 32
+    pr = lib.osc_probe_mfma_fp4
+    fl = C.c_double(0.0)
+    assert pr(0, 4, FAKE, C.addressof(fl), None) == -2 and pr(4, 4, None, C.addressof(fl), None) == -1
     fq = lib.osc_rmsnorm_quantize_act
     assert fq(FAKE, None, 1e-6, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -1     # gamma
     assert fq(FAKE, FAKE, -1.0, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -2     # eps < 0

@@ -36,7 +36,7 @@ DOMINANT_TRAFFIC_BYTES = {8192: 245.6e6}
 PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
 
 
-def cpu_baseline(rows=512):
+def cpu_baseline(rows=1280):
     """The oracle, as it stands, on a bounded sample of the same workload: `rows` tokens through
     the quantiser and the q projection.  Reported baseline only."""
     import oracle

@@ -154,6 +154,16 @@ def rmsnorm(X, gamma, eps=1e-6):
     return Y
 
 
+def swiglu(G, U):
+    """bf16(bf16(silu(G)) * U) with the fixed single-precision silu of ref_swiglu; uint16[M, K] each."""
+    G, U = _c(G, np.uint16), _c(U, np.uint16)
+    M, K = G.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().ref_swiglu.argtypes = [C.c_void_p, C.c_void_p, i64, i64, i64, i64, C.c_void_p]
+    _check(lib().ref_swiglu(_p(G), _p(U), M, K, K, K, _p(Y)), "ref_swiglu")
+    return Y
+
+
 def gather_wl(W, oidx):
     """W uint16[N, K] -> W_L uint16[K_o, N] (rows of the unquantised weight)."""
     W = _c(W, np.uint16)

@@ -24,6 +24,10 @@
  *                           Figure 1), in a form whose result does not depend on
  *                           the order of any summation, so that a producer fused
  *                           with the quantiser can be compared bit for bit
+ *   ref_swiglu              the gated activation that produces the W_2 inputs (position 4 of
+ *                           Section 2.1), y = silu(gate) * up, as a fixed sequence of
+ *                           correctly rounded single-precision operations, so that a producer
+ *                           fused with the 8-bit quantiser can be compared bit for bit
  *   ref_gather_wl           W_L: rows of the high-precision weight named by
  *                           the same table (Section 3.3.1, second bullet)
  *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
@@ -299,6 +303,47 @@ int ref_rmsnorm(const uint16_t *X, const uint16_t *gamma, double eps, int64_t M,
             Y[m * K + j] = float_to_bf16_rne(t * bf16_to_float(gamma[j]));
         }
     }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* SwiGLU, y = bf16(bf16(silu(g)) * u) with silu(g) = g / (1 + exp(-g)), every step one IEEE single
+ * precision operation (fmaf is the fused multiply-add, one rounding):
+ *   z = min(max(-g, -86), 86)                      (keeps 2^n normal; beyond it silu is g or ~0 anyway)
+ *   n = rint(z * log2(e));  r = fma(n, -LN2_HI, z);  r = fma(n, -LN2_LO, r)
+ *   p = 1 + r(1 + r(1/2 + r(1/6 + r(1/24 + r(1/120 + r/720)))))   (Horner, one fma per step)
+ *   e = p * 2^n (exact);  s = g / (1 + e)           (one addition, one division)
+ * G, U: bf16 bits [M, K] with row strides ldg, ldu; Y: bf16 bits [M, K]. */
+static float silu_f32(float g) {
+    const float LOG2E = 0x1.715476p+0f, LN2_HI = 0x1.62e400p-1f, LN2_LO = 0x1.7f7d1cp-20f;
+    float z = -g;
+    if (z < -86.0f) z = -86.0f;
+    if (z > 86.0f) z = 86.0f;
+    float n = rintf(z * LOG2E);
+    float r = fmaf(n, -LN2_HI, z);
+    r = fmaf(n, -LN2_LO, r);
+    float p = 1.0f / 720.0f;
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    float e = ldexpf(p, (int)n);
+    return g / (1.0f + e);
+}
+
+int ref_swiglu(const uint16_t *Gt, const uint16_t *U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+               uint16_t *Y) {
+    if (M < 0 || K < 0 || ldg < K || ldu < K || (M && K && (!Gt || !U || !Y))) return REF_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < K; ++j) {
+            uint16_t g = Gt[m * ldg + j], u = U[m * ldu + j];
+            if ((g & 0x7F80) == 0x7F80 || (u & 0x7F80) == 0x7F80) bad = 1;
+            float t = bf16_to_float(float_to_bf16_rne(silu_f32(bf16_to_float(g))));
+            Y[m * K + j] = float_to_bf16_rne(t * bf16_to_float(u));
+        }
     return bad ? REF_ERR_NONFINITE : REF_OK;
 }
 

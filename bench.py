@@ -305,6 +305,12 @@ def main():
     ms_m8g = time_one(lambda: osc.osc_mxfp8_gemm(*m8, wm8, 4096, K_FF, y_dtype=ydt, out=Y["o"]), reps=10)
     ms_t8q = time_one(lambda: osc.osc_quantize_act(dXf, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=t8), reps=10)
     ms_t8g = time_one(lambda: osc.osc_fp8_gemm(*t8, wf8, 4096, K_FF, y_dtype=ydt, out=Y["o"]), reps=10)
+    # the same position with its producer fused: SwiGLU on the two halves of a gate||up buffer, then MXFP8
+    gseed = torch.Generator(device=dev)
+    gseed.manual_seed(3005)
+    gu = (torch.randn((M, 2 * K_FF), generator=gseed, device=dev) * 2).to(torch.bfloat16).view(torch.uint16)
+    ms_swq = time_one(lambda: osc.osc_swiglu_quantize_act(gu[:, :K_FF], gu[:, K_FF:], out=(m8[0], m8[1], None)), reps=10)
+    del gu
     del dXf, wm8, wf8, m8, t8
     per = {}
     for n, N in PROJ:
@@ -380,6 +386,13 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(quant_bytes / (ms_fused * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": round(quant_bytes / (ms_fused * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         "unfused_quant_ms": round(ms_quant, 4),
+    }
+    sw_bytes = M * K_FF * (4 + 1 + 1 / 32)
+    out["fused_swiglu_quant_mxfp8"] = {
+        "shape": f"M={M} K={K_FF}", "ms": round(ms_swq, 4),
+        "roofline": {"bound": "hbm", "achieved": round(sw_bytes / (ms_swq * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(sw_bytes / (ms_swq * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        "unfused_quant_only_ms": round(ms_m8q, 4),
     }
     out["table2_sweep"] = t2
     out["dynamic_control"] = {

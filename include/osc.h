@@ -232,6 +232,24 @@ int osc_rmsnorm_quantize_act(const void *X, const void *gamma, float eps, int64_
                              void *B, int64_t ldb, void *Xn, void *stream);
 
 /*
+ * SwiGLU fused with the MXFP8 quantiser of the W_2 fallback (the W_2 inputs, position 4 of
+ * Section 2.1, are silu(gate) * up; Section 4.1 quantises them to MXFP8): what
+ * osc_quantize_act(fmt = OSC_FMT_MXFP8) returns for y = bf16(bf16(silu(g)) * u), without y
+ * passing through memory.  silu(g) = g / (1 + exp(-g)) is computed as a fixed sequence of
+ * correctly rounded single-precision operations: z = clamp(-g, -86, 86); n = rint(z * log2 e);
+ * r = fma(n, -LN2_HI, z), r = fma(n, -LN2_LO, r) with LN2_HI = 0x1.62e4p-1, LN2_LO =
+ * 0x1.7f7d1cp-20; p = Horner of 1 + r + r^2/2 + ... + r^6/720, one fma per step from the
+ * highest term; e = p * 2^n; silu = g / (1 + e).
+ *   G, U  bf16 [M, ldg], [M, ldu] (device), 16-byte aligned rows: gate and up projections (two
+ *         halves of one fused GEMM output are fine: pass the pointers and the common stride)
+ *   Xq    uint8 [M, K] E4M3 codes; Xs E8M0 scales as for OSC_FMT_MXFP8
+ *   Yn    bf16 [M, K] (device) or NULL: receives y when given
+ * Errors as osc_quantize_act.
+ */
+int osc_swiglu_quantize_act(const void *G, const void *U, int64_t M, int64_t K, int64_t ldg,
+                            int64_t ldu, uint8_t *Xq, void *Xs, void *Yn, void *stream);
+
+/*
  * "Dynamic" protection, the control experiment of Section 4.2 (Table 3, note 3: per-group
  * maximum value detection at run time).  Like osc_quantize_act(fmt = OSC_FMT_MXFP4_OSC) with
  * one slot per group, except that the protected position is chosen per token: the largest

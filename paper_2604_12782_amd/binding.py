@@ -37,6 +37,7 @@ _SIGS = {
     "osc_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, i64, i64, i64, i32, vp, C.c_int, i64, vp]),
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
     "osc_rmsnorm_quantize_act": (C.c_int, [vp, vp, C.c_float, i64, i64, i64, vp, i32, vp, vp, vp, i64, vp, vp]),
+    "osc_swiglu_quantize_act": (C.c_int, [vp, vp, i64, i64, i64, i64, vp, vp, vp, vp]),
     "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
     "osc_probe_mfma_fp4": (C.c_int, [i32, i32, vp, vp, vp]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
@@ -353,3 +354,20 @@ def osc_probe_mfma_fp4(workgroups, iters, out=None):
     flops = C.c_double(0.0)
     _check(lib().osc_probe_mfma_fp4(workgroups, iters, _ptr(out), C.addressof(flops), _stream()))
     return flops.value
+
+
+def osc_swiglu_quantize_act(G, U, want_y=False, out=None):
+    """SwiGLU + MXFP8 quantiser in one pass -> (Xq uint8 [M, K], Xs, Yn uint16 [M, K] or None)."""
+    G, U = _rows16(G), _rows16(U)
+    M, K = G.shape
+    assert U.shape == G.shape
+    dev = G.device
+    if out is not None:
+        Xq, Xs, Yn = out
+    else:
+        Xq = torch.empty((M, K), dtype=torch.uint8, device=dev)
+        Xs = torch.empty(osc_act_scale_bytes(M, K), dtype=torch.uint8, device=dev)
+        Yn = torch.empty((M, K), dtype=torch.uint16, device=dev) if want_y else None
+    _check(lib().osc_swiglu_quantize_act(_ptr(G), _ptr(U), M, K, G.stride(0), U.stride(0), _ptr(Xq), _ptr(Xs),
+                                         _ptr(Yn), _stream()))
+    return Xq, Xs, Yn

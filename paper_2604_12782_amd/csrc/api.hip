@@ -292,6 +292,20 @@ int osc_rmsnorm_quantize_act(const void* X, const void* gamma, float eps, int64_
                                       B ? ldb : 0, static_cast<uint16_t*>(Xn), as_stream(stream));
 }
 
+int osc_swiglu_quantize_act(const void* G, const void* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                            uint8_t* Xq, void* Xs, void* Yn, void* stream) {
+    int rc = check_mx_shape("osc_swiglu_quantize_act", M, K, ldg, 0);
+    if (rc) return rc;
+    REQUIRE(ldu >= K, OSC_ERR_SHAPE, "osc_swiglu_quantize_act: ldu=%lld < K=%lld", (long long)ldu, (long long)K);
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(G && U && Xq && Xs, OSC_ERR_NULL, "osc_swiglu_quantize_act: null pointer");
+    REQUIRE(ldg % 8 == 0 && ldu % 8 == 0 && aligned(G, 16) && aligned(U, 16) && aligned(Xq, 8) && aligned(Xs, 4) &&
+                aligned(Yn, 16),
+            OSC_ERR_UNSUPPORTED, "osc_swiglu_quantize_act: misaligned pointer or leading dimension");
+    return launch_swiglu_quant_mxfp8(static_cast<const uint16_t*>(G), static_cast<const uint16_t*>(U), M, K, ldg, ldu,
+                                     Xq, static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(Yn), as_stream(stream));
+}
+
 int osc_quantize_act_dynamic(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, void* Xs, void* Bd,
                              int64_t ldb, uint8_t* idx, void* stream) {
     int rc = check_mx_shape("osc_quantize_act_dynamic", M, K, ldx, 0);

@@ -190,4 +190,110 @@ int launch_rmsnorm_quant_mxfp4(const uint16_t* X, const uint16_t* gamma, float e
     return fail(OSC_ERR_UNSUPPORTED, "rmsnorm+quantize: K=%lld exceeds 12288", (long long)K);
 }
 
+// ------------------------------------------------------------------------------------------
+// SwiGLU fused with the MXFP8 quantiser of the W_2 fallback (position 4 of Section 2.1; Section
+// 3.4; Section 4.1: MXFP8 for the W_2 inputs): y = bf16(bf16(silu(g)) * u) goes straight from
+// registers into E4M3 codes and E8M0 scales.  silu is a fixed sequence of correctly rounded single
+// precision operations (range reduction by ln 2, degree-6 Horner polynomial, one division), so the
+// codes are reproducible bit for bit.  Streaming kernel, same work split as the quantisers.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float silu_f32(float g) {
+    const float LOG2E = 0x1.715476p+0f, LN2_HI = 0x1.62e400p-1f, LN2_LO = 0x1.7f7d1cp-20f;
+    const float z = fminf(fmaxf(-g, -86.0f), 86.0f);
+    const float n = __builtin_rintf(__fmul_rn(z, LOG2E));
+    float r = __fmaf_rn(n, -LN2_HI, z);
+    r = __fmaf_rn(n, -LN2_LO, r);
+    float p = 1.0f / 720.0f;
+    p = __fmaf_rn(p, r, 1.0f / 120.0f);
+    p = __fmaf_rn(p, r, 1.0f / 24.0f);
+    p = __fmaf_rn(p, r, 1.0f / 6.0f);
+    p = __fmaf_rn(p, r, 0.5f);
+    p = __fmaf_rn(p, r, 1.0f);
+    p = __fmaf_rn(p, r, 1.0f);
+    const float e = __builtin_ldexpf(p, (int)n);
+    return __fdiv_rn(g, __fadd_rn(1.0f, e));
+}
+// bf16(bf16(silu(g)) * u) for the two halves of a packed word
+__device__ __forceinline__ uint32_t swiglu_pair(uint32_t g, uint32_t u) {
+    const uint32_t gl = g << 16, gh = g & 0xffff0000u;
+    const v2f s = {silu_f32(__builtin_bit_cast(float, gl)), silu_f32(__builtin_bit_cast(float, gh))};
+    const uint32_t t = __builtin_bit_cast(uint32_t, __builtin_convertvector(s, v2bf));
+    return mul_pair(t, u);
+}
+
+__global__ void __launch_bounds__(FT) swiglu_quant_mxfp8_kernel(const uint16_t* __restrict__ G,
+                                                                const uint16_t* __restrict__ U, int M, int K,
+                                                                int64_t ldg, int64_t ldu, uint8_t* __restrict__ Xq,
+                                                                uint8_t* __restrict__ Xs, uint16_t* __restrict__ Yn,
+                                                                int nseg, int total_wg) {
+    const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
+    const int nchunk = K >> 3;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
+        const QItem it = quant_item(wg, wave, nseg, M);
+        if (it.m < 0) continue;  // uniform over the wavefront
+        const int m = it.m;
+        const u32x4* gsrc = reinterpret_cast<const u32x4*>(G + (int64_t)m * ldg);
+        const u32x4* usrc = reinterpret_cast<const u32x4*>(U + (int64_t)m * ldu);
+        const int c0 = it.seg * SEG_CHUNKS + lane;
+        u32x4 gv[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}, uv[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (c0 + 64 * i < nchunk) {
+                gv[i] = __builtin_nontemporal_load(gsrc + c0 + 64 * i);
+                uv[i] = __builtin_nontemporal_load(usrc + c0 + 64 * i);
+            }
+        typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+        u32x2* dst = reinterpret_cast<u32x2*>(Xq + (int64_t)m * K);
+        uint8_t* sdst = Xs + (int64_t)(m >> 5) * Kg4 * 128 + (m & 31) * 4;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = c0 + 64 * i;
+            const uint32_t ww[4] = {swiglu_pair(gv[i].x, uv[i].x), swiglu_pair(gv[i].y, uv[i].y),
+                                    swiglu_pair(gv[i].z, uv[i].z), swiglu_pair(gv[i].w, uv[i].w)};
+            if (Yn && c < nchunk)
+                __builtin_nontemporal_store((u32x4){ww[0], ww[1], ww[2], ww[3]},
+                                            reinterpret_cast<u32x4*>(Yn + (int64_t)m * K) + c);
+            uint32_t a = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) a = max(a, max(ww[k] & 0x7fffu, (ww[k] >> 16) & 0x7fffu));
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true));  // lane ^ 1
+            a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true));  // lane ^ 2
+            const uint32_t code = (uint32_t)max((int)(a >> 7) - 8, 0);  // E8M0 code = max(E - 8, 0)
+            uint32_t word = code;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;
+            word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;
+            if ((lane & 15) == 0 && c < nchunk) *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+            const float inv = __builtin_bit_cast(float, (254u - code) << 23);  // 2^-(code - 127)
+            float p[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t lo = ww[k] << 16, hi = ww[k] & 0xffff0000u;
+                p[2 * k] = fminf(fmaxf(__fmul_rn(__builtin_bit_cast(float, lo), inv), -448.0f), 448.0f);
+                p[2 * k + 1] = fminf(fmaxf(__fmul_rn(__builtin_bit_cast(float, hi), inv), -448.0f), 448.0f);
+            }
+            int r0 = 0, r1 = 0;
+            r0 = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], r0, false);
+            r0 = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], r0, true);
+            r1 = __builtin_amdgcn_cvt_pk_fp8_f32(p[4], p[5], r1, false);
+            r1 = __builtin_amdgcn_cvt_pk_fp8_f32(p[6], p[7], r1, true);
+            if (c < nchunk) __builtin_nontemporal_store((u32x2){(uint32_t)r0, (uint32_t)r1}, dst + c);
+        }
+    }
+}
+
+int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                              uint8_t* Xq, uint8_t* Xs, uint16_t* Yn, hipStream_t st) {
+    const int64_t nchunk = K / 8;
+    const int nseg = (int)((nchunk + SEG_CHUNKS - 1) / SEG_CHUNKS);
+    const int64_t blocks = (M + 31) / 32;
+    const int64_t total_wg = (blocks + 7) / 8 * 8 * (8 * nseg);
+    if (total_wg > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "swiglu+quantize: M=%lld too large", (long long)M);
+    const int grid = (int)(total_wg < 8192 ? total_wg : 8192);
+    hipLaunchKernelGGL(swiglu_quant_mxfp8_kernel, dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, Xq,
+                       Xs, Yn, nseg, (int)total_wg);
+    return check_launch("swiglu_quant_mxfp8_kernel");
+}
+
 }  // namespace osc

@@ -1,6 +1,7 @@
 // Activation quantisers: OSC-enhanced MXFP4 (Section 3.2, Alg. 2) and per-token FP8 (Section 3.4).
 // Both are HBM-bandwidth-bound row kernels: one workgroup walks whole rows with 16-byte loads.
 #include "osc_internal.h"
+#include "wave_util.h"
 
 namespace osc {
 
@@ -30,27 +31,6 @@ constexpr int QT = 256;  // threads per workgroup
 // rows at a time: the 4-byte scale words of those rows share 128-byte lines and meet in that
 // XCD's L2 before they are written back.
 // ------------------------------------------------------------------------------------------
-constexpr int SEG_CHUNKS = 128;             // chunks per segment (two per lane)
-constexpr int SEG_CH = SEG_CHUNKS * 8;      // channels per segment
-
-
-struct QItem {
-    int m, seg;
-};
-// linear work item (four per workgroup trip) -> (row, segment).  A block of 32 rows is
-// 32*nseg items; XCD x = workgroup % 8 owns blocks x, x+8, ...
-__device__ __forceinline__ QItem quant_item(int wg, int wave, int nseg, int M) {
-    const int per_block = 8 * nseg;          // workgroups per 32-row block
-    const int x = wg & 7, s = wg >> 3;
-    const int block = x + 8 * (s / per_block);
-    const int it = (s % per_block) * 4 + wave;  // item within the block, row-major (row, segment)
-    QItem q;
-    q.m = block * 32 + it / nseg;
-    q.seg = it % nseg;
-    if (q.m >= M) q.m = -1;
-    return q;
-}
-
 __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
     const uint16_t* __restrict__ X, int M, int K, int64_t ldx, const int32_t* __restrict__ oidx,
     int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, uint16_t* __restrict__ B,

@@ -1,4 +1,4 @@
-// 64-lane reductions for wavefront-per-item kernels (device code only).
+// 64-lane reductions and the row/segment work split shared by the streaming kernels (device code only).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -48,5 +48,28 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
     return max(max(a, b), max(c, d));
 }
+
+// ---- work split of the row-streaming kernels: (row, 1024-channel segment) items --------------
+constexpr int SEG_CHUNKS = 128;             // chunks per segment (two per lane)
+constexpr int SEG_CH = SEG_CHUNKS * 8;      // channels per segment
+
+
+struct QItem {
+    int m, seg;
+};
+// linear work item (four per workgroup trip) -> (row, segment).  A block of 32 rows is
+// 32*nseg items; XCD x = workgroup % 8 owns blocks x, x+8, ...
+__device__ __forceinline__ QItem quant_item(int wg, int wave, int nseg, int M) {
+    const int per_block = 8 * nseg;          // workgroups per 32-row block
+    const int x = wg & 7, s = wg >> 3;
+    const int block = x + 8 * (s / per_block);
+    const int it = (s % per_block) * 4 + wave;  // item within the block, row-major (row, segment)
+    QItem q;
+    q.m = block * 32 + it / nseg;
+    q.seg = it % nseg;
+    if (q.m >= M) q.m = -1;
+    return q;
+}
+
 
 }  // namespace osc

@@ -110,6 +110,11 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert fq(FAKE, FAKE, 1e-6, 4, 48, 48, None, 0, FAKE, FAKE, None, 0, None, None) == -2     # K % 32
     assert fq(FAKE, FAKE + 2, 1e-6, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -4
     assert fq(None, None, 1e-6, 0, 64, 64, None, 0, None, None, None, 0, None, None) == 0
+    sw = lib.osc_swiglu_quantize_act
+    assert sw(FAKE, None, 4, 64, 64, 64, FAKE, FAKE, None, None) == -1
+    assert sw(FAKE, FAKE, 4, 64, 64, 32, FAKE, FAKE, None, None) == -2   # ldu < K
+    assert sw(FAKE, FAKE, 4, 64, 68, 64, FAKE, FAKE, None, None) == -4   # ldg % 8
+    assert sw(None, None, 0, 64, 64, 64, None, None, None, None) == 0
     dq = lib.osc_quantize_act_dynamic
     assert dq(FAKE, 4, 64, 64, FAKE, FAKE, FAKE, 32, None, None) == -2   # ldb < K
     assert dq(FAKE, 4, 48, 48, FAKE, FAKE, FAKE, 48, None, None) == -2   # K % 32

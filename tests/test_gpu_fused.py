@@ -74,3 +74,45 @@ def test_fused_scales_and_edges(osc):
         check(osc, X, gamma, eps, oidx, ldb=8)
     # eps = 0 on rows without an all-zero row
     check(osc, X[[0, 1, 3, 4, 5, 7]], gamma, 0.0, oidx)
+
+
+# ---- SwiGLU + MXFP8 quantiser ---------------------------------------------------------------
+def check_swiglu(osc, G, U, strided=False):
+    M, K = G.shape
+    if strided:  # the two halves of one fused gate||up buffer
+        both = torch.from_numpy(np.concatenate([G, U], axis=1)).cuda()
+        dG, dU = both[:, :K], both[:, K:]
+    else:
+        dG, dU = dev(G), dev(U)
+    Xq, Xs, Yn = osc.osc_swiglu_quantize_act(dG, dU, want_y=True)
+    y = oracle.swiglu(G, U)
+    rq, rs = oracle.quantize_mxfp8(y)
+    assert np.array_equal(Yn.cpu().numpy(), y), "activation values differ"
+    assert np.array_equal(osc.osc_unpack_act_scales(Xs, M, K).cpu().numpy(), rs), "scales differ"
+    assert np.array_equal(Xq.cpu().numpy(), rq), "codes differ"
+    # and equal to the unfused GPU quantiser on the same values
+    Uq, Us = osc.osc_quantize_act(Yn, None, osc.OSC_FMT_MXFP8)
+    assert torch.equal(Uq, Xq)
+    assert torch.equal(osc.osc_unpack_act_scales(Us, M, K), osc.osc_unpack_act_scales(Xs, M, K))
+
+
+@pytest.mark.parametrize("M,K", [(1, 32), (7, 96), (40, 1056), (130, 4096), (9, 12288)])
+def test_swiglu_fused_matches_oracle(osc, M, K):
+    gen = wl.rng(1300 + M)
+    G = to_bf16_bits((gen.standard_normal((M, K)) * 3).astype(np.float32))
+    U = wl.activations_diffuse(1400 + M, M, K, p=0.01)
+    check_swiglu(osc, G, U)
+    check_swiglu(osc, G, U, strided=True)
+
+
+def test_swiglu_every_gate_value(osc):
+    """every bf16 bit pattern below 2^100 in magnitude as a gate (58 000 of them; above that the
+    product with up leaves the bf16 range), against the oracle, bit for bit"""
+    bits = np.arange(0x10000, dtype=np.uint32).astype(np.uint16)
+    bits = bits[((bits >> 7) & 0xFF) < 227]
+    K = 2048
+    pad = (-len(bits)) % K
+    G = np.concatenate([bits, np.zeros(pad, np.uint16)]).reshape(-1, K)
+    gen = wl.rng(1501)
+    U = to_bf16_bits((0.5 + gen.random(G.shape)).astype(np.float32))
+    check_swiglu(osc, G, U)

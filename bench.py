@@ -12,7 +12,6 @@ Prints one JSON line.  `value` = sum over the four GEMMs of 2*M*N*K, divided by 
 whole step (quantisers included).
 """
 import argparse
-import subprocess
 import zlib
 import json
 import os
@@ -195,15 +194,18 @@ def main():
     ms_probe = time_one(lambda: osc.osc_probe_mfma_fp4(2048, 256, probe_out), reps=5)
 
     def read_sclk():
-        try:
-            txt = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks"], capture_output=True, text=True,
-                                 timeout=20).stdout
-            for line in txt.splitlines():
-                if "sclk" in line and "(" in line:
-                    return int(line.split("(")[1].split("Mhz")[0])
-        except Exception:
-            pass
-        return None
+        # current shader clock from the driver's sysfs table (the line marked with '*'); no child process
+        import glob
+        best = None
+        for path in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+            try:
+                for line in open(path):
+                    if "*" in line:
+                        mhz = int(line.split(":")[1].strip().lower().split("mhz")[0])
+                        best = mhz if best is None else max(best, mhz)
+            except (OSError, ValueError, IndexError):
+                pass
+        return best
 
     for _ in range(6000):  # ~0.6 s of queued GEMMs; the clock is read while they run
         osc.osc_dual_gemm(*q1, packs["q"], 4096, K_HID, K_o, ydt, out=Y["q"])

@@ -1,0 +1,94 @@
+"""Every GEMM kernel template on shapes it would not be chosen for: the launcher's tuning variable
+forces the tile size and the kernel, the results must still meet the GEMM tolerance.  Also outputs
+written into wider buffers (ldy > N) and through the unaligned bf16 store path."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def osc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2604_12782_amd as m
+    m.lib()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def close(Y, ref, what, bf16=False):
+    Y = Y.float().cpu().numpy().astype(np.float64)
+    slack = TOL * np.abs(ref).max() + (2.0 ** -8 * np.abs(ref) if bf16 else 0.0)
+    assert np.isfinite(Y).all() and (np.abs(Y - ref) <= slack).all(), what
+
+
+# tile rows / 64, kernel id: 0 staged, 1 DMA (eight wavefronts at 256 rows), 2 persistent, 3 skinny
+FORCED = ["4,1", "2,1", "1,0", "2,0", "4,2", "2,2"]
+
+
+@pytest.mark.parametrize("cfg", FORCED)
+@pytest.mark.parametrize("M,N,K,r", [(300, 200, 1024, 2), (513, 520, 512, 1), (256, 512, 768, 0), (70, 1000, 256, 4)])
+def test_dual_forced(osc, monkeypatch, cfg, M, N, K, r):
+    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+    X, table = wl.activations_persistent(7000 + M, M, K, r)
+    W = wl.weights(7100 + N, N, K)
+    oidx = oracle.table_to_index(table) if r else np.zeros(0, np.int32)
+    d_oidx = dev(oidx) if r else None
+    Xq, Xs, B = osc.osc_quantize_act(dev(X), d_oidx)
+    Wp = osc.osc_pack_weight(dev(W), d_oidx)
+    rq, rs, rb = oracle.quantize_mxfp4_osc(X, oidx, ldb=B.shape[1] if B is not None else 0)
+    wq, ws, _ = oracle.quantize_mxfp4_osc(W)
+    ref = oracle.dual_gemm(rq, rs, rb if r else None, wq, ws, oracle.gather_wl(W, oidx))
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Y = osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), ydt)
+        close(Y, ref, f"{cfg} {M}x{N}x{K} r={r} bf16={bf}", bf)
+
+
+@pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,0", "2,0"])
+def test_fp8_and_mxfp8_forced(osc, monkeypatch, cfg):
+    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+    M, N, K = 300, 264, 768
+    X = wl.activations_diffuse(7200, M, K)
+    W = wl.weights(7201, N, K)
+    X8, xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    r8, rs = oracle.quantize_fp8_rows(X)
+    w8, ws = oracle.quantize_fp8_rows(W)
+    close(osc.osc_fp8_gemm(X8, xs, osc.osc_pack_weight_fp8(dev(W)), N, K), oracle.fp8_gemm(r8, rs, w8, ws), "fp8 " + cfg)
+    if cfg.endswith(",1"):  # the MXFP8 GEMM exists in the DMA (and skinny) kernels only
+        Xm, Xms = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+        q, s = oracle.quantize_mxfp8(X)
+        wq, wsc = oracle.quantize_mxfp8(W)
+        Y = osc.osc_mxfp8_gemm(Xm, Xms, osc.osc_pack_weight_mxfp8(dev(W)), N, K)
+        close(Y, oracle.mxfp8_gemm(q, s, wq, wsc), "mxfp8 " + cfg)
+
+
+@pytest.mark.parametrize("cfg", [None, "4,1", "1,0"])
+def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
+    if cfg:
+        monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+    M, N, K = 200, 320, 512
+    X, table = wl.activations_persistent(7300, M, K, 2)
+    W = wl.weights(7301, N, K)
+    oidx = oracle.table_to_index(table)
+    Xq, Xs, B = osc.osc_quantize_act(dev(X), dev(oidx))
+    Wp = osc.osc_pack_weight(dev(W), dev(oidx))
+    rq, rs, rb = oracle.quantize_mxfp4_osc(X, oidx, ldb=B.shape[1])
+    wq, ws, _ = oracle.quantize_mxfp4_osc(W)
+    ref = oracle.dual_gemm(rq, rs, rb, wq, ws, oracle.gather_wl(W, oidx))
+    for dt, ydt, bf in ((torch.float32, osc.OSC_DT_F32, False), (torch.bfloat16, osc.OSC_DT_BF16, True)):
+        for width, col0 in ((N + 64, 0), (N + 7, 3)):  # aligned wide buffer; odd stride and odd first column
+            wide = torch.full((M, width), 7.0, dtype=dt, device="cuda")
+            view = wide[:, col0:col0 + N]
+            osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), ydt, out=view)
+            close(view, ref, f"ldy={width} col0={col0} bf16={bf}", bf)
+            rest = torch.cat([wide[:, :col0], wide[:, col0 + N:]], dim=1)
+            assert (rest == 7.0).all(), "wrote outside the output view"

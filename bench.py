@@ -54,6 +54,79 @@ def cpu_baseline(rows=1280):
                       f"(N=4096, K=4096, K_o=256) in {dt:.2f} s"}, float(np.abs(Y).max())
 
 
+def sweep(osc, wl, torch):
+    """GEMM times for the other shapes of the configs (dual path against FP8 W8A8), HIP events around
+    20 launches back to back, bf16 output, random N(0,1) activations.  Decode-sized shapes are bound by
+    the launch from Python here; section 'table2_sweep' of the benchmark line times them inside a graph."""
+    def timeit(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(9001)
+
+    def dual(tag, M, N, K, r):
+        X = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
+        W = (torch.randn((N, K), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        oidx = torch.from_numpy(osc.osc_table_to_index(wl.planted_table(wl.rng(3), K, r))).cuda() if r else None
+        K_o = 0 if oidx is None else int(oidx.numel())
+        q, Wp = osc.osc_quantize_act(X, oidx), osc.osc_pack_weight(W, oidx)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ms = timeit(lambda: osc.osc_dual_gemm(*q, Wp, N, K, K_o, osc.OSC_DT_BF16, out=Y))
+        q8 = osc.osc_quantize_act(X, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+        W8 = osc.osc_pack_weight_fp8(W)
+        ms8 = timeit(lambda: osc.osc_fp8_gemm(*q8, W8, N, K, y_dtype=osc.OSC_DT_BF16, out=Y))
+        tf = 2.0 * M * N * K / ms / 1e9
+        print(f"{tag:6s} M={M:5d} N={N:5d} K={K:5d} r={r}: dual {ms * 1e3:7.1f} us {tf:6.0f} TFLOP/s "
+              f"({100 * tf / PEAK_MXFP4_TFLOPS:4.1f} % of MXFP4 peak) | fp8 {ms8 * 1e3:7.1f} us | speed-up {ms8 / ms:.2f}", flush=True)
+
+    for M in (128, 2048, 8192):
+        for N in (4096, 1024):
+            dual("cfg2", M, N, 4096, 2)
+    dual("cfg3", 8192, 24576, 4096, 2)
+    for r in (0, 1, 2, 4):
+        for M in (64, 512, 4096):
+            dual("cfg5", M, 12288, 4096, r)
+    # cfg4: MoE, 128 experts, top-8 routing of 4096 tokens
+    tokens, K, E, topk, N = 4096, 2048, 128, 8, 1536
+    X = torch.randn((tokens, K), generator=gen, device="cuda").to(torch.bfloat16)
+    oidx = torch.from_numpy(osc.osc_table_to_index(wl.planted_table(wl.rng(3), K, 2))).cuda()
+    K_o = int(oidx.numel())
+    q = osc.osc_quantize_act(X, oidx)
+    off, row_map = wl.moe_routing(4002, tokens, E, topk)
+    T = int(off[-1])
+    stride = osc.osc_packed_weight_bytes(N, K, K_o)
+    Wp = torch.empty(E * stride, dtype=torch.uint8, device="cuda")
+    for e in range(E):
+        W = (torch.randn((N, K), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        osc.osc_pack_weight(W, oidx, out=Wp[e * stride:(e + 1) * stride])
+    d_off, d_map = torch.from_numpy(off).cuda(), torch.from_numpy(row_map).cuda()
+    Y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    ms = timeit(lambda: osc.osc_grouped_dual_gemm(*q, d_map, d_off, T, Wp, N, K, K_o, osc.OSC_DT_BF16, out=Y))
+    print(f"cfg4   grouped dual T={T} N={N} K={K} E={E}: {ms * 1e3:.1f} us, "
+          f"{2.0 * T * N * K / ms / 1e9:.0f} TFLOP/s, weights {E * stride / 1e6:.0f} MB", flush=True)
+    K2, N2 = 768, 2048
+    X2 = torch.randn((T, K2), generator=gen, device="cuda").to(torch.bfloat16)
+    q8 = osc.osc_quantize_act(X2, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    s8 = osc.osc_packed_weight_fp8_bytes(N2, K2)
+    Wp8 = torch.empty(E * s8, dtype=torch.uint8, device="cuda")
+    for e in range(E):
+        W = (torch.randn((N2, K2), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+        osc.osc_pack_weight_fp8(W, out=Wp8[e * s8:(e + 1) * s8])
+    Y2 = torch.empty((T, N2), dtype=torch.bfloat16, device="cuda")
+    ms = timeit(lambda: osc.osc_fp8_gemm(*q8, Wp8, N2, K2, expert_offsets=d_off, y_dtype=osc.OSC_DT_BF16, out=Y2))
+    print(f"cfg4   grouped fp8  T={T} N={N2} K={K2} E={E}: {ms * 1e3:.1f} us, "
+          f"{2.0 * T * N2 * K2 / ms / 1e9:.0f} TFLOP/s", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +135,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: time the other BASELINE shapes (table on stdout)")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a counter yardstick for profiler runs)")
     args = ap.parse_args()
@@ -73,6 +148,8 @@ def main():
     import workloads as wl
     osc.lib()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.sweep:
+        return sweep(osc, wl, torch)
     M = args.tokens
     dev = torch.device("cuda:0")
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)

@@ -1309,12 +1309,12 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
 // and for FP4 exactly the four groups of scale word 2*line + q.
 // MT = number of 32-row tiles of X per workgroup (blockIdx.y selects the group of MT tiles).
 // ------------------------------------------------------------------------------------------
-template <int MODE, int MT>
-__global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
+template <int MODE, int MT, int NW>
+__global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
     constexpr int ROWS = 32 + 32 * MT;      // rows of a line image: 32 weight rows, then the X rows
     constexpr int IMG = ROWS * 128;          // bytes of a line image
     constexpr int NDMA = ROWS / 8;           // DMA instructions per line (8 rows each)
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];  // [4 waves][2 images], later the partial sums
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];  // [NW waves][2 images], later the partial sums
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int q = lane >> 5, r = lane & 31;
     const int n0 = blockIdx.x * 32;
@@ -1431,14 +1431,14 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
             acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 4, 4, I_, sx__[m], I_, sb__); \
         }                                                                                               \
     }
-    // lines wave, wave+4, ...; the next line is in flight while one is consumed.  Everything a wave
+    // lines wave, wave+NW, ...; the next line is in flight while one is consumed.  Everything a wave
     // reads from LDS it wrote itself, so "my loads have landed" is all the synchronisation needed.
     int L = wave, img = 0;
     SKINNY_FETCH(L, 0)
 #pragma unroll 1
-    for (; L < nLT; L += 4) {
-        SKINNY_FETCH(L + 4, img ^ 1)
-        if (L + 4 < nLT) wait_vmcnt<NDMA>(); else wait_vmcnt<0>();
+    for (; L < nLT; L += NW) {
+        SKINNY_FETCH(L + NW, img ^ 1)
+        if (L + NW < nLT) wait_vmcnt<NDMA>(); else wait_vmcnt<0>();
         SKINNY_COMPUTE(L, img)
         img ^= 1;
     }
@@ -1447,9 +1447,9 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
 #undef SKINNY_COMPUTE
 #undef SKINNY_FETCH
 
-    // ---- sum the four partial results in a fixed order, store -----------------------------------
+    // ---- sum the NW partial results in a fixed order, store -------------------------------------
     __syncthreads();  // every wave is done with its strip
-    float* const red = reinterpret_cast<float*>(lds);  // [4 waves][MT][16][64]
+    float* const red = reinterpret_cast<float*>(lds);  // [NW waves][MT][16][64]
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
@@ -1457,14 +1457,15 @@ __global__ void __launch_bounds__(GT) gemm_skinny_kernel(KArgs a) {
     __syncthreads();
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
+        // result register k of lane (q, r): row 8*(k/4) + 4q + k%4, column r; wave w finishes k = w, w+NW, ...
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k = 4 * wave + i;  // result register k of lane (q, r): row 8*(k/4) + 4q + k%4, column r
+        for (int k0 = 0; k0 < 16; k0 += NW) {
+            const int k = k0 + wave;
+            if (k >= 16) break;
             float v = red[((0 * MT + m) * 16 + k) * 64 + lane];
-            v += red[((1 * MT + m) * 16 + k) * 64 + lane];
-            v += red[((2 * MT + m) * 16 + k) * 64 + lane];
-            v += red[((3 * MT + m) * 16 + k) * 64 + lane];
-            const int row = mb + 32 * m + 8 * wave + 4 * q + i, col = n0 + r;
+#pragma unroll
+            for (int w = 1; w < NW; ++w) v += red[((w * MT + m) * 16 + k) * 64 + lane];
+            const int row = mb + 32 * m + 8 * (k >> 2) + 4 * q + (k & 3), col = n0 + r;
             if (MODE == MODE_FP8)  // per-token and per-channel scales
                 v *= a.xs[min(row, a.M - 1)] * reinterpret_cast<const float*>(a.Wpack + a.off_s)[min(col, a.N - 1)];
             if (row < a.M && col < a.N) {
@@ -1481,11 +1482,27 @@ template <int MODE>
 static int launch_skinny(KArgs a, hipStream_t st) {
     const int64_t grid = (a.N + 31) / 32;
     if (grid <= 0) return OSC_OK;
-    // LDS: four strips of two line images (64 KB, two workgroups per CU); the partial sums reuse
-    // the space.  33..64 rows: two workgroups per 32 output channels, one per 32-row tile of X (the
-    // second pass over a weight row is an L2 hit; one workgroup with both tiles would need 96 KB).
+    // LDS: one strip of two line images per wavefront; the partial sums reuse the space.  33..64 rows:
+    // two workgroups per 32 output channels, one per 32-row tile of X (the second pass over a weight
+    // row is an L2 hit; one workgroup with both tiles needs 50 % more LDS and measured slower).
     const unsigned mtiles = a.M <= 32 ? 1u : 2u;
-    hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1>), dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
+        ncu = n;
+    }
+    // Four wavefronts need 64 KB of LDS: two workgroups per CU.  When the grid is larger than that
+    // (12288 output channels x two row tiles = 768 workgroups on 256 CUs) the tail round runs half
+    // empty; three wavefronts (48 KB, three workgroups per CU) keep everything resident: 9.5 us
+    // instead of 11.8 at 64x12288x4096.
+    if (grid * mtiles > 2 * (int64_t)ncu) {
+        hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 3>), dim3((unsigned)grid, mtiles), dim3(192), 3 * 2 * 64 * 128, st, a);
+        return check_launch("gemm_skinny_kernel");
+    }
+    hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 4>), dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
     return check_launch("gemm_skinny_kernel");
 }
 

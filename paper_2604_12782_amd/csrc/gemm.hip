@@ -1485,7 +1485,7 @@ static int launch_skinny(KArgs a, hipStream_t st) {
     // LDS: one strip of two line images per wavefront; the partial sums reuse the space.  33..64 rows:
     // two workgroups per 32 output channels, one per 32-row tile of X (the second pass over a weight
     // row is an L2 hit; one workgroup with both tiles needs 50 % more LDS and measured slower).
-    const unsigned mtiles = a.M <= 32 ? 1u : 2u;
+    const unsigned mtiles = (unsigned)((a.M + 31) / 32);
     static int ncu = 0;
     if (ncu == 0) {
         int dev = 0, n = 0;
@@ -1629,8 +1629,12 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
     if (kind == 1 && pipe_ok && tm == 4) kind = 2;
-    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && p.M <= 64;
-    if (skinny_ok) kind = 3;  // decode-sized problems: the weight-streaming kernel
+    // The weight-streaming kernel (one workgroup per 32 output channels and 32 rows) also wins for a few
+    // hundred rows as long as its grid stays small: a tiled launch of so few tiles leaves most CUs
+    // idle (128 x 4096 x 4096: 17 us on 32 tiles of 128 x 128, 6.4 us on 512 streaming workgroups).
+    const int64_t skinny_wgs = ((p.N + 31) / 32) * ((p.M + 31) / 32);
+    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 1536);
+    if (skinny_ok) kind = 3;
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
         if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {

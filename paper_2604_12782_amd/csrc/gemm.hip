@@ -647,8 +647,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
     constexpr int STG = (BM + BN) * 128;
     constexpr int LA = BM / RPP, LB = BN / RPP;  // DMA loads per thread and stage
     constexpr int NBLK = (BM + BN) / 32;      // 32-row blocks of a stage
-    constexpr int NSB = NBLK / NWV;            // scale DMA loads per wave and stage (one block each)
-    static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
+    constexpr int NSB = (NBLK + NWV - 1) / NWV;  // scale DMA loads per wave and stage (one block each)
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile does not split over the wavefronts");
     constexpr int SCL = NBLK * 256;            // bytes of scale words per stage: [block][half step][32 rows][4]
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* const scl = lds + 2 * STG;        // scale words of the two stages
@@ -688,7 +688,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
     if (MODE == MODE_DUAL || MODE == MODE_MX8) {
 #pragma unroll
         for (int k = 0; k < NSB; ++k) {
-            const int b = wave * NSB + k;
+            const int b = min(wave * NSB + k, NBLK - 1);
             int g;
             if (b < BM / 32) {
                 g = min(m0 + 32 * b + r, row_end - 1);
@@ -748,6 +748,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
         const uint32_t o__ = (MODE == MODE_DUAL ? (uint32_t)min(2 * (T_), Kg4 - 2) : (uint32_t)min((T_), Kg4 - 1)) * 128u; \
         _Pragma("unroll") for (int k = 0; k < NSB; ++k) {                                             \
             const int b__ = wave * NSB + k;                                                           \
+            if (NBLK % NWV != 0 && b__ >= NBLK) continue;                                             \
             const uint8_t* src__ = (b__ < BM / 32 ? a.Xs : wsb) + (o__ + sco[k]);                     \
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src__,    \
                                              (__attribute__((address_space(3))) void*)(scl + (BUF_)*SCL + b__ * 256), \
@@ -1618,12 +1619,13 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     const bool lines = rowbytes > 0 && rowbytes % 128 == 0 &&
                        (MODE != MODE_DUAL || p.K_o == 0 || a.bpitch % 128 == 0);
     const bool ragged = rowbytes % 64 != 0 || (MODE == MODE_DUAL && p.K_o > 0 && a.bpitch % 64 != 0);
-    int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : 2;
-    if (MODE == MODE_MX8) {  // implemented in the DMA and skinny kernels only
-        if (!lines) return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
-        if (tm == 1) tm = 2;
-    }
-    int kind = (lines && tm > 1) ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
+    // 256-row tiles when they fill the chip, else 128x128, else (fewer than one tile per CU) 64x128
+    const int64_t t128 = ((rows + 127) / 128) * ((p.N + 127) / 128) * (grouped ? p.E : 1);
+    const int64_t t128_full = MODE == MODE_DUAL ? 512 : 257;  // measured crossover: two (8-bit: one) 128x128 tiles per CU
+    int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : (t128 < t128_full ? 1 : 2);
+    if (MODE == MODE_MX8 && !lines)  // implemented in the DMA and skinny kernels only
+        return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
+    int kind = lines ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
@@ -1632,15 +1634,17 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     // The weight-streaming kernel (one workgroup per 32 output channels and 32 rows) also wins for a few
     // hundred rows as long as its grid stays small: a tiled launch of so few tiles leaves most CUs
     // idle (128 x 4096 x 4096: 17 us on 32 tiles of 128 x 128, 6.4 us on 512 streaming workgroups).
+    // Above about a thousand workgroups the 64 x 128 tiles of the DMA kernel are as fast or faster.
     const int64_t skinny_wgs = ((p.N + 31) / 32) * ((p.M + 31) / 32);
-    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 1536);
+    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 1024);
     if (skinny_ok) kind = 3;
     if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
         int k2 = kind;
         if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
             if (tm != 1 && tm != 2 && tm != 4) tm = 2;
             if (k2 < 0 || k2 > 3) k2 = kind;
-            if ((k2 == 1 || k2 == 2) && !(lines && tm > 1)) k2 = 0;
+            if ((k2 == 1 || k2 == 2) && !lines) k2 = 0;
+            if (k2 == 2 && tm == 1) k2 = 1;
             if (k2 == 2 && !pipe_ok) k2 = 1;
             if (k2 == 3 && !skinny_ok) k2 = 0;
         }
@@ -1681,6 +1685,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         // 256-row tiles run on eight wavefronts (2 x 4, 128x64 each): 6-8 % faster than four, the second
         // wavefront of a SIMD fills the issue gaps of the first
         if (tm == 4) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
+        if (tm == 1) return launch_dma2<MODE, 1, 2>(a, p.M, grouped, st);
         return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
     }
     if constexpr (MODE == MODE_MX8) {

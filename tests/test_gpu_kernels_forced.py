@@ -32,7 +32,7 @@ def close(Y, ref, what, bf16=False):
 
 
 # tile rows / 64, kernel id: 0 staged, 1 DMA (eight wavefronts at 256 rows), 2 persistent, 3 skinny
-FORCED = ["4,1", "2,1", "1,0", "2,0", "4,2", "2,2"]
+FORCED = ["4,1", "2,1", "1,1", "1,0", "2,0", "4,2", "2,2"]
 
 
 @pytest.mark.parametrize("cfg", FORCED)
@@ -53,7 +53,7 @@ def test_dual_forced(osc, monkeypatch, cfg, M, N, K, r):
         close(Y, ref, f"{cfg} {M}x{N}x{K} r={r} bf16={bf}", bf)
 
 
-@pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,0", "2,0"])
+@pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1", "1,0", "2,0"])
 def test_fp8_and_mxfp8_forced(osc, monkeypatch, cfg):
     monkeypatch.setenv("OSC_GEMM_TILE", cfg)
     M, N, K = 300, 264, 768
@@ -71,7 +71,7 @@ def test_fp8_and_mxfp8_forced(osc, monkeypatch, cfg):
         close(Y, oracle.mxfp8_gemm(q, s, wq, wsc), "mxfp8 " + cfg)
 
 
-@pytest.mark.parametrize("cfg", [None, "4,1", "1,0"])
+@pytest.mark.parametrize("cfg", [None, "4,1", "1,1", "1,0"])
 def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
     if cfg:
         monkeypatch.setenv("OSC_GEMM_TILE", cfg)

@@ -1668,7 +1668,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         return launch_pipe2<2, 2>(a, m_full, grouped, st);
     }
 
-    if (kind >= 1 && grouped && tm == 4 && MODE != MODE_MX8) {
+    if (kind >= 1 && grouped && tm == 4) {
         // experts in 256-row tiles, and what is left of an expert whose last tile would be less than
         // half full in 64-row tiles (an expert of 270 rows: one big tile and one small one, not two
         // big ones)
@@ -1677,9 +1677,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if (rc != OSC_OK) return rc;
         a.grp_mode = 2;
         a.grp_bm = 256;
-        if constexpr (MODE != MODE_MX8)
-            return ragged ? launch_cfg<MODE, 1, 2, true>(a, p.M, grouped, st)
-                          : launch_cfg<MODE, 1, 2, false>(a, p.M, grouped, st);
+        return launch_dma2<MODE, 1, 2>(a, p.M, grouped, st);
     }
     if (kind >= 1) {
         // 256-row tiles run on eight wavefronts (2 x 4, 128x64 each): 6-8 % faster than four, the second

@@ -220,6 +220,26 @@ def test_config4_moe_grouped(osc):
         ref = oracle.fp8_gemm(r8[ts], r8s[ts], *w8ref[e])
         check_close(Y8h[ts], ref, f"cfg4 fp8 expert {e}", bf16_out=True)
 
+    # the same W2 inputs in MXFP8 (Section 4.1), grouped
+    Xm, Xms = osc.osc_quantize_act(dev(X2), None, osc.OSC_FMT_MXFP8)
+    mq, ms_ = oracle.quantize_mxfp8(X2)
+    assert np.array_equal(host(Xm), mq)
+    stridem = osc.osc_packed_weight_mxfp8_bytes(N2, K2)
+    Wpm = torch.empty(E * stridem, dtype=torch.uint8, device="cuda")
+    wmref = {}
+    for e in range(E):
+        W = wl.weights(4300 + e, N2, K2)
+        osc.osc_pack_weight_mxfp8(dev(W), out=Wpm[e * stridem:(e + 1) * stridem])
+        if e in checked:
+            wmref[e] = oracle.quantize_mxfp8(W)
+    Ym = osc.osc_mxfp8_gemm(Xm, Xms, Wpm, N2, K2, expert_offsets=dev(off), y_dtype=osc.OSC_DT_BF16)
+    Ymh = host(Ym.float())
+    for e in checked:
+        lo, hi = int(off[e]), int(off[e + 1])
+        ts = np.unique(np.concatenate([[lo, hi - 1], wl.rng(200 + e).integers(lo, hi, size=22)]))
+        ref = oracle.mxfp8_gemm(mq[ts], ms_[ts], *wmref[e])
+        check_close(Ymh[ts], ref, f"cfg4 mxfp8 expert {e}", bf16_out=True)
+
 
 # ---- configs[4]: Table-2 style sweep -------------------------------------------------------------
 

@@ -99,22 +99,24 @@ def e4m3_encode(v):
 # ---- table -----------------------------------------------------------------
 
 
-def table_to_index(table):
-    """table[Kg, R] int16 (local index or -1) -> ascending channel ids int32[K_o]."""
+def table_to_index(table, G=32):
+    """table[Kg, R] int16 (local index in a group of G channels, or -1) -> ascending channel
+    ids int32[K_o]."""
     table = _c(table, np.int16)
     Kg, R = table.shape
-    oidx = np.zeros(max(Kg * min(R, 32), 1), np.int32)
+    oidx = np.zeros(max(Kg * min(R, G), 1), np.int32)
     ko = i32(0)
-    _check(lib().ref_table_to_index(_p(table), i32(Kg), i32(R), _p(oidx), C.byref(ko)),
-           "ref_table_to_index")
+    _check(lib().ref_table_to_index_g(_p(table), i32(Kg), i32(R), i32(G), _p(oidx), C.byref(ko)),
+           "ref_table_to_index_g")
     return oidx[:ko.value].copy()
 
 
 # ---- quantisers --------------------------------------------------------------
 
 
-def quantize_mxfp4_osc(X, oidx=None, ldb=None):
-    """Alg. 2.  X uint16[M, K] -> (Xq uint8[M, K/2], Xs uint8[M, K/32], B uint16[M, ldb])."""
+def quantize_mxfp4_osc(X, oidx=None, ldb=None, G=32):
+    """Alg. 2.  X uint16[M, K] -> (Xq uint8[M, K/2], Xs uint8[M, K/32], B uint16[M, ldb]).
+    G = 64: one shared exponent per 64 channels, stored in both of its blocks of 32."""
     X = _c(X, np.uint16)
     M, K = X.shape
     oidx = np.zeros(0, np.int32) if oidx is None else _c(oidx, np.int32)
@@ -124,8 +126,8 @@ def quantize_mxfp4_osc(X, oidx=None, ldb=None):
     Xq = np.empty((M, K // 2), np.uint8)
     Xs = np.empty((M, K // 32), np.uint8)
     B = np.empty((M, ldb), np.uint16)
-    _check(lib().ref_quantize_mxfp4_osc(_p(X), i64(M), i64(K), i64(K), _p(oidx), i32(K_o), _p(Xq),
-                                        _p(Xs), _p(B), i64(ldb)), "ref_quantize_mxfp4_osc")
+    _check(lib().ref_quantize_mxfp4_osc_g(_p(X), i64(M), i64(K), i64(K), _p(oidx), i32(K_o), i32(G),
+                                          _p(Xq), _p(Xs), _p(B), i64(ldb)), "ref_quantize_mxfp4_osc_g")
     return Xq, Xs, B
 
 

@@ -181,26 +181,31 @@ int ref_e4m3_encode(float vf) {
 
 /* ---- table ------------------------------------------------------------- */
 
-/* Paper-form table: Kg groups x R slots, each a local index in [0, 32) or -1
- * (no suppression).  Output: the flat list of protected global channel ids in
- * ascending order, and its length K_o. */
-int ref_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oidx, int32_t *K_o) {
-    if (!table || !oidx || !K_o || Kg < 0 || R < 0) return REF_ERR_ARG;
+/* Paper-form table: Kg groups of Gs channels x R slots, each a local index in
+ * [0, Gs) or -1 (no suppression); the paper's group sizes are 16, 32 and 64
+ * (Section 3.1, "Quantifying Clustering Density").  Output: the flat list of
+ * protected global channel ids in ascending order, and its length K_o. */
+int ref_table_to_index_g(const int16_t *table, int32_t Kg, int32_t R, int32_t Gs, int32_t *oidx,
+                         int32_t *K_o) {
+    if (!table || !oidx || !K_o || Kg < 0 || R < 0 || Gs < 1 || Gs > 64) return REF_ERR_ARG;
     int32_t n = 0;
     for (int32_t g = 0; g < Kg; ++g) {
-        uint32_t seen = 0;
+        uint64_t seen = 0;
         for (int32_t s = 0; s < R; ++s) {
             int j = table[(int64_t)g * R + s];
             if (j == -1) continue;
-            if (j < 0 || j >= G) return REF_ERR_TABLE;
-            if (seen & (1u << j)) return REF_ERR_TABLE;
-            seen |= 1u << j;
+            if (j < 0 || j >= Gs) return REF_ERR_TABLE;
+            if (seen & ((uint64_t)1 << j)) return REF_ERR_TABLE;
+            seen |= (uint64_t)1 << j;
         }
-        for (int j = 0; j < G; ++j)
-            if (seen & (1u << j)) oidx[n++] = g * G + j;
+        for (int j = 0; j < Gs; ++j)
+            if (seen & ((uint64_t)1 << j)) oidx[n++] = g * Gs + j;
     }
     *K_o = n;
     return REF_OK;
+}
+int ref_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oidx, int32_t *K_o) {
+    return ref_table_to_index_g(table, Kg, R, G, oidx, K_o);
 }
 
 /* ---- OSC-enhanced MXFP4 quantiser (Alg. 2) ------------------------------ */
@@ -208,11 +213,15 @@ int ref_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oid
 /* X[M, K] bf16 bits, row stride ldx.  oidx[K_o]: protected channel ids.
  * Outputs: Xq[M, K/2] (element 2i in bits 3:0, 2i+1 in bits 7:4),
  * Xs[M, K/32] E8M0 codes, B[M, ldb] bf16 bits with column o = the original
- * value of channel oidx[o] and columns K_o..ldb-1 = +0. */
-int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
-                           const int32_t *oidx, int32_t K_o, uint8_t *Xq, uint8_t *Xs,
-                           uint16_t *B, int64_t ldb) {
-    if (M < 0 || K < 0 || K % G || ldx < K || K_o < 0 || ldb < K_o) return REF_ERR_ARG;
+ * value of channel oidx[o] and columns K_o..ldb-1 = +0.
+ * Gs is the size of a scale group: 32 (the MXFP4 block) or 64 (Table 2's
+ * G = 64 row: one shared exponent for 64 channels, held in the two stored
+ * blocks of 32 that the group covers, so the GEMM below needs no change). */
+int ref_quantize_mxfp4_osc_g(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                             const int32_t *oidx, int32_t K_o, int32_t Gs, uint8_t *Xq, uint8_t *Xs,
+                             uint16_t *B, int64_t ldb) {
+    if (Gs != 32 && Gs != 64) return REF_ERR_ARG;
+    if (M < 0 || K < 0 || K % Gs || ldx < K || K_o < 0 || ldb < K_o) return REF_ERR_ARG;
     if (M == 0 || K == 0) return REF_OK;
     if (!X || !Xq || !Xs || (K_o && (!oidx || !B))) return REF_ERR_ARG;
     for (int32_t o = 0; o < K_o; ++o)
@@ -234,27 +243,33 @@ int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
             removed[oidx[o]] = 1;
         }
         /* step 4: scale and quantise the modified tensor, group by group */
-        for (int64_t g = 0; g < Kg; ++g) {
-            double v[G];
-            int neg[G];
+        for (int64_t g = 0; g < K / Gs; ++g) {
+            double v[64];
+            int neg[64];
             double amax = 0.0;
-            for (int j = 0; j < G; ++j) {
-                uint16_t h = removed[g * G + j] ? (uint16_t)0 : x[g * G + j];
+            for (int j = 0; j < Gs; ++j) {
+                uint16_t h = removed[g * Gs + j] ? (uint16_t)0 : x[g * Gs + j];
                 if ((h & 0x7F80) == 0x7F80) bad = 1;
                 v[j] = (double)bf16_to_float(h);
                 neg[j] = (h >> 15) & 1;
                 if (fabs(v[j]) > amax) amax = fabs(v[j]);
             }
             int e = mx_shared_exponent(amax);
-            Xs[m * Kg + g] = (uint8_t)(e + 127);
-            for (int j = 0; j < G; j += 2) {
+            /* one code per stored block of 32: a group of 64 writes the same code twice */
+            for (int b = 0; b < Gs / G; ++b) Xs[m * Kg + g * (Gs / G) + b] = (uint8_t)(e + 127);
+            for (int j = 0; j < Gs; j += 2) {
                 int lo = ref_e2m1_encode(ldexp(v[j], -e), neg[j]);
                 int hi = ref_e2m1_encode(ldexp(v[j + 1], -e), neg[j + 1]);
-                Xq[m * (K / 2) + (g * G + j) / 2] = (uint8_t)(lo | (hi << 4));
+                Xq[m * (K / 2) + (g * Gs + j) / 2] = (uint8_t)(lo | (hi << 4));
             }
         }
     }
     return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+int ref_quantize_mxfp4_osc(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                           const int32_t *oidx, int32_t K_o, uint8_t *Xq, uint8_t *Xs,
+                           uint16_t *B, int64_t ldb) {
+    return ref_quantize_mxfp4_osc_g(X, M, K, ldx, oidx, K_o, G, Xq, Xs, B, ldb);
 }
 
 /* RMSNorm, y = x / sqrt(mean(x^2) + eps) * gamma, defined so that every step is exact or a single

@@ -31,22 +31,22 @@ def rng(seed):
     return np.random.Generator(np.random.PCG64(seed))
 
 
-def planted_table(gen, K, r):
-    """[K/32, max(r,1)] int16 table: r distinct local indices per group (ascending), else -1."""
-    Kg = K // G
+def planted_table(gen, K, r, group=G):
+    """[K/group, max(r,1)] int16 table: r distinct local indices per group (ascending), else -1."""
+    Kg = K // group
     table = np.full((Kg, max(r, 1)), -1, np.int16)
     for g in range(Kg):
         if r:
-            table[g, :r] = np.sort(gen.choice(G, size=r, replace=False))
+            table[g, :r] = np.sort(gen.choice(group, size=r, replace=False))
     return table
 
 
-def table_channels(table):
+def table_channels(table, group=G):
     """Global channel ids named by a table, ascending (pure index bookkeeping)."""
     out = []
     for g in range(table.shape[0]):
         for j in sorted(int(v) for v in table[g] if v >= 0):
-            out.append(g * G + j)
+            out.append(g * group + j)
     return np.asarray(out, np.int32)
 
 

@@ -327,22 +327,19 @@ def main():
     ms_f8_big = time_one(lambda: osc.osc_fp8_gemm(*f1, packs8["q"], 4096, K_HID, y_dtype=ydt, out=Y["q"]))
     ms_f8_64 = graph_time(lambda: osc.osc_fp8_gemm(*f64, wu8, N_UP, K_HID, y_dtype=ydt, out=Y64))
     for G in (16, 32, 64):
-        tab = np.full((K_HID // 32, 2), -1, np.int16)
-        gen = wl.rng(7000 + G)
-        if G == 16:
-            tab[:, 0] = gen.integers(0, 16, K_HID // 32)
-            tab[:, 1] = 16 + gen.integers(0, 16, K_HID // 32)
-        elif G == 32:
-            tab[:, 0] = gen.integers(0, 32, K_HID // 32)
-        else:
-            tab[::2, 0] = gen.integers(0, 32, K_HID // 64)
-        oi = up(osc.osc_table_to_index(tab))
+        # G = 32 and 64: protection group = scale group (64: one shared exponent per 64 channels, held
+        # in both of its hardware blocks of 32).  G = 16: the matrix core has no 16-element scale block,
+        # so only the protection group is 16 wide; the scale block stays 32.
+        sg = 64 if G == 64 else 32
+        tab = wl.rng(7000 + G).integers(0, G, (K_HID // G, 1)).astype(np.int16)
+        oi = up(osc.osc_table_to_index_g(tab, G))
         ko = int(oi.numel())
-        pk, pu = osc.osc_pack_weight(Wt, oi), osc.osc_pack_weight(Wu, oi)
-        qb, qs = osc.osc_quantize_act(dX1, oi), osc.osc_quantize_act(X64, oi)
+        fmt = osc.OSC_FMT_MXFP4_OSC_G64 if sg == 64 else osc.OSC_FMT_MXFP4_OSC
+        pk, pu = osc.osc_pack_weight_g(Wt, oi, sg), osc.osc_pack_weight_g(Wu, oi, sg)
+        qb, qs = osc.osc_quantize_act(dX1, oi, fmt), osc.osc_quantize_act(X64, oi, fmt)
         tb = time_one(lambda: osc.osc_dual_gemm(*qb, pk, 4096, K_HID, ko, ydt, out=Y["q"]))
         ts = graph_time(lambda: osc.osc_dual_gemm(*qs, pu, N_UP, K_HID, ko, ydt, out=Y64))
-        t2[f"G={G}"] = {"K_o": ko,
+        t2[f"G={G}"] = {"K_o": ko, "scale_group": sg,
                         f"M={M} N=4096": {"osc_ms": round(tb, 4), "fp8_ms": round(ms_f8_big, 4),
                                           "speedup": round(ms_f8_big / tb, 3)},
                         f"M=64 N={N_UP}": {"osc_ms": round(ts, 4), "fp8_ms": round(ms_f8_64, 4),

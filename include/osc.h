@@ -42,7 +42,8 @@ enum {
 };
 
 enum { OSC_DT_F32 = 0, OSC_DT_BF16 = 1 };                   /* dtype of Y */
-enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1, OSC_FMT_MXFP8 = 2 }; /* activation quantiser format */
+enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1, OSC_FMT_MXFP8 = 2,
+       OSC_FMT_MXFP4_OSC_G64 = 3 };                          /* activation quantiser format */
 
 const char *osc_last_error(void);
 int osc_version(void);
@@ -60,6 +61,20 @@ int osc_version(void);
  * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE (Kg < 0, R < 0), OSC_ERR_TABLE.
  */
 int osc_table_to_index(const int16_t *table, int32_t Kg, int32_t R, int32_t *oidx, int32_t *K_o);
+
+/*
+ * The same conversion for the other group sizes of Section 3.1 ("Quantifying Clustering
+ * Density": the channels are cut into groups of G in {16, 32, 64}; Table 2 has one row per
+ * G): table entries are local indices in [0, G), group g covers channels g*G .. g*G+G-1.
+ * G = 32 is osc_table_to_index.  The list it writes is what every quantiser and
+ * osc_pack_weight* take, whatever G was: with G = 16 or 64 and the standard MXFP4 scale
+ * block of 32 this is a protection group narrower or wider than the scale block; for scale
+ * groups of 64 see OSC_FMT_MXFP4_OSC_G64 and osc_pack_weight_g.
+ *   oidx   room for Kg * min(R, G) entries
+ * Errors: as osc_table_to_index; OSC_ERR_UNSUPPORTED for any other G.
+ */
+int osc_table_to_index_g(const int16_t *table, int32_t Kg, int32_t R, int32_t G, int32_t *oidx,
+                         int32_t *K_o);
 
 /*
  * Offline weight preparation (Section 3.3.2, "zero-overhead offline weight
@@ -81,6 +96,17 @@ int osc_pack_weight(const void *W, int64_t N, int64_t K, int64_t ldw, const int3
                     int32_t K_o, void *Wpack, void *stream);
 int osc_unpack_weight(const void *Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t *Wq,
                       uint8_t *Ws, void *WL, void *stream);
+
+/*
+ * osc_pack_weight with scale groups of G = 64 channels along K (Table 2's G = 64 row; G = 32
+ * is osc_pack_weight): one shared exponent floor(log2(amax over the 64 channels)) - 2 per
+ * group, stored as the code of both 32-channel blocks the group covers.  Size, layout and
+ * every consumer (osc_dual_gemm, osc_grouped_dual_gemm, osc_unpack_weight) are those of
+ * osc_pack_weight: the matrix core scales blocks of 32, and two equal block scales are a
+ * group of 64.  K % 64 == 0.  Errors: as osc_pack_weight; OSC_ERR_UNSUPPORTED for any other G.
+ */
+int osc_pack_weight_g(const void *W, int64_t N, int64_t K, int64_t ldw, const int32_t *oidx,
+                      int32_t K_o, int32_t G, void *Wpack, void *stream);
 
 /*
  * FP8 fallback weights (Section 3.4): e4m3 codes with one fp32 scale per output
@@ -121,6 +147,13 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  * even.  oidx, K_o, B, ldb are ignored; K need not be a multiple of 32 but
  * must be a multiple of 8.
  *   Xq    uint8 [M, K] e4m3 codes;  Xs  float [M] scales
+ *
+ * fmt = OSC_FMT_MXFP4_OSC_G64: OSC_FMT_MXFP4_OSC with scale groups of 64 channels (Section
+ * 3.1: G in {16, 32, 64}; Table 2, row G = 64): after the protected channels are zeroed,
+ * every 64 channels share one exponent floor(log2(amax)) - 2, written as the code of both
+ * of their 32-channel blocks; elements, layouts, buffers and the B gather are unchanged, so
+ * the result feeds osc_dual_gemm as it is.  K % 64 == 0.  The table normally names one
+ * channel per 64 (osc_table_to_index_g with G = 64), but any ascending list is accepted.
  *
  * fmt = OSC_FMT_MXFP8: the 8-bit micro-scaling form of the same fallback (Section 3.4:
  * "FP8 or equivalent 8-bit micro-scaling formats"; Section 4.1, implementation

@@ -5,10 +5,11 @@ hand-written HIP kernels of ``libosc.so``.  There is no CPU fallback: calling an
 without the built library raises.
 """
 from .binding import (  # noqa: F401
-    OSC_DT_BF16, OSC_DT_F32, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP4_OSC, OSC_FMT_MXFP8, OscError, lib, lib_path,
+    OSC_DT_BF16, OSC_DT_F32, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP4_OSC, OSC_FMT_MXFP4_OSC_G64, OSC_FMT_MXFP8, OscError, lib, lib_path,
     osc_act_scale_bytes, osc_unpack_act_scales,
     osc_dual_gemm, osc_fp8_gemm, osc_grouped_dual_gemm, osc_last_error, osc_pack_weight,
     osc_pack_weight_fp8, osc_packed_weight_bytes, osc_packed_weight_fp8_bytes, osc_quantize_act,
     osc_table_to_index, osc_unpack_weight, osc_unpack_weight_fp8, osc_version,
     osc_mxfp8_gemm, osc_pack_weight_mxfp8, osc_packed_weight_mxfp8_bytes, osc_unpack_weight_mxfp8,
-    osc_quantize_act_dynamic, osc_rmsnorm_quantize_act, osc_swiglu_quantize_act, osc_probe_mfma_fp4, osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table)
+    osc_quantize_act_dynamic, osc_rmsnorm_quantize_act, osc_swiglu_quantize_act, osc_probe_mfma_fp4, osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table,
+    osc_pack_weight_g, osc_table_to_index_g)

@@ -10,7 +10,7 @@ import numpy as np
 import torch
 
 OSC_DT_F32, OSC_DT_BF16 = 0, 1
-OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP8 = 0, 1, 2
+OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP8, OSC_FMT_MXFP4_OSC_G64 = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libosc.so")
@@ -21,7 +21,9 @@ _SIGS = {
     "osc_last_error": (C.c_char_p, []),
     "osc_version": (C.c_int, []),
     "osc_table_to_index": (C.c_int, [vp, i32, i32, vp, vp]),
+    "osc_table_to_index_g": (C.c_int, [vp, i32, i32, i32, vp, vp]),
     "osc_packed_weight_bytes": (sz, [i64, i64, i32]),
+    "osc_pack_weight_g": (C.c_int, [vp, i64, i64, i64, vp, i32, i32, vp, vp]),
     "osc_pack_weight": (C.c_int, [vp, i64, i64, i64, vp, i32, vp, vp]),
     "osc_unpack_weight": (C.c_int, [vp, i64, i64, i32, vp, vp, vp, vp]),
     "osc_packed_weight_fp8_bytes": (sz, [i64, i64]),
@@ -109,6 +111,16 @@ def osc_table_to_index(table):
     return oidx[:n.value].copy()
 
 
+def osc_table_to_index_g(table, G):
+    """table: int16 [Kg, R] of local indices in groups of G channels -> int32 numpy array of channel ids."""
+    table = np.ascontiguousarray(np.asarray(table), dtype=np.int16)
+    Kg, R = table.shape
+    oidx = np.zeros(max(Kg * min(R, max(G, 1)), 1), np.int32)
+    n = i32(0)
+    _check(lib().osc_table_to_index_g(table.ctypes.data, Kg, R, G, oidx.ctypes.data, C.addressof(n)))
+    return oidx[:n.value].copy()
+
+
 def osc_packed_weight_bytes(N, K, K_o):
     return lib().osc_packed_weight_bytes(N, K, K_o)
 
@@ -126,6 +138,18 @@ def osc_pack_weight(W, oidx, out=None):
         out = torch.empty(osc_packed_weight_bytes(N, K, K_o), dtype=torch.uint8, device=W.device)
     _check(lib().osc_pack_weight(_ptr(W), N, K, W.stride(0), _ptr(oidx) if K_o else None, K_o,
                                  _ptr(out), _stream()))
+    return out
+
+
+def osc_pack_weight_g(W, oidx, G, out=None):
+    """osc_pack_weight with scale groups of G (32 or 64) channels."""
+    W = _rows16(W)
+    N, K = W.shape
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if out is None:
+        out = torch.empty(osc_packed_weight_bytes(N, K, K_o), dtype=torch.uint8, device=W.device)
+    _check(lib().osc_pack_weight_g(_ptr(W), N, K, W.stride(0), _ptr(oidx) if K_o else None, K_o, G,
+                                   _ptr(out), _stream()))
     return out
 
 
@@ -188,8 +212,8 @@ def osc_unpack_act_scales(Xs, M, K):
 
 
 def osc_quantize_act(X, oidx=None, fmt=OSC_FMT_MXFP4_OSC, ldb=None, out=None):
-    """X bf16 [M, K] (device).  MXFP4_OSC -> (Xq uint8 [M,K/2], Xs uint8 row-block-major scales,
-    B uint16 [M,ldb]);
+    """X bf16 [M, K] (device).  MXFP4_OSC, MXFP4_OSC_G64 -> (Xq uint8 [M,K/2], Xs uint8 row-block-major
+    scales, B uint16 [M,ldb]);
     FP8_E4M3_TOKEN -> (X8 uint8 [M,K], xs float32 [M]);
     MXFP8 -> (X8 uint8 [M,K], Xs uint8 row-block-major scales).  `out` may hold preallocated outputs."""
     X = _rows16(X)

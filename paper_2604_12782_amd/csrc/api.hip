@@ -66,27 +66,33 @@ extern "C" {
 const char* osc_last_error(void) { return g_err; }
 int osc_version(void) { return 100; }
 
-int osc_table_to_index(const int16_t* table, int32_t Kg, int32_t R, int32_t* oidx, int32_t* K_o) {
+int osc_table_to_index_g(const int16_t* table, int32_t Kg, int32_t R, int32_t G, int32_t* oidx, int32_t* K_o) {
     REQUIRE(table && oidx && K_o, OSC_ERR_NULL, "osc_table_to_index: null pointer");
     REQUIRE(Kg >= 0 && R >= 0, OSC_ERR_SHAPE, "osc_table_to_index: Kg=%d R=%d", Kg, R);
+    REQUIRE(G == 16 || G == 32 || G == 64, OSC_ERR_UNSUPPORTED, "osc_table_to_index: group size %d (16, 32 or 64)", G);
+    REQUIRE((int64_t)Kg * G <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "osc_table_to_index: more than 2^31-1 channels");
     int32_t n = 0;
     for (int32_t g = 0; g < Kg; ++g) {
-        uint32_t seen = 0;
+        uint64_t seen = 0;
         for (int32_t s = 0; s < R; ++s) {
             const int j = table[(int64_t)g * R + s];
             if (j == -1) continue;
-            REQUIRE(j >= 0 && j < 32, OSC_ERR_TABLE, "osc_table_to_index: group %d holds index %d", g, j);
+            REQUIRE(j >= 0 && j < G, OSC_ERR_TABLE, "osc_table_to_index: group %d holds index %d", g, j);
             REQUIRE(!(seen >> j & 1u), OSC_ERR_TABLE, "osc_table_to_index: group %d repeats index %d", g, j);
-            seen |= 1u << j;
+            seen |= (uint64_t)1 << j;
         }
         while (seen) {
-            const int j = __builtin_ctz(seen);
+            const int j = __builtin_ctzll(seen);
             seen &= seen - 1;
-            oidx[n++] = g * 32 + j;
+            oidx[n++] = g * G + j;
         }
     }
     *K_o = n;
     return OSC_OK;
+}
+
+int osc_table_to_index(const int16_t* table, int32_t Kg, int32_t R, int32_t* oidx, int32_t* K_o) {
+    return osc_table_to_index_g(table, Kg, R, 32, oidx, K_o);
 }
 
 size_t osc_packed_weight_bytes(int64_t N, int64_t K, int32_t K_o) {
@@ -108,10 +114,12 @@ static int check_mx_shape(const char* who, int64_t rows, int64_t K, int64_t ld, 
     return OSC_OK;
 }
 
-int osc_pack_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
-                    int32_t K_o, void* Wpack, void* stream) {
+int osc_pack_weight_g(const void* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
+                      int32_t K_o, int32_t G, void* Wpack, void* stream) {
+    REQUIRE(G == 32 || G == 64, OSC_ERR_UNSUPPORTED, "osc_pack_weight: scale group %d (32 or 64)", G);
     int rc = check_mx_shape("osc_pack_weight", N, K, ldw, K_o);
     if (rc) return rc;
+    REQUIRE(K % G == 0, OSC_ERR_SHAPE, "osc_pack_weight: K=%lld is not a multiple of G=%d", (long long)K, G);
     if (N == 0) return OSC_OK;
     REQUIRE(W && Wpack && (K_o == 0 || oidx), OSC_ERR_NULL, "osc_pack_weight: null pointer");
     REQUIRE(ldw % 8 == 0 && aligned(W, 16) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
@@ -120,13 +128,18 @@ int osc_pack_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const int3
     uint8_t* base = static_cast<uint8_t*>(Wpack);
     if (K > 0) {
         rc = launch_quant_mxfp4(static_cast<const uint16_t*>(W), N, K, ldw, nullptr, 0, base + L.off_q,
-                                base + L.off_s, nullptr, 0, as_stream(stream));
+                                base + L.off_s, nullptr, 0, as_stream(stream), G);
         if (rc) return rc;
     }
     if (hipMemsetAsync(base + L.off_z, 0, 256, as_stream(stream)) != hipSuccess)
         return fail(OSC_ERR_HIP, "osc_pack_weight: cannot clear the zero block");
     return launch_gather_wl(static_cast<const uint16_t*>(W), N, K, ldw, oidx, K_o,
                             reinterpret_cast<uint16_t*>(base + L.off_l), L.ldwl, as_stream(stream));
+}
+
+int osc_pack_weight(const void* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx,
+                    int32_t K_o, void* Wpack, void* stream) {
+    return osc_pack_weight_g(W, N, K, ldw, oidx, K_o, 32, Wpack, stream);
 }
 
 int osc_unpack_weight(const void* Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t* Wq, uint8_t* Ws,
@@ -232,7 +245,8 @@ int osc_unpack_weight_mxfp8(const void* Wpack, int64_t N, int64_t K, uint8_t* W8
 
 int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx, int32_t K_o,
                      int fmt, uint8_t* Xq, void* Xs, void* B, int64_t ldb, void* stream) {
-    REQUIRE(fmt == OSC_FMT_MXFP4_OSC || fmt == OSC_FMT_FP8_E4M3_TOKEN || fmt == OSC_FMT_MXFP8, OSC_ERR_UNSUPPORTED,
+    REQUIRE(fmt == OSC_FMT_MXFP4_OSC || fmt == OSC_FMT_FP8_E4M3_TOKEN || fmt == OSC_FMT_MXFP8 ||
+                fmt == OSC_FMT_MXFP4_OSC_G64, OSC_ERR_UNSUPPORTED,
             "osc_quantize_act: unknown format %d", fmt);
     if (fmt == OSC_FMT_MXFP8) {
         int rc8 = check_mx_shape("osc_quantize_act", M, K, ldx, 0);
@@ -258,6 +272,9 @@ int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int
     }
     int rc = check_mx_shape("osc_quantize_act", M, K, ldx, K_o);
     if (rc) return rc;
+    const int group = fmt == OSC_FMT_MXFP4_OSC_G64 ? 64 : 32;
+    REQUIRE(K % group == 0, OSC_ERR_SHAPE, "osc_quantize_act: K=%lld is not a multiple of the scale group %d",
+            (long long)K, group);
     REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "osc_quantize_act: ldb=%lld < K_o=%d", (long long)ldb, K_o);
     if (M == 0 || K == 0) return OSC_OK;
     REQUIRE(X && Xq && Xs, OSC_ERR_NULL, "osc_quantize_act: null pointer");
@@ -271,7 +288,7 @@ int osc_quantize_act(const void* X, int64_t M, int64_t K, int64_t ldx, const int
     }
     return launch_quant_mxfp4(static_cast<const uint16_t*>(X), M, K, ldx, oidx, K_o, Xq,
                               static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(B), B ? ldb : 0,
-                              as_stream(stream));
+                              as_stream(stream), group);
 }
 
 int osc_rmsnorm_quantize_act(const void* X, const void* gamma, float eps, int64_t M, int64_t K, int64_t ldx,

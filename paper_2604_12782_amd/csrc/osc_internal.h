@@ -52,7 +52,7 @@ PackM8Layout packm8_layout(int64_t N, int64_t K);
 // kernels' host launchers (each enqueues on `st`, returns OSC_OK / OSC_ERR_HIP)
 int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx,
                        int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
-                       hipStream_t st);
+                       hipStream_t st, int group = 32);
 int launch_quant_mxfp4_dynamic(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, uint8_t* Xs,
                                uint16_t* Bd, int64_t ldb, uint8_t* idx, hipStream_t st);
 int launch_rmsnorm_quant_mxfp4(const uint16_t* X, const uint16_t* gamma, float eps, int64_t M, int64_t K, int64_t ldx,

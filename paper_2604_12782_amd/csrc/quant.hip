@@ -31,6 +31,10 @@ constexpr int QT = 256;  // threads per workgroup
 // rows at a time: the 4-byte scale words of those rows share 128-byte lines and meet in that
 // XCD's L2 before they are written back.
 // ------------------------------------------------------------------------------------------
+//
+// GS is the size of a scale group: 32, or 64 (one more exchange: the two quads that hold a group
+// of 64 agree on the larger amax, and its code is written for both of the group's blocks of 32).
+template <int GS>
 __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
     const uint16_t* __restrict__ X, int M, int K, int64_t ldx, const int32_t* __restrict__ oidx,
     int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs, uint16_t* __restrict__ B,
@@ -106,9 +110,11 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
                 a = max(a, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
                 a = max(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0xB1, 0xF, 0xF, false));  // lane ^ 1
                 a = max(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x4E, 0xF, 0xF, false));  // lane ^ 2
+                if (GS == 64)  // lane 7 - l of the same eight lanes sits in the group's other quad
+                    a = max(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x141, 0xF, 0xF, false));
                 // shared exponent floor(log2 amax) - 2, clamped below: E8M0 code = max(E - 2, 0)
                 const uint32_t code = (uint32_t)max((int)(a >> 7) - 2, 0);
-                // four groups (one DPP row of 16 lanes) -> one 32-bit scale word in the row's first lane;
+                // four blocks of 32 (one DPP row of 16 lanes) -> one 32-bit scale word in the row's first lane;
                 // chunks past the end of the row hold zeros, so their code is 0
                 uint32_t word = code;
                 word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;   // lane + 4
@@ -161,7 +167,9 @@ __global__ void zero_rows_kernel(uint16_t* B, int M, int64_t ldb) {
 
 int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx,
                        int32_t K_o, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb,
-                       hipStream_t st) {
+                       hipStream_t st, int group) {
+    if (group != 32 && group != 64) return fail(OSC_ERR_UNSUPPORTED, "quantize: scale group %d (32 or 64)", group);
+    if (K % group) return fail(OSC_ERR_SHAPE, "quantize: K=%lld is not a multiple of the scale group %d", (long long)K, group);
     if (K > 65536) return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld exceeds 65536", (long long)K);
     const int64_t nchunk = K / 8;
     const int nseg = (int)((nchunk + SEG_CHUNKS - 1) / SEG_CHUNKS);
@@ -169,8 +177,9 @@ int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, con
     if (K_o > 0) smem += (size_t)(K / 2) * 4 + (size_t)(nseg + 1) * 4 + (size_t)K_o * 2;
     if (smem > 160 * 1024)
         return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld with K_o=%d needs %zu bytes of LDS", (long long)K, (int)K_o, smem);
+    auto kern = group == 64 ? quant_mxfp4_osc_kernel<64> : quant_mxfp4_osc_kernel<32>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(quant_mxfp4_osc_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return fail(OSC_ERR_HIP, "quantize: LDS attribute: %s", hipGetErrorString(e));
     }
@@ -182,7 +191,7 @@ int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, con
     int grid = (int)(total_wg < cap ? total_wg : cap);
     if (K_o == 0 && B && ldb > 0)
         hipLaunchKernelGGL(zero_rows_kernel, dim3(grid), dim3(QT), 0, st, B, (int)M, ldb);
-    hipLaunchKernelGGL(quant_mxfp4_osc_kernel, dim3(grid), dim3(QT), smem, st, X, (int)M, (int)K, ldx, oidx,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(QT), smem, st, X, (int)M, (int)K, ldx, oidx,
                        (int)K_o, Xq, Xs, B, ldb, nseg, (int)total_wg);
     return check_launch("quant_mxfp4_osc_kernel");
 }

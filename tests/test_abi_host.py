@@ -37,6 +37,16 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
     assert osc.osc_version() >= 100
 
 
+def test_table_to_index_g_host(lib):
+    t = np.array([[63, -1], [0, 40], [-1, -1]], np.int16)
+    assert osc.osc_table_to_index_g(t, 64).tolist() == [63, 64, 104]
+    assert osc.osc_table_to_index_g(np.array([[15, 0], [-1, 3]], np.int16), 16).tolist() == [0, 15, 19]
+    assert osc.osc_table_to_index_g(t[:, :1] % 32, 32).tolist() == osc.osc_table_to_index(t[:, :1] % 32).tolist()
+    for bad, G in (([[64]], 64), ([[16]], 16), ([[3, 3]], 64), ([[1]], 48), ([[1]], 0)):
+        with pytest.raises(osc.OscError):
+            osc.osc_table_to_index_g(np.array(bad, np.int16), G)
+
+
 def test_table_to_index_host(lib):
     t = np.array([[5, -1], [-1, -1], [31, 0], [-1, 7]], np.int16)
     assert osc.osc_table_to_index(t).tolist() == [5, 64, 95, 96 + 7]

@@ -58,17 +58,17 @@ def gaussian_rows(gen, M, K, chunk=1024):
     return x
 
 
-def activations_persistent(seed, M, K, r, factor="loguniform", lo=20.0, hi=100.0, jitter=0.0):
-    """N(0,1) activations with r token-persistent outlier channels per 32-group.
+def activations_persistent(seed, M, K, r, factor="loguniform", lo=20.0, hi=100.0, jitter=0.0, group=G):
+    """N(0,1) activations with r token-persistent outlier channels per group of `group` channels.
 
     factor: "loguniform" -> one factor per channel, exp(U(ln lo, ln hi));
             a float      -> that constant.
     jitter: per-(token, channel) relative jitter u*jitter, u ~ U(-1, 1).
-    Returns (X bits [M,K], table int16 [K/32, max(r,1)]).
+    Returns (X bits [M,K], table int16 [K/group, max(r,1)]).
     """
     gen = rng(seed)
-    table = planted_table(gen, K, r)
-    ch = table_channels(table)
+    table = planted_table(gen, K, r, group)
+    ch = table_channels(table, group)
     x = gaussian_rows(gen, M, K)
     if len(ch):
         if factor == "loguniform":

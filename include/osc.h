@@ -283,6 +283,18 @@ int osc_swiglu_quantize_act(const void *G, const void *U, int64_t M, int64_t K, 
                             int64_t ldu, uint8_t *Xq, void *Xs, void *Yn, void *stream);
 
 /*
+ * The same producer fused with the per-token FP8 quantiser (Section 3.4, the e4m3 form of the
+ * W_2 fallback that osc_fp8_gemm multiplies): what osc_quantize_act(fmt =
+ * OSC_FMT_FP8_E4M3_TOKEN) returns for y = bf16(bf16(silu(g)) * u), silu as defined above.
+ *   G, U  as above; K % 8 == 0, K <= 16384
+ *   X8    uint8 [M, K] e4m3 codes;  xs  float [M] scales (amax/448, or 1 for rows below 2^-100)
+ *   Yn    bf16 [M, K] (device) or NULL: receives y when given
+ * Errors as osc_quantize_act.
+ */
+int osc_swiglu_quantize_act_fp8(const void *G, const void *U, int64_t M, int64_t K, int64_t ldg,
+                                int64_t ldu, uint8_t *X8, float *xs, void *Yn, void *stream);
+
+/*
  * "Dynamic" protection, the control experiment of Section 4.2 (Table 3, note 3: per-group
  * maximum value detection at run time).  Like osc_quantize_act(fmt = OSC_FMT_MXFP4_OSC) with
  * one slot per group, except that the protected position is chosen per token: the largest

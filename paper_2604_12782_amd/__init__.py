@@ -12,4 +12,4 @@ from .binding import (  # noqa: F401
     osc_table_to_index, osc_unpack_weight, osc_unpack_weight_fp8, osc_version,
     osc_mxfp8_gemm, osc_pack_weight_mxfp8, osc_packed_weight_mxfp8_bytes, osc_unpack_weight_mxfp8,
     osc_quantize_act_dynamic, osc_rmsnorm_quantize_act, osc_swiglu_quantize_act, osc_probe_mfma_fp4, osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table,
-    osc_pack_weight_g, osc_table_to_index_g)
+    osc_pack_weight_g, osc_table_to_index_g, osc_swiglu_quantize_act_fp8)

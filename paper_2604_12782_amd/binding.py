@@ -40,6 +40,7 @@ _SIGS = {
     "osc_fp8_gemm": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, i32, vp, C.c_int, i64, vp]),
     "osc_rmsnorm_quantize_act": (C.c_int, [vp, vp, C.c_float, i64, i64, i64, vp, i32, vp, vp, vp, i64, vp, vp]),
     "osc_swiglu_quantize_act": (C.c_int, [vp, vp, i64, i64, i64, i64, vp, vp, vp, vp]),
+    "osc_swiglu_quantize_act_fp8": (C.c_int, [vp, vp, i64, i64, i64, i64, vp, vp, vp, vp]),
     "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
     "osc_probe_mfma_fp4": (C.c_int, [i32, i32, vp, vp, vp]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
@@ -395,3 +396,20 @@ def osc_swiglu_quantize_act(G, U, want_y=False, out=None):
     _check(lib().osc_swiglu_quantize_act(_ptr(G), _ptr(U), M, K, G.stride(0), U.stride(0), _ptr(Xq), _ptr(Xs),
                                          _ptr(Yn), _stream()))
     return Xq, Xs, Yn
+
+
+def osc_swiglu_quantize_act_fp8(G, U, want_y=False, out=None):
+    """SwiGLU + per-token FP8 quantiser in one pass -> (X8 uint8 [M, K], xs float32 [M], Yn uint16 [M, K] or None)."""
+    G, U = _rows16(G), _rows16(U)
+    M, K = G.shape
+    assert U.shape == G.shape
+    dev = G.device
+    if out is not None:
+        X8, xs, Yn = out
+    else:
+        X8 = torch.empty((M, K), dtype=torch.uint8, device=dev)
+        xs = torch.empty(M, dtype=torch.float32, device=dev)
+        Yn = torch.empty((M, K), dtype=torch.uint16, device=dev) if want_y else None
+    _check(lib().osc_swiglu_quantize_act_fp8(_ptr(G), _ptr(U), M, K, G.stride(0), U.stride(0), _ptr(X8), _ptr(xs),
+                                             _ptr(Yn), _stream()))
+    return X8, xs, Yn

@@ -323,6 +323,21 @@ int osc_swiglu_quantize_act(const void* G, const void* U, int64_t M, int64_t K, 
                                      Xq, static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(Yn), as_stream(stream));
 }
 
+int osc_swiglu_quantize_act_fp8(const void* G, const void* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                uint8_t* X8, float* xs, void* Yn, void* stream) {
+    REQUIRE(M >= 0 && K >= 0, OSC_ERR_SHAPE, "osc_swiglu_quantize_act_fp8: negative extent");
+    REQUIRE(ldg >= K && ldu >= K, OSC_ERR_SHAPE, "osc_swiglu_quantize_act_fp8: leading dimension below K=%lld", (long long)K);
+    REQUIRE(K % 8 == 0, OSC_ERR_SHAPE, "osc_swiglu_quantize_act_fp8: K=%lld is not a multiple of 8", (long long)K);
+    REQUIRE(M <= 0x7fffffff && K <= 0x7fffffff, OSC_ERR_UNSUPPORTED, "osc_swiglu_quantize_act_fp8: extent above 2^31-1");
+    if (M == 0) return OSC_OK;
+    REQUIRE(X8 && xs && ((G && U) || K == 0), OSC_ERR_NULL, "osc_swiglu_quantize_act_fp8: null pointer");
+    REQUIRE(ldg % 8 == 0 && ldu % 8 == 0 && aligned(G, 16) && aligned(U, 16) && aligned(X8, 8) && aligned(xs, 4) &&
+                aligned(Yn, 16),
+            OSC_ERR_UNSUPPORTED, "osc_swiglu_quantize_act_fp8: misaligned pointer or leading dimension");
+    return launch_swiglu_quant_fp8(static_cast<const uint16_t*>(G), static_cast<const uint16_t*>(U), M, K, ldg, ldu,
+                                   X8, xs, static_cast<uint16_t*>(Yn), as_stream(stream));
+}
+
 int osc_quantize_act_dynamic(const void* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, void* Xs, void* Bd,
                              int64_t ldb, uint8_t* idx, void* stream) {
     int rc = check_mx_shape("osc_quantize_act_dynamic", M, K, ldx, 0);

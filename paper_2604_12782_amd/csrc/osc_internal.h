@@ -60,6 +60,8 @@ int launch_rmsnorm_quant_mxfp4(const uint16_t* X, const uint16_t* gamma, float e
                                uint16_t* Xn, hipStream_t st);
 int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                               uint8_t* Xq, uint8_t* Xs, uint16_t* Yn, hipStream_t st);
+int launch_swiglu_quant_fp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                            uint8_t* X8, float* xs, uint16_t* Yn, hipStream_t st);
 int launch_quant_fp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* X8, float* xs,
                      hipStream_t st);
 int launch_quant_mxfp8(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, uint8_t* Xq, uint8_t* Xs,

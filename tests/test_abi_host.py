@@ -125,6 +125,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert sw(FAKE, FAKE, 4, 64, 64, 32, FAKE, FAKE, None, None) == -2   # ldu < K
     assert sw(FAKE, FAKE, 4, 64, 68, 64, FAKE, FAKE, None, None) == -4   # ldg % 8
     assert sw(None, None, 0, 64, 64, 64, None, None, None, None) == 0
+    s8 = lib.osc_swiglu_quantize_act_fp8
+    assert s8(FAKE, None, 4, 64, 64, 64, FAKE, FAKE, None, None) == -1
+    assert s8(FAKE, FAKE, 4, 64, 64, 32, FAKE, FAKE, None, None) == -2   # ldu < K
+    assert s8(FAKE, FAKE, 4, 60, 64, 64, FAKE, FAKE, None, None) == -2   # K % 8
+    assert s8(FAKE, FAKE, 4, 64, 68, 64, FAKE, FAKE, None, None) == -4   # ldg % 8
+    assert s8(FAKE, FAKE, 4, 32768, 32768, 32768, FAKE, FAKE, None, None) == -4   # K above the kernel's limit
+    assert s8(None, None, 0, 64, 64, 64, None, None, None, None) == 0
     dq = lib.osc_quantize_act_dynamic
     assert dq(FAKE, 4, 64, 64, FAKE, FAKE, FAKE, 32, None, None) == -2   # ldb < K
     assert dq(FAKE, 4, 48, 48, FAKE, FAKE, FAKE, 48, None, None) == -2   # K % 32

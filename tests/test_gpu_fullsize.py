@@ -292,3 +292,21 @@ def test_fused_rmsnorm_quant_config1_shape(osc):
     assert np.array_equal(host(Xn), y)
     assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, M, K)), rs)
     assert np.array_equal(host(Xq), rq) and np.array_equal(host(B), rb)
+
+
+def test_fused_swiglu_quant_ffn_width(osc):
+    """Both SwiGLU fusions at the FFN width of configs[2] (K = 12288), gate and up as the two halves
+    of one buffer, compared in full."""
+    M, K = 2048, 12288
+    gen = wl.rng(3300)
+    G = wl.to_bf16_bits((gen.standard_normal((M, K)) * 2.5).astype(np.float32))
+    U = wl.activations_diffuse(3301, M, K, p=0.005)
+    both = dev(np.concatenate([G, U], axis=1))
+    y = oracle.swiglu(G, U)
+    Xq, Xs, Yn = osc.osc_swiglu_quantize_act(both[:, :K], both[:, K:], want_y=True)
+    rq, rs = oracle.quantize_mxfp8(y)
+    assert np.array_equal(host(Yn), y) and np.array_equal(host(Xq), rq)
+    assert np.array_equal(host(osc.osc_unpack_act_scales(Xs, M, K)), rs)
+    X8, xs, _ = osc.osc_swiglu_quantize_act_fp8(both[:, :K], both[:, K:])
+    r8, rsc = oracle.quantize_fp8_rows(y)
+    assert np.array_equal(host(X8), r8) and np.array_equal(host(xs).view(np.uint32), rsc.view(np.uint32))

@@ -116,3 +116,45 @@ def test_swiglu_every_gate_value(osc):
     gen = wl.rng(1501)
     U = to_bf16_bits((0.5 + gen.random(G.shape)).astype(np.float32))
     check_swiglu(osc, G, U)
+
+
+# ---- SwiGLU + per-token FP8 quantiser -------------------------------------------------------
+def check_swiglu_fp8(osc, G, U, strided=False):
+    M, K = G.shape
+    if strided:
+        both = torch.from_numpy(np.concatenate([G, U], axis=1)).cuda()
+        dG, dU = both[:, :K], both[:, K:]
+    else:
+        dG, dU = dev(G), dev(U)
+    X8, xs, Yn = osc.osc_swiglu_quantize_act_fp8(dG, dU, want_y=True)
+    y = oracle.swiglu(G, U)
+    r8, rsc = oracle.quantize_fp8_rows(y)
+    assert np.array_equal(Yn.cpu().numpy(), y), "activation values differ"
+    assert np.array_equal(xs.cpu().numpy().view(np.uint32), rsc.view(np.uint32)), "scales differ"
+    assert np.array_equal(X8.cpu().numpy(), r8), "codes differ"
+    U8, us = osc.osc_quantize_act(Yn, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    assert torch.equal(U8, X8) and torch.equal(us, xs)
+    X8b, xsb, none = osc.osc_swiglu_quantize_act_fp8(dG, dU)
+    assert none is None and torch.equal(X8b, X8) and torch.equal(xsb, xs)
+
+
+@pytest.mark.parametrize("M,K", [(1, 8), (7, 96), (40, 1056), (130, 4096), (9, 12288), (3, 16384), (5, 2056)])
+def test_swiglu_fp8_fused_matches_oracle(osc, M, K):
+    gen = wl.rng(1600 + M)
+    G = to_bf16_bits((gen.standard_normal((M, K)) * 3).astype(np.float32))
+    U = wl.activations_diffuse(1700 + M, M, K, p=0.01)
+    if M > 4:
+        G[2] = 0  # an all-zero row: scale 1, codes 0
+        U[3] = to_bf16_bits(np.full(K, 1e-36, np.float32))  # a row below 2^-100: scale 1
+    check_swiglu_fp8(osc, G, U)
+    check_swiglu_fp8(osc, G, U, strided=True)
+
+
+def test_swiglu_fp8_every_gate_value(osc):
+    bits = np.arange(0x10000, dtype=np.uint32).astype(np.uint16)
+    bits = bits[((bits >> 7) & 0xFF) < 227]
+    K = 2048
+    pad = (-len(bits)) % K
+    G = np.concatenate([bits, np.zeros(pad, np.uint16)]).reshape(-1, K)
+    U = to_bf16_bits((0.5 + wl.rng(1801).random(G.shape)).astype(np.float32))
+    check_swiglu_fp8(osc, G, U)

@@ -193,6 +193,8 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
     // byte offset of this lane's four columns inside a 32x32 result tile: row 4q + r%4, columns 4(r/4) ..
     const uint32_t yoff8 = 2u * (uint32_t)((4 * q + (r & 3)) * (int)a.ldy + (r & ~3));
     const bool hi2 = (r & 2) != 0;
+    // 16-byte stores of eight bf16 columns need rows that keep 16-byte alignment
+    const bool wide16 = (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
     // byte selector of step 2: even lanes [own.lo, other.lo], odd lanes [other.hi, own.hi]
     const uint32_t sel12 = odd ? 0x03020706u : 0x05040100u;
     auto store_tile = [&](auto kind_tag) __attribute__((always_inline)) {
@@ -209,6 +211,62 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
                 for (int k = 0; k < 16; ++k) {
                     const int row = rbase + 8 * (k >> 2) + (k & 3);
                     xr[k] = a.xs[FULL ? row : min(row, row_end - 1)];
+                }
+            }
+            if constexpr (KIND >= 1 && TN % 2 == 0) {
+                if (a.y_bf16 && wide16) {
+                    // 16-byte stores: the two exchange rounds described below, on two neighbouring tiles,
+                    // then a third between lanes l and l^4: lanes of even column groups complete eight
+                    // adjacent columns of the left tile, the others of the right tile, so one store
+                    // instruction writes eight rows of 128 contiguous bytes.
+                    const bool lo4 = (r & 4) != 0;
+                    const uint32_t yoff16 = 2u * (uint32_t)((4 * q + (r & 3)) * (int)a.ldy + (r & ~3) + (lo4 ? 28 : 0));
+#pragma unroll
+                    for (int jp = 0; jp < TN; jp += 2) {
+                        u32x2 o[2][4];
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const int j = jp + s2;
+                            float cs = 1.0f;
+                            if (MODE == MODE_FP8) cs = wsc[n0 + wn * (TN * 32) + j * 32 + r];
+                            uint32_t P[8], W[8];
+#pragma unroll
+                            for (int k = 0; k < 8; ++k) {
+                                const float v0 = (MODE == MODE_FP8) ? acc[i][j][2 * k] * (xr[2 * k] * cs) : acc[i][j][2 * k];
+                                const float v1 = (MODE == MODE_FP8) ? acc[i][j][2 * k + 1] * (xr[2 * k + 1] * cs)
+                                                                     : acc[i][j][2 * k + 1];
+                                const v2f pair = {v0, v1};
+                                P[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pair, v2bf));
+                            }
+#pragma unroll
+                            for (int k = 0; k < 8; ++k) {
+                                const uint32_t Q = (uint32_t)__builtin_amdgcn_mov_dpp((int)P[k], 0xB1, 0xF, 0xF, true);
+                                W[k] = __builtin_amdgcn_perm(Q, P[k], sel12);
+                            }
+#pragma unroll
+                            for (int h = 0; h < 4; ++h) {
+                                const uint32_t ra = (uint32_t)__builtin_amdgcn_mov_dpp((int)W[2 * h], 0x4E, 0xF, 0xF, true);
+                                const uint32_t rb = (uint32_t)__builtin_amdgcn_mov_dpp((int)W[2 * h + 1], 0x4E, 0xF, 0xF, true);
+                                o[s2][h] = (u32x2){hi2 ? rb : W[2 * h], hi2 ? W[2 * h + 1] : ra};
+                            }
+                        }
+                        uint8_t* const ybase = reinterpret_cast<uint8_t*>(a.Y) +
+                            2 * ((int64_t)(m0 + wu_m * (TM * 32) + i * 32) * a.ldy + n0 + wu_n * (TN * 32) + jp * 32);
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            // lane + 4 sends its left-tile words down, lane - 4 its right-tile words up
+                            const uint32_t dx = (uint32_t)__builtin_amdgcn_mov_dpp((int)o[0][h].x, 0x104, 0xF, 0xF, true);
+                            const uint32_t dy = (uint32_t)__builtin_amdgcn_mov_dpp((int)o[0][h].y, 0x104, 0xF, 0xF, true);
+                            const uint32_t ux = (uint32_t)__builtin_amdgcn_mov_dpp((int)o[1][h].x, 0x114, 0xF, 0xF, true);
+                            const uint32_t uy = (uint32_t)__builtin_amdgcn_mov_dpp((int)o[1][h].y, 0x114, 0xF, 0xF, true);
+                            const u32x4 out = {lo4 ? ux : o[0][h].x, lo4 ? uy : o[0][h].y, lo4 ? o[1][h].x : dx,
+                                               lo4 ? o[1][h].y : dy};
+                            uint8_t* const hbase = ybase + 2 * (int64_t)(8 * h) * a.ldy;
+                            if (FULL || rbase + 8 * h + (r & 3) < row_end)
+                                __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(hbase + yoff16));
+                        }
+                    }
+                    continue;
                 }
             }
 #pragma unroll

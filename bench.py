@@ -31,7 +31,7 @@ K_HID = 4096
 # K_o=256, bf16 out), from rocprofv3 FETCH_SIZE/WRITE_SIZE runs of this script scaled by a 1 GiB
 # plain copy (summary: profiles/configs1_M8192_step__hbm_traffic.txt).  A profiler reading, not
 # something this script can measure itself.
-DOMINANT_TRAFFIC_BYTES = {8192: 245.6e6}
+DOMINANT_TRAFFIC_BYTES = {8192: 218.3e6}
 PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
 
 

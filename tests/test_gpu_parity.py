@@ -343,3 +343,27 @@ def test_mxfp8_grouped(osc):
             ref[lo:hi] = oracle.mxfp8_gemm(r8[lo:hi], rs[lo:hi], w8, wsc)
     Y = osc.osc_mxfp8_gemm(X8, Xs, Wp, N, K, expert_offsets=dev(off))
     check_close(host(Y), ref, "grouped mxfp8 gemm")
+
+
+# ---- largest supported row length ---------------------------------------------------------------
+
+
+@pytest.mark.parametrize("r", [0, 1])
+def test_quant_longest_rows(osc, r):
+    """K = 65536 is the quantiser's limit (with a table the masks of a row take 128 KB of LDS)."""
+    M, K = 5, 65536
+    X, table = wl.activations_persistent(900 + r, M, K, r)
+    oidx = oracle.table_to_index(table)
+    assert len(oidx) == r * K // 32
+    quant_both(osc, X, oidx)
+    with pytest.raises(osc.OscError):
+        osc.osc_quantize_act(dev(np.zeros((2, 65536 + 32), np.uint16)), None)
+
+
+def test_dual_gemm_long_k(osc):
+    """256 stages in one tile: M = 40 rows (the skinny kernel) and 200 rows (the DMA kernel)."""
+    N, K = 96, 32768
+    W = wl.weights(911, N, K)
+    for M in (40, 200):
+        X, table = wl.activations_persistent(910 + M, M, K, 1)
+        run_dual(osc, X, W, oracle.table_to_index(table))

@@ -92,3 +92,56 @@ def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
             close(view, ref, f"ldy={width} col0={col0} bf16={bf}", bf)
             rest = torch.cat([wide[:, :col0], wide[:, col0 + N:]], dim=1)
             assert (rest == 7.0).all(), "wrote outside the output view"
+
+
+@pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1"])
+def test_grouped_with_skewed_experts(osc, monkeypatch, cfg):
+    """Experts of 0, 1, 63 ... 700 rows, sizes on both sides of every tile border, through the
+    256-row tiles with their 64-row remainder pass (4,1) and the smaller tiles: dual path with a row
+    map, per-token FP8 and MXFP8."""
+    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+    sizes = [0, 1, 63, 64, 65, 127, 128, 129, 255, 256, 257, 383, 384, 385, 700, 0, 130]
+    E = len(sizes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    T = int(off[-1])
+    tokens, K, N, r = 900, 512, 256, 2
+    X, table = wl.activations_persistent(7500, tokens, K, r)
+    oidx = oracle.table_to_index(table)
+    row_map = wl.rng(7501).integers(0, tokens, T).astype(np.int32)
+    Xq, Xs, B = osc.osc_quantize_act(dev(X), dev(oidx))
+    rq, rs, rb = oracle.quantize_mxfp4_osc(X, oidx, ldb=B.shape[1])
+    stride = osc.osc_packed_weight_bytes(N, K, len(oidx))
+    Wp = torch.empty(E * stride, dtype=torch.uint8, device="cuda")
+    wq, wsc, wlr = [], [], []
+    for e in range(E):
+        W = wl.weights(7510 + e, N, K)
+        osc.osc_pack_weight(dev(W), dev(oidx), out=Wp[e * stride:(e + 1) * stride])
+        a, b, _ = oracle.quantize_mxfp4_osc(W)
+        wq.append(a), wsc.append(b), wlr.append(oracle.gather_wl(W, oidx))
+    ref = oracle.grouped_dual_gemm(rq, rs, rb, row_map, off, np.stack(wq), np.stack(wsc), np.stack(wlr))
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Y = osc.osc_grouped_dual_gemm(Xq, Xs, B, dev(row_map), dev(off), T, Wp, N, K, len(oidx), ydt)
+        close(Y, ref, f"grouped dual {cfg} bf16={bf}", bf)
+    # 8-bit forms: rows in expert order (no row map in these entry points)
+    K2 = 384
+    X2 = wl.activations_diffuse(7502, T, K2)
+    X8, xs = osc.osc_quantize_act(dev(X2), None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    Xm, Xms = osc.osc_quantize_act(dev(X2), None, osc.OSC_FMT_MXFP8)
+    r8, r8s = oracle.quantize_fp8_rows(X2)
+    m8, m8s = oracle.quantize_mxfp8(X2)
+    s8, sm = osc.osc_packed_weight_fp8_bytes(N, K2), osc.osc_packed_weight_mxfp8_bytes(N, K2)
+    Wp8 = torch.empty(E * s8, dtype=torch.uint8, device="cuda")
+    Wpm = torch.empty(E * sm, dtype=torch.uint8, device="cuda")
+    w8, w8s = [], []
+    refm = np.zeros((T, N))
+    for e in range(E):
+        W = wl.weights(7530 + e, N, K2)
+        osc.osc_pack_weight_fp8(dev(W), out=Wp8[e * s8:(e + 1) * s8])
+        osc.osc_pack_weight_mxfp8(dev(W), out=Wpm[e * sm:(e + 1) * sm])
+        a, b = oracle.quantize_fp8_rows(W)
+        w8.append(a), w8s.append(b)
+        if off[e + 1] > off[e]:
+            refm[off[e]:off[e + 1]] = oracle.mxfp8_gemm(m8[off[e]:off[e + 1]], m8s[off[e]:off[e + 1]], *oracle.quantize_mxfp8(W))
+    ref8 = oracle.grouped_fp8_gemm(r8, r8s, off, np.stack(w8), np.stack(w8s))
+    close(osc.osc_fp8_gemm(X8, xs, Wp8, N, K2, expert_offsets=dev(off), y_dtype=osc.OSC_DT_BF16), ref8, "grouped fp8 " + cfg, True)
+    close(osc.osc_mxfp8_gemm(Xm, Xms, Wpm, N, K2, expert_offsets=dev(off), y_dtype=osc.OSC_DT_BF16), refm, "grouped mxfp8 " + cfg, True)

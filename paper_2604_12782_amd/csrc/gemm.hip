@@ -1742,6 +1742,13 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         // wavefront of a SIMD fills the issue gaps of the first
         if (tm == 4) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
         if (tm == 1) return launch_dma2<MODE, 1, 2>(a, p.M, grouped, st);
+        // dual path, one problem: 128x256 tiles on eight wavefronts (64x64 each) beat two resident
+        // workgroups of 128x128 by 4 % when they still give every CU a tile (8192x1024x4096: 29.1
+        // against 30.3 us); the 8-bit modes gain nothing from them
+        if constexpr (MODE == MODE_DUAL) {
+            if (!grouped && ((p.M + 127) / 128) * ((p.N + 255) / 256) >= 256)
+                return launch_dma2<MODE, 2, 2, 4>(a, p.M, grouped, st);
+        }
         return launch_dma2<MODE, 2, 2>(a, p.M, grouped, st);
     }
     if constexpr (MODE == MODE_MX8) {

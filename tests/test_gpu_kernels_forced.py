@@ -145,3 +145,22 @@ def test_grouped_with_skewed_experts(osc, monkeypatch, cfg):
     ref8 = oracle.grouped_fp8_gemm(r8, r8s, off, np.stack(w8), np.stack(w8s))
     close(osc.osc_fp8_gemm(X8, xs, Wp8, N, K2, expert_offsets=dev(off), y_dtype=osc.OSC_DT_BF16), ref8, "grouped fp8 " + cfg, True)
     close(osc.osc_mxfp8_gemm(Xm, Xms, Wpm, N, K2, expert_offsets=dev(off), y_dtype=osc.OSC_DT_BF16), refm, "grouped mxfp8 " + cfg, True)
+
+
+def test_wide_128x256_tiles_ragged(osc):
+    """4100 x 2000: the launcher's own choice here is 128x256 tiles on eight wavefronts, with a ragged
+    last tile in both directions; a row of every fourth m-tile and the borders against the oracle."""
+    M, N, K, r = 4100, 2000, 512, 2
+    X, table = wl.activations_persistent(7600, M, K, r)
+    W = wl.weights(7601, N, K)
+    oidx = oracle.table_to_index(table)
+    rows = np.unique(np.concatenate([np.arange(0, 32, 4) * 128 + 5, [0, 127, 128, 4095, 4096, 4099]]))
+    Xq, Xs, B = osc.osc_quantize_act(dev(X), dev(oidx))
+    Wp = osc.osc_pack_weight(dev(W), dev(oidx))
+    rq, rs, rb = oracle.quantize_mxfp4_osc(X[rows], oidx, ldb=B.shape[1])
+    wq, ws, _ = oracle.quantize_mxfp4_osc(W)
+    ref = oracle.dual_gemm(rq, rs, rb, wq, ws, oracle.gather_wl(W, oidx))
+    sel = torch.from_numpy(rows).cuda()
+    for ydt, bf in ((osc.OSC_DT_BF16, True), (osc.OSC_DT_F32, False)):
+        Y = osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), ydt)
+        close(Y[sel], ref, f"128x256 tiles bf16={bf}", bf)

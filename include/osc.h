@@ -5,7 +5,8 @@
  * Conventions shared by every entry point
  *   - Linear layer Y = X . W^T with X[M, K] (tokens x input channels) and
  *     W[N, K] (output x input channels).  Quantisation groups are 32 consecutive
- *     input channels (MXFP4, G = 32).
+ *     input channels (MXFP4, G = 32) unless an entry point says otherwise (scale
+ *     groups of 64: OSC_FMT_MXFP4_OSC_G64, osc_pack_weight_g).
  *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked
  *     "host".  The library never allocates, frees or keeps a pointer past the call.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
@@ -35,7 +36,7 @@ enum {
     OSC_OK = 0,
     OSC_ERR_NULL = -1,        /* a required pointer is NULL */
     OSC_ERR_SHAPE = -2,       /* negative extent, K % 32 != 0, leading dimension < extent */
-    OSC_ERR_TABLE = -3,       /* table entry outside [-1, 32) or repeated inside a group */
+    OSC_ERR_TABLE = -3,       /* table entry outside [-1, G) or repeated inside a group */
     OSC_ERR_UNSUPPORTED = -4, /* unknown enum value, misaligned pointer or stride */
     OSC_ERR_WORKSPACE = -5,   /* reserved */
     OSC_ERR_HIP = -6          /* the HIP runtime refused a launch */

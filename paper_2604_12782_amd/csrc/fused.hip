@@ -304,64 +304,55 @@ int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, i
 
 // ------------------------------------------------------------------------------------------
 // SwiGLU fused with the per-token FP8 quantiser (Section 3.4: the W_2 inputs stay in 8 bits; this
-// is the per-token e4m3 form of that fallback): one workgroup per row, y = bf16(bf16(silu(g)) * u)
+// is the per-token e4m3 form of that fallback): one wavefront per row, y = bf16(bf16(silu(g)) * u)
 // stays in registers between the row's amax reduction and the conversion, so gate and up are read
 // once and y is never written unless asked for.
 // ------------------------------------------------------------------------------------------
-template <int CPT>
+template <int NCI>
 __global__ void __launch_bounds__(FT) swiglu_quant_fp8_kernel(const uint16_t* __restrict__ G,
                                                               const uint16_t* __restrict__ U, int M, int K,
                                                               int64_t ldg, int64_t ldu, uint8_t* __restrict__ X8,
                                                               float* __restrict__ xs, uint16_t* __restrict__ Yn) {
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-    __shared__ uint32_t red[FT / 64];
-    const int t = threadIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int nchunk = K >> 3;
-    for (int m = blockIdx.x; m < M; m += gridDim.x) {
+    // a wavefront owns a whole row (lane l holds chunks l, l + 64, ...): the row's amax is register work
+    // plus one 64-lane reduction, no barrier
+    for (int m = blockIdx.x * 4 + wave; m < M; m += gridDim.x * 4) {
         const u32x4* gsrc = reinterpret_cast<const u32x4*>(G + (int64_t)m * ldg);
         const u32x4* usrc = reinterpret_cast<const u32x4*>(U + (int64_t)m * ldu);
-        u32x4 gv[CPT], uv[CPT];
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int c = t + FT * i;
-            gv[i] = (u32x4){0u, 0u, 0u, 0u};
-            uv[i] = (u32x4){0u, 0u, 0u, 0u};
-            if (c < nchunk) {
-                gv[i] = __builtin_nontemporal_load(gsrc + c);
-                uv[i] = __builtin_nontemporal_load(usrc + c);
-            }
-        }
-        uint32_t y[CPT][4];
+        uint32_t y[NCI][4];
         uint32_t a = 0;
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            y[i][0] = swiglu_pair(gv[i].x, uv[i].x);
-            y[i][1] = swiglu_pair(gv[i].y, uv[i].y);
-            y[i][2] = swiglu_pair(gv[i].z, uv[i].z);
-            y[i][3] = swiglu_pair(gv[i].w, uv[i].w);
+        for (int i = 0; i < NCI; ++i) {
+            const int c = lane + 64 * i;
+            u32x4 gv = {0u, 0u, 0u, 0u}, uv = {0u, 0u, 0u, 0u};
+            if (c < nchunk) {
+                gv = __builtin_nontemporal_load(gsrc + c);
+                uv = __builtin_nontemporal_load(usrc + c);
+            }
+            y[i][0] = swiglu_pair(gv.x, uv.x);
+            y[i][1] = swiglu_pair(gv.y, uv.y);
+            y[i][2] = swiglu_pair(gv.z, uv.z);
+            y[i][3] = swiglu_pair(gv.w, uv.w);
 #pragma unroll
             for (int k = 0; k < 4; ++k) a = max(a, max(y[i][k] & 0x7fffu, (y[i][k] >> 16) & 0x7fffu));
-            const int c = t + FT * i;
             if (Yn && c < nchunk)
                 __builtin_nontemporal_store((u32x4){y[i][0], y[i][1], y[i][2], y[i][3]},
                                             reinterpret_cast<u32x4*>(Yn + (int64_t)m * K) + c);
         }
         a = wave_max_u32(a);
-        __syncthreads();  // red[] of the previous row is no longer read
-        if ((t & 63) == 0) red[t >> 6] = a;
-        __syncthreads();
-        a = max(max(red[0], red[1]), max(red[2], red[3]));
         const float amax = __builtin_bit_cast(float, a << 16);
         float scale = 1.0f, inv = 1.0f;
         if (amax >= 0x1p-100f) {
             scale = __fdiv_rn(amax, 448.0f);
             inv = __fdiv_rn(448.0f, amax);
         }
-        if (t == 0) xs[m] = scale;
+        if (lane == 0) xs[m] = scale;
         u32x2* dst = reinterpret_cast<u32x2*>(X8 + (int64_t)m * K);
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int c = t + FT * i;
+        for (int i = 0; i < NCI; ++i) {
+            const int c = lane + 64 * i;
             if (c < nchunk) {
                 float p[8];
 #pragma unroll
@@ -384,16 +375,17 @@ __global__ void __launch_bounds__(FT) swiglu_quant_fp8_kernel(const uint16_t* __
 
 int launch_swiglu_quant_fp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                             uint8_t* X8, float* xs, uint16_t* Yn, hipStream_t st) {
-    const int64_t nchunk = K / 8;
-    const int cpt = (int)((nchunk + FT - 1) / FT);
-    const int grid = (int)(M < 8192 ? M : 8192);
+    const int64_t nci = (K / 8 + 63) / 64;
+    const int64_t want = (M + 3) / 4;
+    const int grid = (int)(want < 4096 ? want : 4096);
 #define OSC_SLAUNCH(C)                                                                                      \
     hipLaunchKernelGGL(swiglu_quant_fp8_kernel<C>, dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, X8, \
                        xs, Yn)
-    if (cpt <= 1) OSC_SLAUNCH(1);
-    else if (cpt <= 2) OSC_SLAUNCH(2);
-    else if (cpt <= 4) OSC_SLAUNCH(4);
-    else if (cpt <= 8) OSC_SLAUNCH(8);
+    if (nci <= 4) OSC_SLAUNCH(4);
+    else if (nci <= 8) OSC_SLAUNCH(8);
+    else if (nci <= 16) OSC_SLAUNCH(16);
+    else if (nci <= 24) OSC_SLAUNCH(24);
+    else if (nci <= 32) OSC_SLAUNCH(32);
     else return fail(OSC_ERR_UNSUPPORTED, "swiglu+fp8 quantize: K=%lld exceeds 16384", (long long)K);
 #undef OSC_SLAUNCH
     return check_launch("swiglu_quant_fp8_kernel");

@@ -8,7 +8,9 @@
  *     input channels (MXFP4, G = 32) unless an entry point says otherwise (scale
  *     groups of 64: OSC_FMT_MXFP4_OSC_G64, osc_pack_weight_g).
  *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked
- *     "host".  The library never allocates, frees or keeps a pointer past the call.
+ *     "host".  The library never allocates, frees or keeps a pointer past the call
+ *     (its only device memory of its own is one static 128 KB table, see
+ *     osc_swiglu_quantize_act).
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
  *     enqueue work and return; they never synchronise the device.
  *   - Return value: OSC_OK or a negative error; on error nothing was launched.
@@ -278,6 +280,11 @@ int osc_rmsnorm_quantize_act(const void *X, const void *gamma, float eps, int64_
  *         halves of one fused GEMM output are fine: pass the pointers and the common stride)
  *   Xq    uint8 [M, K] E4M3 codes; Xs E8M0 scales as for OSC_FMT_MXFP8
  *   Yn    bf16 [M, K] (device) or NULL: receives y when given
+ * From a few million elements on, this call and osc_swiglu_quantize_act_fp8 first tabulate
+ * bf16(silu(g)) for all 65536 bf16 values of g with the arithmetic above (a second small kernel on
+ * the same stream, into 128 KB of device memory that the library owns) and look the values up;
+ * the results are the same bits.  Calls that overlap on one device rewrite the table with
+ * identical contents.  The environment variable OSC_SWIGLU_TABLE = 0 / 1 forces the choice.
  * Errors as osc_quantize_act.
  */
 int osc_swiglu_quantize_act(const void *G, const void *U, int64_t M, int64_t K, int64_t ldg,

@@ -227,15 +227,54 @@ __device__ __forceinline__ uint32_t swiglu_pair(uint32_t g, uint32_t u) {
     return mul_pair(t, u);
 }
 
-__global__ void __launch_bounds__(FT) swiglu_quant_mxfp8_kernel(const uint16_t* __restrict__ G,
+// bf16(silu(g)) is a function of the 16 bits of g: 65536 values, 128 KB.  For large inputs the
+// kernels below tabulate it once per call with the arithmetic above (every CU takes a slice), copy
+// the table into LDS (one workgroup per CU) and replace ~28 vector operations per element by one
+// LDS read; the results are the same bits by construction.  The table lives in device memory owned
+// by the library (128 KB per process and device); concurrent calls rewrite it with identical values.
+__device__ __attribute__((aligned(256))) uint16_t g_silu_tab[65536];
+
+__global__ void __launch_bounds__(256) silu_table_kernel() {
+    const uint32_t i = (blockIdx.x * 256u + threadIdx.x) * 2u;  // two neighbouring entries per thread
+    const v2f s = {silu_f32(__builtin_bit_cast(float, i << 16)), silu_f32(__builtin_bit_cast(float, (i + 1u) << 16))};
+    reinterpret_cast<uint32_t*>(g_silu_tab)[i >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(s, v2bf));
+}
+// the table from device memory into this workgroup's LDS (blockDim threads, 16 bytes each per trip)
+__device__ __forceinline__ void load_silu_table(uint16_t* tab) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(g_silu_tab);
+    u32x4* dst = reinterpret_cast<u32x4*>(tab);
+    for (int i = threadIdx.x; i < 65536 * 2 / 16; i += blockDim.x) dst[i] = src[i];
+    __syncthreads();
+}
+template <bool TAB>
+__device__ __forceinline__ uint32_t swiglu_pair_t(uint32_t g, uint32_t u, const uint16_t* tab) {
+    if constexpr (TAB) {
+        const uint32_t t = (uint32_t)tab[g & 0xffffu] | ((uint32_t)tab[g >> 16] << 16);
+        return mul_pair(t, u);
+    } else {
+        return swiglu_pair(g, u);
+    }
+}
+
+// TAB: 1024 threads, the silu table in LDS; every four wavefronts act as one of the 256-thread
+// workgroups of the work split
+template <bool TAB>
+__global__ void __launch_bounds__(TAB ? 1024 : FT) swiglu_quant_mxfp8_kernel(const uint16_t* __restrict__ G,
                                                                 const uint16_t* __restrict__ U, int M, int K,
                                                                 int64_t ldg, int64_t ldu, uint8_t* __restrict__ Xq,
                                                                 uint8_t* __restrict__ Xs, uint16_t* __restrict__ Yn,
                                                                 int nseg, int total_wg) {
+    extern __shared__ uint16_t silu_lds[];
+    if (TAB) load_silu_table(silu_lds);
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
+    const int t = threadIdx.x, lane = t & 63, wave = (t >> 6) & 3;
+    const int sub = TAB ? (t >> 8) : 0, nsub = TAB ? 4 : 1;
+    // virtual workgroup number: keeps "number % 8 = XCD of the real workgroup", which the work split uses
+    // to give one XCD the 32 rows that share lines of scale words
+    const int b = blockIdx.x;
+    const int first = (gridDim.x & 7) == 0 ? (b & 7) + 8 * ((b >> 3) * nsub + sub) : b * nsub + sub;
+    for (int wg = first; wg < total_wg; wg += gridDim.x * nsub) {
         const QItem it = quant_item(wg, wave, nseg, M);
         if (it.m < 0) continue;  // uniform over the wavefront
         const int m = it.m;
@@ -255,8 +294,8 @@ __global__ void __launch_bounds__(FT) swiglu_quant_mxfp8_kernel(const uint16_t* 
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = c0 + 64 * i;
-            const uint32_t ww[4] = {swiglu_pair(gv[i].x, uv[i].x), swiglu_pair(gv[i].y, uv[i].y),
-                                    swiglu_pair(gv[i].z, uv[i].z), swiglu_pair(gv[i].w, uv[i].w)};
+            const uint32_t ww[4] = {swiglu_pair_t<TAB>(gv[i].x, uv[i].x, silu_lds), swiglu_pair_t<TAB>(gv[i].y, uv[i].y, silu_lds),
+                                    swiglu_pair_t<TAB>(gv[i].z, uv[i].z, silu_lds), swiglu_pair_t<TAB>(gv[i].w, uv[i].w, silu_lds)};
             if (Yn && c < nchunk)
                 __builtin_nontemporal_store((u32x4){ww[0], ww[1], ww[2], ww[3]},
                                             reinterpret_cast<u32x4*>(Yn + (int64_t)m * K) + c);
@@ -289,6 +328,19 @@ __global__ void __launch_bounds__(FT) swiglu_quant_mxfp8_kernel(const uint16_t* 
     }
 }
 
+constexpr int SILU_TAB_BYTES = 65536 * 2;
+// The table pays for itself (its 128 KB are copied into every CU's LDS, about 2 us) from a few
+// million elements on.  OSC_SWIGLU_TABLE=0 / 1 forces the choice (a tuning and test aid; the results
+// are the same bits either way).
+static bool use_silu_table(int64_t M, int64_t K) {
+    if (const char* ev = getenv("OSC_SWIGLU_TABLE")) return ev[0] == '1';
+    return M * K >= ((int64_t)4 << 20);
+}
+static int launch_silu_table(hipStream_t st) {
+    hipLaunchKernelGGL(silu_table_kernel, dim3(128), dim3(256), 0, st);
+    return check_launch("silu_table_kernel");
+}
+
 int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                               uint8_t* Xq, uint8_t* Xs, uint16_t* Yn, hipStream_t st) {
     const int64_t nchunk = K / 8;
@@ -296,8 +348,21 @@ int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, i
     const int64_t blocks = (M + 31) / 32;
     const int64_t total_wg = (blocks + 7) / 8 * 8 * (8 * nseg);
     if (total_wg > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "swiglu+quantize: M=%lld too large", (long long)M);
+    if (use_silu_table(M, K)) {
+        int rc = launch_silu_table(st);
+        if (rc) return rc;
+        auto kern = swiglu_quant_mxfp8_kernel<true>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                SILU_TAB_BYTES) != hipSuccess)
+            return fail(OSC_ERR_HIP, "swiglu+quantize: cannot reserve the table's LDS");
+        const int64_t need = (total_wg + 3) / 4;
+        const int grid = (int)(need < 256 ? need : 256);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), SILU_TAB_BYTES, st, G, U, (int)M, (int)K, ldg, ldu, Xq, Xs, Yn,
+                           nseg, (int)total_wg);
+        return check_launch("swiglu_quant_mxfp8_kernel<table>");
+    }
     const int grid = (int)(total_wg < 8192 ? total_wg : 8192);
-    hipLaunchKernelGGL(swiglu_quant_mxfp8_kernel, dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, Xq,
+    hipLaunchKernelGGL(swiglu_quant_mxfp8_kernel<false>, dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, Xq,
                        Xs, Yn, nseg, (int)total_wg);
     return check_launch("swiglu_quant_mxfp8_kernel");
 }
@@ -308,17 +373,21 @@ int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, i
 // stays in registers between the row's amax reduction and the conversion, so gate and up are read
 // once and y is never written unless asked for.
 // ------------------------------------------------------------------------------------------
-template <int NCI>
-__global__ void __launch_bounds__(FT) swiglu_quant_fp8_kernel(const uint16_t* __restrict__ G,
+// TAB: 768 threads (twelve rows at a time), the silu table in LDS
+template <int NCI, bool TAB>
+__global__ void __launch_bounds__(TAB ? 768 : FT) swiglu_quant_fp8_kernel(const uint16_t* __restrict__ G,
                                                               const uint16_t* __restrict__ U, int M, int K,
                                                               int64_t ldg, int64_t ldu, uint8_t* __restrict__ X8,
                                                               float* __restrict__ xs, uint16_t* __restrict__ Yn) {
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    extern __shared__ uint16_t silu_lds[];
+    if (TAB) load_silu_table(silu_lds);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int nwave = TAB ? 12 : 4;
     const int nchunk = K >> 3;
     // a wavefront owns a whole row (lane l holds chunks l, l + 64, ...): the row's amax is register work
     // plus one 64-lane reduction, no barrier
-    for (int m = blockIdx.x * 4 + wave; m < M; m += gridDim.x * 4) {
+    for (int m = blockIdx.x * nwave + wave; m < M; m += gridDim.x * nwave) {
         const u32x4* gsrc = reinterpret_cast<const u32x4*>(G + (int64_t)m * ldg);
         const u32x4* usrc = reinterpret_cast<const u32x4*>(U + (int64_t)m * ldu);
         uint32_t y[NCI][4];
@@ -331,10 +400,10 @@ __global__ void __launch_bounds__(FT) swiglu_quant_fp8_kernel(const uint16_t* __
                 gv = __builtin_nontemporal_load(gsrc + c);
                 uv = __builtin_nontemporal_load(usrc + c);
             }
-            y[i][0] = swiglu_pair(gv.x, uv.x);
-            y[i][1] = swiglu_pair(gv.y, uv.y);
-            y[i][2] = swiglu_pair(gv.z, uv.z);
-            y[i][3] = swiglu_pair(gv.w, uv.w);
+            y[i][0] = swiglu_pair_t<TAB>(gv.x, uv.x, silu_lds);
+            y[i][1] = swiglu_pair_t<TAB>(gv.y, uv.y, silu_lds);
+            y[i][2] = swiglu_pair_t<TAB>(gv.z, uv.z, silu_lds);
+            y[i][3] = swiglu_pair_t<TAB>(gv.w, uv.w, silu_lds);
 #pragma unroll
             for (int k = 0; k < 4; ++k) a = max(a, max(y[i][k] & 0x7fffu, (y[i][k] >> 16) & 0x7fffu));
             if (Yn && c < nchunk)
@@ -376,10 +445,32 @@ __global__ void __launch_bounds__(FT) swiglu_quant_fp8_kernel(const uint16_t* __
 int launch_swiglu_quant_fp8(const uint16_t* G, const uint16_t* U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
                             uint8_t* X8, float* xs, uint16_t* Yn, hipStream_t st) {
     const int64_t nci = (K / 8 + 63) / 64;
+    if (nci > 32) return fail(OSC_ERR_UNSUPPORTED, "swiglu+fp8 quantize: K=%lld exceeds 16384", (long long)K);
+    if (use_silu_table(M, K)) {
+        int rc = launch_silu_table(st);
+        if (rc) return rc;
+        const int64_t need = (M + 11) / 12;
+        const int tgrid = (int)(need < 256 ? need : 256);
+#define OSC_TLAUNCH(C)                                                                                          \
+    {                                                                                                           \
+        auto kern = swiglu_quant_fp8_kernel<C, true>;                                                           \
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                SILU_TAB_BYTES) != hipSuccess)                                                  \
+            return fail(OSC_ERR_HIP, "swiglu+fp8 quantize: cannot reserve the table's LDS");                    \
+        hipLaunchKernelGGL(kern, dim3(tgrid), dim3(768), SILU_TAB_BYTES, st, G, U, (int)M, (int)K, ldg, ldu, X8, xs, Yn); \
+    }
+        if (nci <= 4) OSC_TLAUNCH(4)
+        else if (nci <= 8) OSC_TLAUNCH(8)
+        else if (nci <= 16) OSC_TLAUNCH(16)
+        else if (nci <= 24) OSC_TLAUNCH(24)
+        else OSC_TLAUNCH(32)
+#undef OSC_TLAUNCH
+        return check_launch("swiglu_quant_fp8_kernel<table>");
+    }
     const int64_t want = (M + 3) / 4;
     const int grid = (int)(want < 4096 ? want : 4096);
 #define OSC_SLAUNCH(C)                                                                                      \
-    hipLaunchKernelGGL(swiglu_quant_fp8_kernel<C>, dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, X8, \
+    hipLaunchKernelGGL((swiglu_quant_fp8_kernel<C, false>), dim3(grid), dim3(FT), 0, st, G, U, (int)M, (int)K, ldg, ldu, X8, \
                        xs, Yn)
     if (nci <= 4) OSC_SLAUNCH(4);
     else if (nci <= 8) OSC_SLAUNCH(8);

@@ -66,3 +66,47 @@ def test_step_replays_equal_eager(osc, M):
         # eager work of the same entry points between replays
         osc.osc_dual_gemm(*q, Wp, N, K, K_o, osc.OSC_DT_F32, out=torch.empty_like(Y1))
         torch.cuda.synchronize()
+
+
+def test_swiglu_fusions_with_table_replay_equal_eager(osc, monkeypatch):
+    """The SwiGLU fusions on their table path (two kernels per call: the silu table, then the
+    quantiser that copies it into LDS) under capture; replays on changing inputs equal eager runs."""
+    monkeypatch.setenv("OSC_SWIGLU_TABLE", "1")
+    M, K = 300, 1536
+    dev = torch.device("cuda:0")
+    gen = wl.rng(4100)
+    bits = [wl.to_bf16_bits((gen.standard_normal((M, 2 * K)) * s).astype(np.float32)) for s in (1.0, 4.0)]
+    GU = torch.empty((M, 2 * K), dtype=torch.uint16, device=dev)
+    m8 = osc.osc_swiglu_quantize_act(GU[:, :K], GU[:, K:])
+    f8 = osc.osc_swiglu_quantize_act_fp8(GU[:, :K], GU[:, K:])
+
+    def step():
+        osc.osc_swiglu_quantize_act(GU[:, :K], GU[:, K:], out=(m8[0], m8[1], None))
+        osc.osc_swiglu_quantize_act_fp8(GU[:, :K], GU[:, K:], out=(f8[0], f8[1], None))
+
+    def eager(b):
+        GU.copy_(torch.from_numpy(b).to(dev))
+        step()
+        torch.cuda.synchronize()
+        return m8[0].clone(), m8[1].clone(), f8[0].clone(), f8[1].clone()
+
+    refs = [eager(b) for b in bits]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i in range(4):
+        GU.copy_(torch.from_numpy(bits[i & 1]).to(dev))
+        for t in (m8[0], f8[0], f8[1]):
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        r = refs[i & 1]
+        assert torch.equal(m8[0], r[0]) and torch.equal(m8[1], r[1]) and torch.equal(f8[0], r[2]) and torch.equal(f8[1], r[3]), f"replay {i}"
+        monkeypatch.setenv("OSC_SWIGLU_TABLE", "0")  # eager work on the other path in between
+        osc.osc_swiglu_quantize_act(GU[:, :K], GU[:, K:])
+        monkeypatch.setenv("OSC_SWIGLU_TABLE", "1")
+        torch.cuda.synchronize()

@@ -2,7 +2,7 @@
 """Benchmark of the OSC dual-path linear layer on one MI355X.
 
 One step = the whole hot path of one Qwen3-8B attention block's linear layers at M tokens
-(BASELINE configs[1]): quantise+gather the attention input, dual-path GEMMs q (4096->4096),
+(benchmark configuration 1, "configs[1]"): quantise+gather the attention input, dual-path GEMMs q (4096->4096),
 k and v (4096->1024) on it, quantise+gather the o-projection input, dual-path GEMM o
 (4096->4096).  Inputs are synthetic (seeded N(0,1) with two token-persistent outlier channels
 per 32-group), resident in HBM before the timed region.  The same GEMM shapes are also run
@@ -136,7 +136,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
     ap.add_argument("--sweep", action="store_true",
-                    help="instead of the benchmark line: time the other BASELINE shapes (table on stdout)")
+                    help="instead of the benchmark line: time the shapes of the other benchmark configurations (table on stdout)")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a counter yardstick for profiler runs)")
     args = ap.parse_args()

@@ -1,4 +1,4 @@
-"""GPU parity at the full BASELINE sizes, in the launch configuration that bench.py times.
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration that bench.py times.
 
 The quantisers' outputs are compared with the oracle in full (bit for bit).  The GEMMs run on the
 whole problem on the GPU; the oracle recomputes a seeded sample of complete output rows (all N)

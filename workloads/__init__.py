@@ -121,7 +121,7 @@ def moe_routing(seed, tokens, E, top_k):
     return offsets, row_map
 
 
-# ---- the five BASELINE configurations -----------------------------------------
+# ---- the five benchmark configurations ----------------------------------------
 
 
 def config1_tiny():

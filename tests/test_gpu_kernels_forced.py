@@ -85,7 +85,9 @@ def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
     wq, ws, _ = oracle.quantize_mxfp4_osc(W)
     ref = oracle.dual_gemm(rq, rs, rb, wq, ws, oracle.gather_wl(W, oidx))
     for dt, ydt, bf in ((torch.float32, osc.OSC_DT_F32, False), (torch.bfloat16, osc.OSC_DT_BF16, True)):
-        for width, col0 in ((N + 64, 0), (N + 7, 3)):  # aligned wide buffer; odd stride and odd first column
+        # aligned wide buffer (16-byte stores); first column 4 elements in (8-byte stores for bf16);
+        # odd stride and odd first column (element stores)
+        for width, col0 in ((N + 64, 0), (N + 64, 4), (N + 7, 3)):
             wide = torch.full((M, width), 7.0, dtype=dt, device="cuda")
             view = wide[:, col0:col0 + N]
             osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), ydt, out=view)

@@ -112,3 +112,26 @@ def test_g64_attention_m8192_full_size():
     wl_ref = oracle.gather_wl(W, oidx)
     assert np.array_equal(host(Wq), wq) and np.array_equal(host(Ws), ws) and np.array_equal(host(WL), wl_ref)
     dual_sampled(m, qd, qr, Wp, (wq, ws, wl_ref), N, K, 128, sample_rows(64, M, 32), m.OSC_DT_BF16, "g64 cfg2 bf16")
+
+
+def test_profile_to_quantiser_pipeline_g64(osc):
+    """The offline chain at G = 64, all on the device side: threshold (Eq. 1), per-token group
+    argmax counts, table (Alg. 1), then the table through osc_table_to_index_g into the G = 64
+    quantiser.  The planted table comes back, and the quantiser's gathered sub-tensor holds exactly
+    the planted channels."""
+    S, H, r = 600, 1024, 1
+    X, planted = wl.activations_persistent(6464, S, H, r, group=64)
+    dX = dev(X.view(np.int16)).view(torch.bfloat16)
+    T = osc.osc_profile_threshold(osc.osc_profile_abs_sum(dX), S * H, 5.0)
+    hist = osc.osc_profile_hist(dX, T, 64)
+    table, n_total, n_hit, density, cbar = osc.osc_profile_table(hist, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(table.cpu().numpy(), planted)
+    assert cbar.item() > 0.95
+    # the oracle's profile of the same data agrees
+    rt, _, _, _, _ = oracle.profile_table(oracle.profile_hist(X, oracle.profile_threshold(X, 5.0), G=64), 1)
+    assert np.array_equal(rt, planted)
+    oidx = osc.osc_table_to_index_g(table.cpu().numpy(), 64)
+    assert np.array_equal(oidx, oracle.table_to_index(planted, G=64))
+    (Xq, Xs, B), _ = quant_both_g64(osc, X, oidx)
+    assert np.array_equal(host(B)[:, :len(oidx)], X[:, oidx])

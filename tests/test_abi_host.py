@@ -163,3 +163,14 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libosc.so")
     with pytest.raises(OSError):
         binding.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: the benchmark says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)

@@ -269,8 +269,8 @@ def main():
     ms_copy = time_one(lambda: cp_dst.copy_(cp_src), reps=5)
     del cp_src, cp_dst
     probe_out = torch.zeros(1, dtype=torch.float32, device=dev)
-    probe_flops = osc.osc_probe_mfma_fp4(2048, 256, probe_out)
-    ms_probe = time_one(lambda: osc.osc_probe_mfma_fp4(2048, 256, probe_out), reps=5)
+    probe_flops = osc_probe.osc_probe_mfma_fp4(2048, 256, probe_out)
+    ms_probe = time_one(lambda: osc_probe.osc_probe_mfma_fp4(2048, 256, probe_out), reps=5)
 
     def read_sclk():
         # current shader clock from the driver's sysfs table (the line marked with '*'); no child process

@@ -284,7 +284,7 @@ int osc_rmsnorm_quantize_act(const void *X, const void *gamma, float eps, int64_
  * bf16(silu(g)) for all 65536 bf16 values of g with the arithmetic above (a second small kernel on
  * the same stream, into 128 KB of device memory that the library owns) and look the values up;
  * the results are the same bits.  Calls that overlap on one device rewrite the table with
- * identical contents.  The environment variable OSC_SWIGLU_TABLE = 0 / 1 forces the choice.
+ * identical contents.
  * Errors as osc_quantize_act.
  */
 int osc_swiglu_quantize_act(const void *G, const void *U, int64_t M, int64_t K, int64_t ldg,
@@ -318,19 +318,6 @@ int osc_swiglu_quantize_act_fp8(const void *G, const void *U, int64_t M, int64_t
  */
 int osc_quantize_act_dynamic(const void *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
                              void *Xs, void *Bd, int64_t ldb, uint8_t *idx, void *stream);
-
-/* ---- measurement aid ------------------------------------------------------------ */
-
-/*
- * Matrix-core probe (no passage of the paper: a yardstick for the measurements).  Runs
- * `workgroups` workgroups of eight wavefronts, each issuing `iters` x 8 FP4 block-scaled MFMAs
- * (the instruction of the dual-path GEMM) on pseudo-random register operands with nothing else in
- * the loop, and reports through *flops (host) how many floating-point operations that is.  Timed by
- * the caller, it gives the matrix rate this machine sustains at its real clocks, to be set beside
- * the published peak.
- *   out  float (device), 4-byte aligned: never written in practice (keeps the result alive)
- */
-int osc_probe_mfma_fp4(int32_t workgroups, int32_t iters, float *out, double *flops, void *stream);
 
 /* ---- offline profiling (calibration) ------------------------------------------ */
 

@@ -42,7 +42,8 @@ _SIGS = {
     "osc_swiglu_quantize_act": (C.c_int, [vp, vp, i64, i64, i64, i64, vp, vp, vp, vp]),
     "osc_swiglu_quantize_act_fp8": (C.c_int, [vp, vp, i64, i64, i64, i64, vp, vp, vp, vp]),
     "osc_quantize_act_dynamic": (C.c_int, [vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]),
-    "osc_probe_mfma_fp4": (C.c_int, [i32, i32, vp, vp, vp]),
+    "osc_tuning_set": (C.c_int, [C.c_int, C.c_int]),
+    "osc_tuning_get": (C.c_int, [C.c_int]),
     "osc_profile_abs_sum": (C.c_int, [vp, i64, i64, i64, vp, vp]),
     "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
     "osc_profile_hist": (C.c_int, [vp, i64, i64, i64, i32, vp, vp, vp]),
@@ -372,13 +373,16 @@ def osc_rmsnorm_quantize_act(X, gamma, eps=1e-6, oidx=None, ldb=None, want_norm=
     return Xq, Xs, B, Xn
 
 
-def osc_probe_mfma_fp4(workgroups, iters, out=None):
-    """Enqueues the matrix-core probe; returns the number of floating-point operations it performs."""
-    if out is None:
-        out = torch.zeros(1, dtype=torch.float32, device="cuda")
-    flops = C.c_double(0.0)
-    _check(lib().osc_probe_mfma_fp4(workgroups, iters, _ptr(out), C.addressof(flops), _stream()))
-    return flops.value
+OSC_TUNE_GEMM_TILE, OSC_TUNE_GEMM_KERNEL, OSC_TUNE_GROUPED_ONE_TILE, OSC_TUNE_SWIGLU_TABLE = 0, 1, 2, 3
+
+
+def osc_tuning_set(knob, value):
+    """Kernel-choice override for tests and tuning (include/osc_tuning.h); value < 0 = automatic."""
+    _check(lib().osc_tuning_set(knob, -1 if value is None else int(value)))
+
+
+def osc_tuning_get(knob):
+    return lib().osc_tuning_get(knob)
 
 
 def osc_swiglu_quantize_act(G, U, want_y=False, out=None):

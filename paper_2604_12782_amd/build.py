@@ -1,4 +1,5 @@
-"""Builds libosc.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds libosc.so (the product) and libosc_probe.so (the benchmark's matrix-core yardstick) in-tree
+with hipcc, for gfx950 only."""
 import os
 import subprocess
 import sys
@@ -6,11 +7,13 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libosc.so")
-SOURCES = ["api.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip", "probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libosc_probe.so")
+SOURCES = ["api.hip", "tuning.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip"]
+PROBE_SOURCES = ["probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function", *([f"-D{d}" for d in __import__("os").environ.get("OSC_DEFINES","").split()]),
+    "-Wall", "-Wno-unused-function",
 ]
 
 
@@ -18,7 +21,7 @@ def build(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
-    for s in SOURCES:
+    for s in SOURCES + PROBE_SOURCES:
         o = os.path.join(CSRC, s.replace(".hip", ".o"))
         objs.append(o)
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o]
@@ -32,7 +35,9 @@ def build(verbose=False):
             raise RuntimeError(f"hipcc failed on {s}:\n{out}")
         if verbose and out.strip():
             print(out)
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    n = len(SOURCES)
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[:n], "-o", LIB])
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[n:], "-o", PROBE_LIB])
     return LIB
 
 

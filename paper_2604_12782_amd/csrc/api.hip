@@ -470,16 +470,6 @@ int osc_fp8_gemm(const uint8_t* X8, const float* xs, const void* W8pack, int64_t
     return launch_fp8_gemm(p, as_stream(stream));
 }
 
-// ---- measurement aid ---------------------------------------------------------------------
-
-int osc_probe_mfma_fp4(int32_t workgroups, int32_t iters, float* out, double* flops, void* stream) {
-    REQUIRE(workgroups > 0 && iters > 0, OSC_ERR_SHAPE, "osc_probe_mfma_fp4: workgroups=%d iters=%d", workgroups, iters);
-    REQUIRE(out && flops, OSC_ERR_NULL, "osc_probe_mfma_fp4: null pointer");
-    // 8 wavefronts x 8 MFMAs of 32x32x64 per iteration, 2 flops per multiply-add
-    *flops = (double)workgroups * 8.0 * 8.0 * (double)iters * 2.0 * 32.0 * 32.0 * 64.0;
-    return launch_probe_mfma_fp4(workgroups, iters, out, as_stream(stream));
-}
-
 // ---- offline profiling -------------------------------------------------------------------
 
 static int check_profile_x(const char* who, const void* X, int64_t S, int64_t H, int64_t ldx) {

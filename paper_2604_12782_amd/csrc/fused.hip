@@ -167,9 +167,9 @@ static int launch_fused_nci(const uint16_t* X, const uint16_t* gamma, double eps
                     (int)K_o, smem);
     auto kern = rmsnorm_quant_mxfp4_kernel<NCI>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return fail(OSC_ERR_HIP, "rmsnorm+quantize: LDS attribute: %s", hipGetErrorString(e));
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
     }
     const int64_t want = (M + 3) / 4;
     // as many workgroups as the chip holds at once (LDS decides how many per CU), each wavefront then
@@ -330,10 +330,10 @@ __global__ void __launch_bounds__(TAB ? 1024 : FT) swiglu_quant_mxfp8_kernel(con
 
 constexpr int SILU_TAB_BYTES = 65536 * 2;
 // The table pays for itself (its 128 KB are copied into every CU's LDS, about 2 us) from a few
-// million elements on.  OSC_SWIGLU_TABLE=0 / 1 forces the choice (a tuning and test aid; the results
+// million elements on.  The OSC_TUNE_SWIGLU_TABLE override forces the choice (a tuning and test aid; the results
 // are the same bits either way).
 static bool use_silu_table(int64_t M, int64_t K) {
-    if (const char* ev = getenv("OSC_SWIGLU_TABLE")) return ev[0] == '1';
+    if (const int t = tuning(TUNE_SWIGLU_TABLE); t >= 0) return t == 1;
     return M * K >= ((int64_t)4 << 20);
 }
 static int launch_silu_table(hipStream_t st) {
@@ -352,9 +352,9 @@ int launch_swiglu_quant_mxfp8(const uint16_t* G, const uint16_t* U, int64_t M, i
         int rc = launch_silu_table(st);
         if (rc) return rc;
         auto kern = swiglu_quant_mxfp8_kernel<true>;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                SILU_TAB_BYTES) != hipSuccess)
-            return fail(OSC_ERR_HIP, "swiglu+quantize: cannot reserve the table's LDS");
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), SILU_TAB_BYTES, lds_done, lds_reserved)) return rc;
         const int64_t need = (total_wg + 3) / 4;
         const int grid = (int)(need < 256 ? need : 256);
         hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), SILU_TAB_BYTES, st, G, U, (int)M, (int)K, ldg, ldu, Xq, Xs, Yn,
@@ -454,9 +454,9 @@ int launch_swiglu_quant_fp8(const uint16_t* G, const uint16_t* U, int64_t M, int
 #define OSC_TLAUNCH(C)                                                                                          \
     {                                                                                                           \
         auto kern = swiglu_quant_fp8_kernel<C, true>;                                                           \
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                SILU_TAB_BYTES) != hipSuccess)                                                  \
-            return fail(OSC_ERR_HIP, "swiglu+fp8 quantize: cannot reserve the table's LDS");                    \
+        static unsigned char lds_done[MAX_DEVICES];                                                             \
+        static size_t lds_reserved[MAX_DEVICES];                                                                \
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), SILU_TAB_BYTES, lds_done, lds_reserved)) return rc; \
         hipLaunchKernelGGL(kern, dim3(tgrid), dim3(768), SILU_TAB_BYTES, st, G, U, (int)M, (int)K, ldg, ldu, X8, xs, Yn); \
     }
         if (nci <= 4) OSC_TLAUNCH(4)

@@ -1509,21 +1509,15 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
     const int64_t ntiles = tiles_m * a.tiles_n;
     if (ntiles <= 0) return OSC_OK;
     if (ntiles > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
-        ncu = n;
-    }
+    const int ncu = cu_count();
+    if (ncu <= 0) return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;  // workgroups that fit one CU's LDS
     const int64_t grid = ntiles < (int64_t)ncu * per_cu ? ntiles : (int64_t)ncu * per_cu;
     auto kern = gemm_pipe2_kernel<TM, TN, WN>;
     if (smem > 64 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a, (int)ntiles);
     return check_launch("gemm_pipe2_kernel");
@@ -1719,14 +1713,8 @@ static int launch_skinny(KArgs a, hipStream_t st) {
     // two workgroups per 32 output channels, one per 32-row tile of X (the second pass over a weight
     // row is an L2 hit; one workgroup with both tiles needs 50 % more LDS and measured slower).
     const unsigned mtiles = (unsigned)((a.M + 31) / 32);
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
-        ncu = n;
-    }
+    const int ncu = cu_count();
+    if (ncu <= 0) return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
     // Four wavefronts need 64 KB of LDS: two workgroups per CU.  When the grid is larger than that
     // (12288 output channels x two row tiles = 768 workgroups on 256 CUs) the tail round runs half
     // empty; three wavefronts (48 KB, three workgroups per CU) keep everything resident: 9.5 us
@@ -1755,9 +1743,9 @@ static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st)
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
     auto kern = gemm_kernel<MODE, TM, TN, RAGGED>;
     if (smem > 64 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), smem, st, a);
     return check_launch("gemm_kernel");
@@ -1779,9 +1767,9 @@ static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
     auto kern = gemm_dma2_kernel<MODE, TM, TN, WN>;
     if (smem > 64 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a);
     return check_launch("gemm_dma2_kernel");
@@ -1800,21 +1788,17 @@ static int launch_dma2g(KArgs a, int64_t rows_total, hipStream_t st) {
     const int64_t ntiles = tiles_m * a.tiles_n;
     if (ntiles <= 0) return OSC_OK;
     if (ntiles > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
-        ncu = n;
-    }
+    const int ncu = cu_count();
+    if (ncu <= 0) return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
     const int64_t cap = (int64_t)ncu / 8 * 8;  // whole rounds of the 8 XCDs
     const int64_t grid = ntiles < cap ? ntiles : cap;
     const size_t smem_all = smem + (size_t)(3 * a.E + 1) * 4;  // + the per-expert table
     auto kern = gemm_dma2g_kernel<MODE, TM, TN, WN>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem_all) != hipSuccess)
-        return fail(OSC_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", smem);
+    {
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem_all, lds_done, lds_reserved)) return rc;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem_all, st, a, (int)ntiles);
     return check_launch("gemm_dma2g_kernel");
 }
@@ -1902,16 +1886,15 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     const int64_t skinny_wgs = ((p.N + 31) / 32) * ((p.M + 31) / 32);
     const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 1024);
     if (skinny_ok) kind = 3;
-    if (const char* ov = getenv("OSC_GEMM_TILE")) {  // tuning aid: "<tile rows / 64>,<kernel>"
-        int k2 = kind;
-        if (sscanf(ov, "%d,%d", &tm, &k2) == 2) {
-            if (tm != 1 && tm != 2 && tm != 4) tm = 2;
-            if (k2 < 0 || k2 > 3) k2 = kind;
-            if ((k2 == 1 || k2 == 2) && !lines) k2 = 0;
-            if (k2 == 2 && tm == 1) k2 = 1;
-            if (k2 == 2 && !pipe_ok) k2 = 1;
-            if (k2 == 3 && !skinny_ok) k2 = 0;
-        }
+    if (const int t_tile = tuning(TUNE_GEMM_TILE), t_kern = tuning(TUNE_GEMM_KERNEL); t_tile >= 0 || t_kern >= 0) {
+        // test and tuning overrides (osc_tuning.h); a kernel that cannot serve the shape is not forced
+        if (t_tile >= 0) tm = (t_tile == 1 || t_tile == 2 || t_tile == 4) ? t_tile : 2;
+        int k2 = (t_kern >= 0 && t_kern <= 3) ? t_kern : kind;
+        if (t_tile >= 0 && t_kern < 0 && k2 == 3) k2 = lines ? 1 : 0;  // a forced tile means a tiled kernel
+        if ((k2 == 1 || k2 == 2) && !lines) k2 = 0;
+        if (k2 == 2 && tm == 1) k2 = 1;
+        if (k2 == 2 && !pipe_ok) k2 = 1;
+        if (k2 == 3 && !skinny_ok) k2 = 0;
         kind = k2;
     }
     if (kind == 3) return launch_skinny<MODE>(a, st);
@@ -1939,9 +1922,9 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         a.grp_mode = 1;
         int rc;
         if constexpr (MODE != MODE_DUAL) {
-            // 8-bit modes: persistent workgroups (OSC_GROUPED_ONE_TILE=1, a tuning aid, keeps one tile each)
+            // 8-bit modes: persistent workgroups (the OSC_TUNE_GROUPED_ONE_TILE override keeps one tile each)
             const bool persistent = p.E >= 1 && p.E <= 1024 && !p.row_map && rowbytes / 128 >= 2 &&
-                                    !getenv("OSC_GROUPED_ONE_TILE");
+                                    tuning(TUNE_GROUPED_ONE_TILE) != 1;
             rc = persistent ? launch_dma2g<MODE, 4, 2, 4>(a, p.M, st) : launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
         } else {
             rc = launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);

@@ -11,6 +11,16 @@ namespace osc {
 int fail(int code, const char* fmt, ...);  // records the thread-local message, returns code
 int check_launch(const char* what);        // hipGetLastError -> OSC_OK / OSC_ERR_HIP
 
+// Kernel-choice overrides (osc_tuning.h): process-wide, -1 = automatic.  Read with relaxed loads.
+enum { TUNE_GEMM_TILE = 0, TUNE_GEMM_KERNEL = 1, TUNE_GROUPED_ONE_TILE = 2, TUNE_SWIGLU_TABLE = 3, TUNE_COUNT = 4 };
+int tuning(int knob);
+// number of compute units of the current device (cached per device); <= 0 on error
+int cu_count();
+// hipFuncAttributeMaxDynamicSharedMemorySize, issued once per (kernel, device); `done` is the
+// caller's per-kernel flag array, one entry per device
+constexpr int MAX_DEVICES = 64;
+int reserve_lds(const void* kernel, size_t bytes, unsigned char (&done)[MAX_DEVICES], size_t (&reserved)[MAX_DEVICES]);
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -78,8 +88,6 @@ int launch_profile_hist(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, in
                         uint32_t* hist, hipStream_t st);
 int launch_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, int16_t* table,
                          uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar, hipStream_t st);
-
-int launch_probe_mfma_fp4(int workgroups, int iters, float* out, hipStream_t st);
 
 struct GemmProblem {
     // activations

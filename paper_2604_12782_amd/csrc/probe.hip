@@ -2,15 +2,17 @@
 // GEMM uses (v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 operands), with nothing else in the loop.
 // Sustained clocks sit below the published peak and fall further with the switching activity of
 // the operands, so the probe runs on pseudo-random register contents.
-#include "osc_internal.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace osc {
+#include "../../include/osc_probe.h"
+
+namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int PROBE_THREADS = 512;  // eight wavefronts: two per SIMD, as in the GEMM
-constexpr int PROBE_TILES = 8;      // independent accumulators per wavefront (4 x 2 operand fragments)
 
 __global__ void __launch_bounds__(PROBE_THREADS) probe_mfma_fp4_kernel(int iters, uint32_t seed, float* out) {
     uint32_t x = seed ^ (blockIdx.x * 2654435761u) ^ (threadIdx.x * 40503u);
@@ -39,9 +41,14 @@ __global__ void __launch_bounds__(PROBE_THREADS) probe_mfma_fp4_kernel(int iters
     if (s == 12345.678f) out[0] = s;  // never true in practice; keeps the accumulators alive
 }
 
-int launch_probe_mfma_fp4(int workgroups, int iters, float* out, hipStream_t st) {
-    hipLaunchKernelGGL(probe_mfma_fp4_kernel, dim3(workgroups), dim3(PROBE_THREADS), 0, st, iters, 12345u, out);
-    return check_launch("probe_mfma_fp4_kernel");
-}
+}  // namespace
 
-}  // namespace osc
+extern "C" int osc_probe_mfma_fp4(int32_t workgroups, int32_t iters, float* out, double* flops, void* stream) {
+    if (workgroups <= 0 || iters <= 0) return -2;
+    if (!out || !flops) return -1;
+    // 8 wavefronts x 8 MFMAs of 32x32x64 per iteration (4 x 2 operand fragments), 2 flops per multiply-add
+    *flops = (double)workgroups * 8.0 * 8.0 * (double)iters * 2.0 * 32.0 * 32.0 * 64.0;
+    hipLaunchKernelGGL(probe_mfma_fp4_kernel, dim3(workgroups), dim3(PROBE_THREADS), 0,
+                       reinterpret_cast<hipStream_t>(stream), iters, 12345u, out);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}

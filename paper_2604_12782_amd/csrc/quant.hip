@@ -179,9 +179,11 @@ int launch_quant_mxfp4(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, con
         return fail(OSC_ERR_UNSUPPORTED, "quantize: K=%lld with K_o=%d needs %zu bytes of LDS", (long long)K, (int)K_o, smem);
     auto kern = group == 64 ? quant_mxfp4_osc_kernel<64> : quant_mxfp4_osc_kernel<32>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return fail(OSC_ERR_HIP, "quantize: LDS attribute: %s", hipGetErrorString(e));
+        // one flag set per kernel instantiation (scale groups of 32 and of 64)
+        static unsigned char lds_done[2][MAX_DEVICES];
+        static size_t lds_reserved[2][MAX_DEVICES];
+        const int which = group == 64;
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done[which], lds_reserved[which])) return rc;
     }
     // 32-row blocks of 8*nseg workgroups each, dealt to XCDs in groups of eight blocks
     const int64_t blocks = (M + 31) / 32;

@@ -21,20 +21,43 @@ def lib():
     return osc.lib()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "osc.h")).read()
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(osc_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported_and_bound(lib):
-    names = declared_symbols()
+    headers = sorted(h for h in os.listdir(os.path.join(ROOT, "include")) if h.endswith(".h"))
+    assert headers == ["osc.h", "osc_probe.h", "osc_tuning.h"]
+    names = declared_symbols("osc.h") + declared_symbols("osc_tuning.h")
     assert {"osc_quantize_act", "osc_dual_gemm", "osc_fp8_gemm", "osc_grouped_dual_gemm"} <= set(names)
     for n in names:
-        assert hasattr(lib, n), f"{n} declared in osc.h but not exported"
+        assert hasattr(lib, n), f"{n} declared but not exported"
         assert n in binding._SIGS, f"{n} has no ctypes signature"
         assert hasattr(osc, n), f"{n} has no Python binding of the same name"
     assert osc.osc_version() >= 100
+    # the matrix-core yardstick lives in a library of its own that only the benchmark loads
+    from paper_2604_12782_amd import probe
+    for n in declared_symbols("osc_probe.h"):
+        assert hasattr(probe.lib(), n) and hasattr(probe, n), n
+        assert not hasattr(osc, n), f"{n} belongs to the probe library, not to the product"
+
+
+def test_tuning_knobs_host(lib):
+    for k in range(4):
+        assert osc.osc_tuning_get(k) == -1
+        osc.osc_tuning_set(k, 1)
+        assert osc.osc_tuning_get(k) == 1
+        osc.osc_tuning_set(k, -5)
+        assert osc.osc_tuning_get(k) == -1
+    assert lib.osc_tuning_set(99, 1) == -4 and lib.osc_tuning_get(99) == -1
+
+
+def test_no_entry_point_reads_the_environment():
+    for f in os.listdir(os.path.join(ROOT, "paper_2604_12782_amd", "csrc")):
+        if f.endswith((".hip", ".h")):
+            assert "getenv" not in open(os.path.join(ROOT, "paper_2604_12782_amd", "csrc", f)).read(), f
 
 
 def test_table_to_index_g_host(lib):
@@ -111,7 +134,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert m8(FAKE, FAKE, FAKE, 4, 64, 96, None, 0, FAKE, 0, 64, None) == -4  # K % 128
     assert m8(FAKE, None, FAKE, 4, 64, 128, None, 0, FAKE, 0, 64, None) == -1
     assert q(FAKE, 4, 48, 48, None, 0, 2, FAKE, FAKE, None, 0, None) == -2  # MXFP8 quantiser, K % 32
-    pr = lib.osc_probe_mfma_fp4
+    from paper_2604_12782_amd import probe
+    pr = probe.lib().osc_probe_mfma_fp4
     fl = C.c_double(0.0)
     assert pr(0, 4, FAKE, C.addressof(fl), None) == -2 and pr(4, 4, None, C.addressof(fl), None) == -1
     fq = lib.osc_rmsnorm_quantize_act

@@ -96,12 +96,12 @@ def check_swiglu(osc, G, U, strided=False):
     assert torch.equal(osc.osc_unpack_act_scales(Us, M, K), osc.osc_unpack_act_scales(Xs, M, K))
 
 
-# OSC_SWIGLU_TABLE: "0" = silu evaluated per element, "1" = looked up in the 128 KB table in LDS (the
+# OSC_TUNE_SWIGLU_TABLE: "0" = silu evaluated per element, "1" = looked up in the 128 KB table in LDS (the
 # launcher's own choice depends on the size); both must give the oracle's bits
 @pytest.mark.parametrize("table", ["0", "1"])
 @pytest.mark.parametrize("M,K", [(1, 32), (7, 96), (40, 1056), (130, 4096), (9, 12288)])
-def test_swiglu_fused_matches_oracle(osc, monkeypatch, table, M, K):
-    monkeypatch.setenv("OSC_SWIGLU_TABLE", table)
+def test_swiglu_fused_matches_oracle(osc, tuning, table, M, K):
+    tuning.swiglu_table(table)
     gen = wl.rng(1300 + M)
     G = to_bf16_bits((gen.standard_normal((M, K)) * 3).astype(np.float32))
     U = wl.activations_diffuse(1400 + M, M, K, p=0.01)
@@ -110,10 +110,10 @@ def test_swiglu_fused_matches_oracle(osc, monkeypatch, table, M, K):
 
 
 @pytest.mark.parametrize("table", ["0", "1"])
-def test_swiglu_every_gate_value(osc, monkeypatch, table):
+def test_swiglu_every_gate_value(osc, tuning, table):
     """every bf16 bit pattern below 2^100 in magnitude as a gate (58 000 of them; above that the
     product with up leaves the bf16 range), against the oracle, bit for bit"""
-    monkeypatch.setenv("OSC_SWIGLU_TABLE", table)
+    tuning.swiglu_table(table)
     bits = np.arange(0x10000, dtype=np.uint32).astype(np.uint16)
     bits = bits[((bits >> 7) & 0xFF) < 227]
     K = 2048
@@ -146,8 +146,8 @@ def check_swiglu_fp8(osc, G, U, strided=False):
 
 @pytest.mark.parametrize("table", ["0", "1"])
 @pytest.mark.parametrize("M,K", [(1, 8), (7, 96), (40, 1056), (130, 4096), (9, 12288), (3, 16384), (5, 2056)])
-def test_swiglu_fp8_fused_matches_oracle(osc, monkeypatch, table, M, K):
-    monkeypatch.setenv("OSC_SWIGLU_TABLE", table)
+def test_swiglu_fp8_fused_matches_oracle(osc, tuning, table, M, K):
+    tuning.swiglu_table(table)
     gen = wl.rng(1600 + M)
     G = to_bf16_bits((gen.standard_normal((M, K)) * 3).astype(np.float32))
     U = wl.activations_diffuse(1700 + M, M, K, p=0.01)
@@ -159,8 +159,8 @@ def test_swiglu_fp8_fused_matches_oracle(osc, monkeypatch, table, M, K):
 
 
 @pytest.mark.parametrize("table", ["0", "1"])
-def test_swiglu_fp8_every_gate_value(osc, monkeypatch, table):
-    monkeypatch.setenv("OSC_SWIGLU_TABLE", table)
+def test_swiglu_fp8_every_gate_value(osc, tuning, table):
+    tuning.swiglu_table(table)
     bits = np.arange(0x10000, dtype=np.uint32).astype(np.uint16)
     bits = bits[((bits >> 7) & 0xFF) < 227]
     K = 2048

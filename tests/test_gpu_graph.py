@@ -68,10 +68,10 @@ def test_step_replays_equal_eager(osc, M):
         torch.cuda.synchronize()
 
 
-def test_swiglu_fusions_with_table_replay_equal_eager(osc, monkeypatch):
+def test_swiglu_fusions_with_table_replay_equal_eager(osc, tuning):
     """The SwiGLU fusions on their table path (two kernels per call: the silu table, then the
     quantiser that copies it into LDS) under capture; replays on changing inputs equal eager runs."""
-    monkeypatch.setenv("OSC_SWIGLU_TABLE", "1")
+    tuning.swiglu_table("1")
     M, K = 300, 1536
     dev = torch.device("cuda:0")
     gen = wl.rng(4100)
@@ -106,7 +106,7 @@ def test_swiglu_fusions_with_table_replay_equal_eager(osc, monkeypatch):
         torch.cuda.synchronize()
         r = refs[i & 1]
         assert torch.equal(m8[0], r[0]) and torch.equal(m8[1], r[1]) and torch.equal(f8[0], r[2]) and torch.equal(f8[1], r[3]), f"replay {i}"
-        monkeypatch.setenv("OSC_SWIGLU_TABLE", "0")  # eager work on the other path in between
+        tuning.swiglu_table("0")  # eager work on the other path in between
         osc.osc_swiglu_quantize_act(GU[:, :K], GU[:, K:])
-        monkeypatch.setenv("OSC_SWIGLU_TABLE", "1")
+        tuning.swiglu_table("1")
         torch.cuda.synchronize()

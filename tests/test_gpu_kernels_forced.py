@@ -1,5 +1,5 @@
-"""Every GEMM kernel template on shapes it would not be chosen for: the launcher's tuning variable
-forces the tile size and the kernel, the results must still meet the GEMM tolerance.  Also outputs
+"""Every GEMM kernel template on shapes it would not be chosen for: the launcher's tuning knobs
+(include/osc_tuning.h) force the tile size and the kernel, the results must still meet the GEMM tolerance.  Also outputs
 written into wider buffers (ldy > N) and through the unaligned bf16 store path."""
 import numpy as np
 import pytest
@@ -37,8 +37,8 @@ FORCED = ["4,1", "2,1", "1,1", "1,0", "2,0", "4,2", "2,2"]
 
 @pytest.mark.parametrize("cfg", FORCED)
 @pytest.mark.parametrize("M,N,K,r", [(300, 200, 1024, 2), (513, 520, 512, 1), (256, 512, 768, 0), (70, 1000, 256, 4)])
-def test_dual_forced(osc, monkeypatch, cfg, M, N, K, r):
-    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+def test_dual_forced(osc, tuning, cfg, M, N, K, r):
+    tuning.gemm(cfg)
     X, table = wl.activations_persistent(7000 + M, M, K, r)
     W = wl.weights(7100 + N, N, K)
     oidx = oracle.table_to_index(table) if r else np.zeros(0, np.int32)
@@ -54,8 +54,8 @@ def test_dual_forced(osc, monkeypatch, cfg, M, N, K, r):
 
 
 @pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1", "1,0", "2,0"])
-def test_fp8_and_mxfp8_forced(osc, monkeypatch, cfg):
-    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+def test_fp8_and_mxfp8_forced(osc, tuning, cfg):
+    tuning.gemm(cfg)
     M, N, K = 300, 264, 768
     X = wl.activations_diffuse(7200, M, K)
     W = wl.weights(7201, N, K)
@@ -72,9 +72,9 @@ def test_fp8_and_mxfp8_forced(osc, monkeypatch, cfg):
 
 
 @pytest.mark.parametrize("cfg", [None, "4,1", "1,1", "1,0"])
-def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
+def test_output_into_wider_and_odd_buffers(osc, tuning, cfg):
     if cfg:
-        monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+        tuning.gemm(cfg)
     M, N, K = 200, 320, 512
     X, table = wl.activations_persistent(7300, M, K, 2)
     W = wl.weights(7301, N, K)
@@ -97,11 +97,11 @@ def test_output_into_wider_and_odd_buffers(osc, monkeypatch, cfg):
 
 
 @pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1"])
-def test_grouped_with_skewed_experts(osc, monkeypatch, cfg):
+def test_grouped_with_skewed_experts(osc, tuning, cfg):
     """Experts of 0, 1, 63 ... 700 rows, sizes on both sides of every tile border, through the
     256-row tiles with their 64-row remainder pass (4,1) and the smaller tiles: dual path with a row
     map, per-token FP8 and MXFP8."""
-    monkeypatch.setenv("OSC_GEMM_TILE", cfg)
+    tuning.gemm(cfg)
     sizes = [0, 1, 63, 64, 65, 127, 128, 129, 255, 256, 257, 383, 384, 385, 700, 0, 130]
     E = len(sizes)
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)

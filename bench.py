@@ -145,6 +145,7 @@ def main():
 
     import torch
     import paper_2604_12782_amd as osc
+    from paper_2604_12782_amd import probe as osc_probe
     import workloads as wl
     osc.lib()
     assert torch.cuda.is_available(), "bench.py needs the GPU"

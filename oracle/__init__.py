@@ -15,14 +15,20 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "osc_ref.c")
-_LIB = os.path.join(_HERE, "liboscref.so")
+# OSC_ORACLE_SANITIZE=1 (set by tests/test_oracle_sanitized.py for a child process that preloads the
+# sanitizer runtimes) selects a second build of the same source with address and undefined-behaviour
+# checks compiled in
+_SANITIZE = os.environ.get("OSC_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "liboscref_san.so" if _SANITIZE else "liboscref.so")
 
 
 def build(force=False):
     """Compile osc_ref.c with gcc (plain C, OpenMP over rows)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        flags = (["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                  "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"])
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", _SRC, "-lm",
+            ["gcc", *flags, "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", _SRC, "-lm",
              "-o", _LIB])
     return _LIB
 
@@ -163,6 +169,29 @@ def swiglu(G, U):
     Y = np.empty((M, K), np.uint16)
     lib().ref_swiglu.argtypes = [C.c_void_p, C.c_void_p, i64, i64, i64, i64, C.c_void_p]
     _check(lib().ref_swiglu(_p(G), _p(U), M, K, K, K, _p(Y)), "ref_swiglu")
+    return Y
+
+
+def rmsnorm_plain(X, gamma, eps=1e-6, mid_round=False):
+    """Textbook RMSNorm in double precision, one rounding to bf16 at the end; mid_round also rounds
+    the normalised value to bf16 before the product with gamma (see ref_rmsnorm_plain)."""
+    X, gamma = _c(X, np.uint16), _c(gamma, np.uint16)
+    M, K = X.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().ref_rmsnorm_plain.argtypes = [C.c_void_p, C.c_void_p, C.c_double, i64, i64, i64, C.c_int, C.c_void_p]
+    _check(lib().ref_rmsnorm_plain(_p(X), _p(gamma), float(np.float32(eps)), M, K, K, int(mid_round), _p(Y)),
+           "ref_rmsnorm_plain")
+    return Y
+
+
+def swiglu_plain(G, U, mid_round=False):
+    """Textbook silu(G) * U in double precision, one rounding to bf16 at the end; mid_round also
+    rounds silu(G) to bf16 before the product."""
+    G, U = _c(G, np.uint16), _c(U, np.uint16)
+    M, K = G.shape
+    Y = np.empty((M, K), np.uint16)
+    lib().ref_swiglu_plain.argtypes = [C.c_void_p, C.c_void_p, i64, i64, i64, i64, C.c_int, C.c_void_p]
+    _check(lib().ref_swiglu_plain(_p(G), _p(U), M, K, K, K, int(mid_round), _p(Y)), "ref_swiglu_plain")
     return Y
 
 

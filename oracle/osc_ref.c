@@ -28,6 +28,9 @@
  *                           Section 2.1), y = silu(gate) * up, as a fixed sequence of
  *                           correctly rounded single-precision operations, so that a producer
  *                           fused with the 8-bit quantiser can be compared bit for bit
+ *   ref_rmsnorm_plain, ref_swiglu_plain  the same two producers in plain double precision with a
+ *                           single final rounding: the pin that ties the two recipes above (and the
+ *                           kernels that reproduce them) to RMSNorm and SwiGLU themselves
  *   ref_gather_wl           W_L: rows of the high-precision weight named by
  *                           the same table (Section 3.3.1, second bullet)
  *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
@@ -66,6 +69,7 @@
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -shared -fPIC osc_ref.c -lm
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
@@ -157,6 +161,7 @@ int ref_e4m3_encode(float vf) {
     int sign = signbit(v) ? 0x80 : 0;
     double a = fabs(v);
     if (a == 0.0) return sign;
+    if (!(a <= DBL_MAX)) return sign | 0x7F; /* not finite: outside the contract (callers report an error) */
     int ex;
     (void)frexp(a, &ex);
     int p = ex - 1; /* floor(log2 a) */
@@ -360,6 +365,66 @@ int ref_swiglu(const uint16_t *Gt, const uint16_t *U, int64_t M, int64_t K, int6
             Y[m * K + j] = float_to_bf16_rne(t * bf16_to_float(u));
         }
     return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+/* The textbook forms of the two producers, written without any of the devices above: every
+ * quantity in double precision (the sum of squares in plain double accumulation, sqrt and exp from
+ * libm) and ONE rounding to bf16 at the very end, or, with mid_round, the two roundings that a model
+ * made of bf16 modules performs (after the normalisation / after silu, then after the product).
+ * They do not define the fused kernels' bits (the
+ * recipes above do, and those were shaped so that a kernel can reproduce them exactly); they pin
+ * the recipes, and through them the kernels, to RMSNorm and SwiGLU themselves: results may differ
+ * from ref_rmsnorm / ref_swiglu by at most one bf16 step, and rarely do. */
+static uint16_t double_to_bf16_rne(double v) {
+    /* nearest bf16 of a finite double (ties to even), through the exact neighbours in float */
+    float f = (float)v;             /* 24 significant bits: may itself sit on a bf16 tie by rounding, */
+    uint32_t u;                     /* so decide by comparing v with the two bf16 neighbours exactly   */
+    memcpy(&u, &f, 4);
+    uint32_t lo = u & 0xFFFF0000u, hi = lo + 0x10000u;
+    float flo, fhi;
+    memcpy(&flo, &lo, 4);
+    memcpy(&fhi, &hi, 4);
+    double dlo = fabs(v - (double)flo), dhi = fabs((double)fhi - v);
+    if (dlo < dhi) return (uint16_t)(lo >> 16);
+    if (dhi < dlo) return (uint16_t)(hi >> 16);
+    return (uint16_t)(((lo >> 16) & 1u) ? (hi >> 16) : (lo >> 16));
+}
+
+/* mid_round = 1 also rounds the normalised value (the gated value) to bf16 before the last
+ * product, as a model whose modules exchange bf16 tensors does; 0 rounds once, at the end. */
+int ref_rmsnorm_plain(const uint16_t *X, const uint16_t *gamma, double eps, int64_t M, int64_t K, int64_t ldx,
+                      int mid_round, uint16_t *Y) {
+    if (M < 0 || K <= 0 || ldx < K || !X || !gamma || !Y) return REF_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        double ss = 0.0;
+        for (int64_t j = 0; j < K; ++j) {
+            double v = (double)bf16_to_float(x[j]);
+            ss += v * v;
+        }
+        double r = 1.0 / sqrt(ss / (double)K + eps);
+        for (int64_t j = 0; j < K; ++j) {
+            double t = (double)bf16_to_float(x[j]) * r;
+            if (mid_round) t = (double)bf16_to_float(double_to_bf16_rne(t));
+            Y[m * K + j] = double_to_bf16_rne(t * (double)bf16_to_float(gamma[j]));
+        }
+    }
+    return REF_OK;
+}
+
+int ref_swiglu_plain(const uint16_t *Gt, const uint16_t *U, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                     int mid_round, uint16_t *Y) {
+    if (M < 0 || K < 0 || ldg < K || ldu < K || (M && K && (!Gt || !U || !Y))) return REF_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < K; ++j) {
+            double g = (double)bf16_to_float(Gt[m * ldg + j]), u = (double)bf16_to_float(U[m * ldu + j]);
+            double t = g / (1.0 + exp(-g));
+            if (mid_round) t = (double)bf16_to_float(double_to_bf16_rne(t));
+            Y[m * K + j] = double_to_bf16_rne(t * u);
+        }
+    return REF_OK;
 }
 
 /* Dynamic protection (Section 4.2: per-group maximum value detection at run time).  For every

@@ -32,11 +32,13 @@ def host(t):
     return t.cpu().numpy()
 
 
-def check_close(Y_gpu, Y_ref, what="", bf16_out=False):
+def check_close(Y_gpu, Y_ref, what="", bf16_out=False, scale=None):
     """max|Y_gpu - Y_ref| <= 1e-3 * max|Y_ref| on the fp32 result.  A bf16 output adds its own
-    rounding: half a unit in the last place of 8 significant bits, at most 2^-8 of the value."""
+    rounding: half a unit in the last place of 8 significant bits, at most 2^-8 of the value.
+    `scale` stands in for max|Y_ref| when Y_ref is a small sample of a larger output (pass the
+    maximum over a bigger sample of the same output: never more than the true maximum)."""
     Y_gpu = np.asarray(Y_gpu, np.float64)
-    ref = np.abs(Y_ref).max()
+    ref = np.abs(Y_ref).max() if scale is None else float(scale)
     assert np.isfinite(Y_gpu).all(), what
     slack = TOL * ref + (2.0 ** -8 * np.abs(Y_ref) if bf16_out else 0.0)
     excess = np.abs(Y_gpu - Y_ref) - slack
@@ -367,3 +369,27 @@ def test_dual_gemm_long_k(osc):
     for M in (40, 200):
         X, table = wl.activations_persistent(910 + M, M, K, 1)
         run_dual(osc, X, W, oracle.table_to_index(table))
+
+
+def test_raw_scale_layout_against_the_header_formula(osc):
+    """The row-block-major E8M0 layout as include/osc.h states it, read from the raw bytes with
+    numpy indexing (no unpack kernel of the library involved): the scale of (row m, group g) is byte
+    ((m/32)*ceil(K/128) + g/4)*128 + (m%32)*4 + g%4; bytes of groups >= K/32 are zero."""
+    for M, K, r in ((70, 96, 1), (33, 4096, 2), (256, 160, 0), (5, 32, 1)):
+        X, table = wl.activations_persistent(8800 + M, M, K, r)
+        oidx = oracle.table_to_index(table) if r else np.zeros(0, np.int32)
+        Xq, Xs, B = osc.osc_quantize_act(dev(X), dev(oidx) if r else None)
+        raw = host(Xs)
+        assert raw.size == osc.osc_act_scale_bytes(M, K)
+        _, rs, _ = oracle.quantize_mxfp4_osc(X, oidx, ldb=0 if B is None else B.shape[1])
+        Kg, nb = K // 32, (K // 32 + 3) // 4
+        m, g = np.meshgrid(np.arange(M), np.arange(nb * 4), indexing="ij")
+        at = ((m // 32) * nb + g // 4) * 128 + (m % 32) * 4 + g % 4
+        got = raw[at]
+        assert np.array_equal(got[:, :Kg], rs), (M, K)
+        assert (got[:, Kg:] == 0).all(), "bytes of groups past K/32 must be zero"
+        # the same for the 8-bit micro-scaling quantiser
+        X8, X8s = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+        _, r8s = oracle.quantize_mxfp8(X)
+        got8 = host(X8s)[at]
+        assert np.array_equal(got8[:, :Kg], r8s) and (got8[:, Kg:] == 0).all(), (M, K, "mxfp8")

@@ -92,3 +92,27 @@ def test_nonfinite_rejected():
     except oracle.OracleError:
         return
     raise AssertionError("a non-finite input must be refused")
+
+
+def test_recipe_against_the_plain_double_precision_form():
+    """The order-free recipe (fixed-point sum of squares, single-precision products) against the
+    oracle's textbook RMSNorm: double accumulation, libm sqrt, roundings only where a model made of
+    bf16 modules has them.  The plain form is itself pinned to numpy float64 here, so a slip in
+    either shows."""
+    X = wl.activations_persistent(191, 256, 4096, 2, jitter=0.2)[0]
+    gamma = to_bf16_bits((1.0 + 0.2 * wl.rng(192).standard_normal(4096)).astype(np.float32))
+    eps = 1e-6
+    x, g = from_bf16_bits(X).astype(np.float64), from_bf16_bits(gamma).astype(np.float64)
+    ref = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + np.float64(np.float32(eps))) * g
+    plain1 = oracle.rmsnorm_plain(X, gamma, eps)
+    # a float64 value lands on a bf16 tie with probability ~2^-45: rounding through float32 is safe here
+    d = _ulp_distance(plain1, to_bf16_bits(ref.astype(np.float32)))
+    assert d.max() <= 1 and (d == 0).mean() > 0.9999
+    Y = oracle.rmsnorm(X, gamma, eps)
+    d1 = _ulp_distance(Y, plain1)                                   # one rounding against two
+    assert d1.max() <= 1
+    d2 = _ulp_distance(Y, oracle.rmsnorm_plain(X, gamma, eps, mid_round=True))   # same roundings, plain arithmetic
+    assert d2.max() <= 2 and (d2 == 0).mean() >= 0.999
+    ones = to_bf16_bits(np.ones(4096, np.float32))
+    d3 = _ulp_distance(oracle.rmsnorm(X, ones, eps), oracle.rmsnorm_plain(X, ones, eps))
+    assert d3.max() <= 1 and (d3 == 0).mean() >= 0.999

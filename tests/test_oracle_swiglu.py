@@ -79,3 +79,23 @@ def test_identities_and_edges():
     except oracle.OracleError:
         return
     raise AssertionError("a non-finite input must be refused")
+
+
+def test_recipe_against_the_plain_double_precision_form():
+    """The fixed single-precision silu recipe against the oracle's textbook SwiGLU (libm exp in
+    double, roundings only where a model made of bf16 modules has them); the plain form is pinned to
+    numpy float64 here."""
+    gen = wl.rng(195)
+    G = to_bf16_bits((gen.standard_normal((128, 4096)) * 2.5).astype(np.float32))
+    U = wl.activations_diffuse(196, 128, 4096, p=0.01)
+    g64, u64 = from_bf16_bits(G).astype(np.float64), from_bf16_bits(U).astype(np.float64)
+    plain1 = oracle.swiglu_plain(G, U)
+    d = _steps(plain1, _bf16(g64 / (1.0 + np.exp(-g64)) * u64))
+    assert d.max() <= 1 and (d == 0).mean() > 0.9999
+    Y = oracle.swiglu(G, U)
+    assert _steps(Y, plain1).max() <= 1                              # one rounding against two
+    d2 = _steps(Y, oracle.swiglu_plain(G, U, mid_round=True))        # same roundings, plain arithmetic
+    assert d2.max() <= 1 and (d2 == 0).mean() >= 0.999
+    ones = to_bf16_bits(np.ones_like(g64, dtype=np.float32))
+    d3 = _steps(oracle.swiglu(G, ones), oracle.swiglu_plain(G, ones))
+    assert d3.max() <= 1 and (d3 == 0).mean() >= 0.999

@@ -40,7 +40,7 @@ enum {
     OSC_ERR_SHAPE = -2,       /* negative extent, K % 32 != 0, leading dimension < extent */
     OSC_ERR_TABLE = -3,       /* table entry outside [-1, G) or repeated inside a group */
     OSC_ERR_UNSUPPORTED = -4, /* unknown enum value, misaligned pointer or stride */
-    OSC_ERR_WORKSPACE = -5,   /* reserved */
+    OSC_ERR_WORKSPACE = -5,   /* a caller-provided workspace is too small */
     OSC_ERR_HIP = -6          /* the HIP runtime refused a launch */
 };
 
@@ -371,6 +371,23 @@ int osc_profile_hist(const void *X, int64_t S, int64_t H, int64_t ldx, int32_t G
 int osc_profile_table(const uint32_t *hist, int32_t Kg, int32_t G, int32_t R, int16_t *table,
                       uint32_t *n_total, uint32_t *n_hit, float *density, float *cbar,
                       void *stream);
+
+/*
+ * Alg. 1 for one activation interface in one call: Eq. 1's threshold over X, the candidate counts
+ * of Eq. 2-3, and the table, densities and mean density of Eq. 4, i.e. osc_profile_abs_sum,
+ * osc_profile_threshold, osc_profile_hist and osc_profile_table in sequence on one calibration
+ * piece X[S, H] (S > 0, H > 0).  The intermediate results live in `workspace`.
+ *   T_out            float (device) or NULL: receives the threshold that was used
+ *   workspace        device memory, 256-byte aligned, osc_profile_workspace_bytes(H) bytes
+ *                    (= 256 + 4*H); cleared by the call itself, contents afterwards unspecified
+ *   everything else as in the four calls above (table int16 [H/G, R], ...).
+ * Errors: those of the four calls; OSC_ERR_WORKSPACE when workspace_bytes is too small.
+ */
+size_t osc_profile_workspace_bytes(int64_t H);
+int osc_profile_calibrate(const void *X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha,
+                          int32_t R, int16_t *table, uint32_t *n_total, uint32_t *n_hit,
+                          float *density, float *cbar, float *T_out, void *workspace,
+                          size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -48,6 +48,8 @@ _SIGS = {
     "osc_profile_threshold": (C.c_int, [vp, i64, C.c_float, vp, vp]),
     "osc_profile_hist": (C.c_int, [vp, i64, i64, i64, i32, vp, vp, vp]),
     "osc_profile_table": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+    "osc_profile_workspace_bytes": (sz, [i64]),
+    "osc_profile_calibrate": (C.c_int, [vp, i64, i64, i64, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
     "osc_grouped_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, vp, i32, i64, vp, i64, i64, i32, vp,
                                         C.c_int, i64, vp]),
 }
@@ -331,6 +333,32 @@ def osc_profile_table(hist, R=1):
     _check(lib().osc_profile_table(_ptr(hist), Kg, G, R, _ptr(table), _ptr(n_total), _ptr(n_hit), _ptr(density),
                                    _ptr(cbar), _stream()))
     return table, n_total, n_hit, density, cbar
+
+
+def osc_profile_workspace_bytes(H):
+    return lib().osc_profile_workspace_bytes(H)
+
+
+def _calibrate_outputs(H, G, R, dev, out):
+    if out is not None:
+        return out
+    Kg = H // G
+    return (torch.empty((Kg, R), dtype=torch.int16, device=dev), torch.empty(Kg, dtype=torch.int32, device=dev),
+            torch.empty(Kg, dtype=torch.int32, device=dev), torch.empty(Kg, dtype=torch.float32, device=dev),
+            torch.empty(1, dtype=torch.float32, device=dev), torch.empty(1, dtype=torch.float32, device=dev))
+
+
+def osc_profile_calibrate(X, G=32, alpha=5.0, R=1, workspace=None, out=None):
+    """Alg. 1 in one call -> (table, n_total, n_hit, density, cbar, T).  `workspace`: uint8 device
+    tensor of osc_profile_workspace_bytes(H) bytes (allocated here when not given)."""
+    X = _rows16(X)
+    S, H = X.shape
+    if workspace is None:
+        workspace = torch.empty(osc_profile_workspace_bytes(H), dtype=torch.uint8, device=X.device)
+    o = _calibrate_outputs(H, G, R, X.device, out)
+    _check(lib().osc_profile_calibrate(_ptr(X), S, H, X.stride(0), G, alpha, R, *[_ptr(t) for t in o], _ptr(workspace),
+                                       workspace.numel(), _stream()))
+    return o
 
 
 def osc_quantize_act_dynamic(X, ldb=None, want_idx=True, out=None):

@@ -520,4 +520,31 @@ int osc_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, in
     return launch_profile_table(hist, Kg, G, R, table, n_total, n_hit, density, cbar, as_stream(stream));
 }
 
+size_t osc_profile_workspace_bytes(int64_t H) { return H < 0 ? 0 : profile_scratch_bytes(H); }
+
+static int check_calibrate(const char* who, const void* X, int64_t S, int64_t H, int64_t ldx, int32_t G, int32_t R,
+                           const int16_t* table) {
+    int rc = check_profile_x(who, X, S, H, ldx);
+    if (rc) return rc;
+    REQUIRE(G == 16 || G == 32 || G == 64, OSC_ERR_UNSUPPORTED, "%s: group size %d (16, 32 or 64)", who, G);
+    REQUIRE(H % G == 0, OSC_ERR_SHAPE, "%s: H=%lld is not a multiple of G=%d", who, (long long)H, G);
+    REQUIRE(S > 0 && H > 0, OSC_ERR_SHAPE, "%s: empty calibration piece (S=%lld, H=%lld)", who, (long long)S, (long long)H);
+    REQUIRE(R >= 0, OSC_ERR_SHAPE, "%s: R=%d", who, R);
+    REQUIRE(R == 0 || table, OSC_ERR_NULL, "%s: null table", who);
+    return OSC_OK;
+}
+
+int osc_profile_calibrate(const void* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha, int32_t R,
+                          int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
+                          float* T_out, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_calibrate("osc_profile_calibrate", X, S, H, ldx, G, R, table);
+    if (rc) return rc;
+    REQUIRE(workspace, OSC_ERR_NULL, "osc_profile_calibrate: null workspace");
+    REQUIRE(aligned(workspace, 256), OSC_ERR_UNSUPPORTED, "osc_profile_calibrate: workspace must be 256-byte aligned");
+    REQUIRE(workspace_bytes >= profile_scratch_bytes(H), OSC_ERR_WORKSPACE,
+            "osc_profile_calibrate: workspace of %zu bytes, %zu needed", workspace_bytes, profile_scratch_bytes(H));
+    return launch_profile_calibrate(static_cast<const uint16_t*>(X), S, H, ldx, G, alpha, R, table, n_total, n_hit,
+                                    density, cbar, T_out, static_cast<uint8_t*>(workspace), as_stream(stream));
+}
+
 }  // extern "C"

@@ -89,6 +89,11 @@ int launch_profile_hist(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, in
 int launch_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, int16_t* table,
                          uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar, hipStream_t st);
 
+size_t profile_scratch_bytes(int64_t H);
+int launch_profile_calibrate(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha, int32_t R,
+                             int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
+                             float* T_out, uint8_t* scratch, hipStream_t st);
+
 struct GemmProblem {
     // activations
     const uint8_t* Xq;   // dual: codes [*, K/2]; fp8, mxfp8: codes [*, K]

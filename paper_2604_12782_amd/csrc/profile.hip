@@ -301,4 +301,38 @@ int launch_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R,
     return check_launch("profile_cbar_kernel");
 }
 
+// ---- Alg. 1 in one call: threshold, candidate counts, table -------------------------------------
+// Scratch layout (caller's workspace): double abs_sum at 0, float T at 8, uint32 hist[H] at 256.
+__global__ void profile_clear_kernel(uint32_t* words, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        words[i] = 0u;
+}
+__global__ void profile_copy_float_kernel(const float* src, float* dst) { *dst = *src; }
+
+size_t profile_scratch_bytes(int64_t H) { return 256 + (size_t)H * 4; }
+
+int launch_profile_calibrate(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha, int32_t R,
+                             int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
+                             float* T_out, uint8_t* scratch, hipStream_t st) {
+    double* abs_sum = reinterpret_cast<double*>(scratch);
+    float* T = reinterpret_cast<float*>(scratch + 8);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(scratch + 256);
+    // a fill kernel, not a memset: callers may record this call into a graph
+    const int64_t words = (int64_t)(profile_scratch_bytes(H) / 4);
+    const int64_t wgs = (words + 255) / 256;
+    hipLaunchKernelGGL(profile_clear_kernel, dim3((unsigned)(wgs < 1024 ? wgs : 1024)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(scratch), words);
+    int rc = check_launch("profile_clear_kernel");
+    if (rc) return rc;
+    if ((rc = launch_profile_abs_sum(X, S, H, ldx, abs_sum, st))) return rc;
+    if ((rc = launch_profile_threshold(abs_sum, S * H, alpha, T, st))) return rc;
+    if ((rc = launch_profile_hist(X, S, H, ldx, G, T, hist, st))) return rc;
+    if ((rc = launch_profile_table(hist, (int32_t)(H / G), G, R, table, n_total, n_hit, density, cbar, st))) return rc;
+    if (T_out) {
+        hipLaunchKernelGGL(profile_copy_float_kernel, dim3(1), dim3(1), 0, st, T, T_out);
+        rc = check_launch("profile_copy_float_kernel");
+    }
+    return rc;
+}
+
 }  // namespace osc

@@ -198,3 +198,20 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_profile_calibrate_arguments(lib):
+    f = lib.osc_profile_calibrate
+    ok = (FAKE, 8, 64, 64, 32, 5.0, 1, FAKE, None, None, None, None, None, FAKE, 256 + 4 * 64, None)
+
+    def call(**kw):
+        names = ["X", "S", "H", "ldx", "G", "alpha", "R", "table", "n_total", "n_hit", "density", "cbar", "T", "ws", "wsb", "st"]
+        a = dict(zip(names, ok))
+        a.update(kw)
+        return f(*[a[n] for n in names])
+    assert lib.osc_profile_workspace_bytes(64) == 256 + 4 * 64 and lib.osc_profile_workspace_bytes(-1) == 0
+    assert call(wsb=256 + 4 * 64 - 1) == -5                 # workspace too small
+    assert call(ws=None) == -1 and call(table=None) == -1 and call(X=None) == -1
+    assert call(ws=FAKE + 64) == -4                          # workspace alignment
+    assert call(G=48) == -4 and call(H=72, ldx=72) == -2     # group size; H % G
+    assert call(S=0) == -2 and call(R=-1) == -2 and call(ldx=32) == -2

@@ -145,3 +145,24 @@ def test_planted_table_end_to_end(osc):
     Xq, Xs, B = osc.osc_quantize_act(Xd, dev(oidx), osc.OSC_FMT_MXFP4_OSC)
     rq, rs, rb = oracle.quantize_mxfp4_osc(X, oidx, ldb=B.shape[1])
     assert np.array_equal(Xq.cpu().numpy(), rq) and np.array_equal(B.cpu().numpy().view(np.uint16), rb)
+
+
+@pytest.mark.parametrize("S,H,G,R", [(1536, 4096, 32, 2), (300, 1088, 16, 1), (77, 2112, 64, 3), (5, 64, 32, 1)])
+def test_calibrate_in_one_call(osc, S, H, G, R):
+    """Alg. 1 through the single entry point (threshold, counts, table, densities with the
+    intermediate results in a caller's workspace) against the oracle's three steps."""
+    X, _ = wl.activations_persistent(9300 + S, S, H, 2, jitter=0.3) if G == 32 else (wl.activations_diffuse(9300 + S, S, H, p=0.02), None)
+    ref_T = oracle.profile_threshold(X, 5.0)
+    ws = torch.full((osc.osc_profile_workspace_bytes(H) + 512,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = ws[:osc.osc_profile_workspace_bytes(H)]  # stale contents: the call clears what it needs
+    table, n_total, n_hit, density, cbar, T = osc.osc_profile_calibrate(bf(X), G, 5.0, R, workspace=ws)
+    assert abs(T.item() - ref_T) <= 1e-6 * ref_T
+    rt, rn, rh, rd, rc = oracle.profile_table(oracle.profile_hist(X, T.item(), G), R)
+    assert np.array_equal(table.cpu().numpy(), rt)
+    assert np.array_equal(as_u32(n_total), rn.astype(np.uint32)) and np.array_equal(as_u32(n_hit), rh.astype(np.uint32))
+    assert np.allclose(density.cpu().numpy(), rd, rtol=1e-6, atol=0) and abs(cbar.item() - rc) <= 1e-6
+    # and equal to the four separate calls
+    acc = osc.osc_profile_abs_sum(bf(X))
+    T4 = osc.osc_profile_threshold(acc, S * H, 5.0)
+    t4 = osc.osc_profile_table(osc.osc_profile_hist(bf(X), T4, G), R)
+    assert torch.equal(t4[0], table) and torch.equal(t4[1], n_total) and torch.equal(t4[2], n_hit)

@@ -389,6 +389,21 @@ int osc_profile_calibrate(const void *X, int64_t S, int64_t H, int64_t ldx, int3
                           float *density, float *cbar, float *T_out, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/*
+ * osc_profile_calibrate for callers that cannot allocate device memory or have none to spare for a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments without the workspace, same results.  The intermediate results live in a fixed
+ * 64.25 KB array inside the library (one copy on every GPU the library runs on, kept until the
+ * process ends), so H <= 16384 (OSC_ERR_UNSUPPORTED above that).  The call allocates nothing and
+ * clears the part of the array it uses itself.  Every call on one GPU uses that GPU's one array:
+ * calls that overlap on the same GPU (different streams, different threads) race and give wrong
+ * results; calls on one stream, or otherwise ordered, are fine.
+ */
+int osc_profile_calibrate_static(const void *X, int64_t S, int64_t H, int64_t ldx, int32_t G,
+                                 float alpha, int32_t R, int16_t *table, uint32_t *n_total,
+                                 uint32_t *n_hit, float *density, float *cbar, float *T_out,
+                                 void *stream);
+
 #ifdef __cplusplus
 }
 #endif

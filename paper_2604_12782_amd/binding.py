@@ -50,6 +50,7 @@ _SIGS = {
     "osc_profile_table": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
     "osc_profile_workspace_bytes": (sz, [i64]),
     "osc_profile_calibrate": (C.c_int, [vp, i64, i64, i64, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+    "osc_profile_calibrate_static": (C.c_int, [vp, i64, i64, i64, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp]),
     "osc_grouped_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, vp, i32, i64, vp, i64, i64, i32, vp,
                                         C.c_int, i64, vp]),
 }
@@ -358,6 +359,16 @@ def osc_profile_calibrate(X, G=32, alpha=5.0, R=1, workspace=None, out=None):
     o = _calibrate_outputs(H, G, R, X.device, out)
     _check(lib().osc_profile_calibrate(_ptr(X), S, H, X.stride(0), G, alpha, R, *[_ptr(t) for t in o], _ptr(workspace),
                                        workspace.numel(), _stream()))
+    return o
+
+
+def osc_profile_calibrate_static(X, G=32, alpha=5.0, R=1, out=None):
+    """osc_profile_calibrate on the library's own fixed scratch array (H <= 16384); with `out` given
+    (the six output tensors) the call allocates nothing at all."""
+    X = _rows16(X)
+    S, H = X.shape
+    o = _calibrate_outputs(H, G, R, X.device, out)
+    _check(lib().osc_profile_calibrate_static(_ptr(X), S, H, X.stride(0), G, alpha, R, *[_ptr(t) for t in o], _stream()))
     return o
 
 

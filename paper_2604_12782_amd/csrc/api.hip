@@ -547,4 +547,16 @@ int osc_profile_calibrate(const void* X, int64_t S, int64_t H, int64_t ldx, int3
                                     density, cbar, T_out, static_cast<uint8_t*>(workspace), as_stream(stream));
 }
 
+int osc_profile_calibrate_static(const void* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha, int32_t R,
+                                 int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
+                                 float* T_out, void* stream) {
+    int rc = check_calibrate("osc_profile_calibrate_static", X, S, H, ldx, G, R, table);
+    if (rc) return rc;
+    REQUIRE(H <= PROFILE_STATIC_MAX_H, OSC_ERR_UNSUPPORTED,
+            "osc_profile_calibrate_static: H=%lld exceeds the %lld channels its fixed scratch array holds "
+            "(use osc_profile_calibrate with a workspace)", (long long)H, (long long)PROFILE_STATIC_MAX_H);
+    return launch_profile_calibrate_static(static_cast<const uint16_t*>(X), S, H, ldx, G, alpha, R, table, n_total,
+                                           n_hit, density, cbar, T_out, as_stream(stream));
+}
+
 }  // extern "C"

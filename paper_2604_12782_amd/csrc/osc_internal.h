@@ -89,7 +89,11 @@ int launch_profile_hist(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, in
 int launch_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, int16_t* table,
                          uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar, hipStream_t st);
 
+constexpr int64_t PROFILE_STATIC_MAX_H = 16384;  // widest activation the allocation-free profiling call takes
 size_t profile_scratch_bytes(int64_t H);
+int launch_profile_calibrate_static(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha,
+                                    int32_t R, int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density,
+                                    float* cbar, float* T_out, hipStream_t st);
 int launch_profile_calibrate(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha, int32_t R,
                              int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
                              float* T_out, uint8_t* scratch, hipStream_t st);

@@ -1,6 +1,8 @@
 // Offline profiling on the device (Section 2.1 Eq. 1, Section 2.2 Eq. 2-4, Alg. 1): the layer-wise
 // threshold, the per-token group-argmax counts and the suppression table built from them.
 // The two kernels that read the activations are HBM-bandwidth-bound, read-only streams.
+#include <mutex>
+
 #include "osc_internal.h"
 #include "wave_util.h"
 
@@ -333,6 +335,37 @@ int launch_profile_calibrate(const uint16_t* X, int64_t S, int64_t H, int64_t ld
         rc = check_launch("profile_copy_float_kernel");
     }
     return rc;
+}
+
+// ---- the same call for callers that cannot allocate -----------------------------------------------
+// The intermediate results live in a file-scope device array instead of a caller's workspace.  In
+// host code the array's name is only a handle: its device address is looked up once per device
+// (every GPU holds its own copy at its own address) and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[256 + 4 * PROFILE_STATIC_MAX_H];
+
+static uint8_t* static_scratch_address() {
+    static std::mutex mu;
+    static uint8_t* ptr[MAX_DEVICES];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev] = static_cast<uint8_t*>(p);
+    }
+    return ptr[dev];
+}
+
+int launch_profile_calibrate_static(const uint16_t* X, int64_t S, int64_t H, int64_t ldx, int32_t G, float alpha,
+                                    int32_t R, int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density,
+                                    float* cbar, float* T_out, hipStream_t st) {
+    uint8_t* const ptr = static_scratch_address();
+    if (!ptr) return fail(OSC_ERR_HIP, "osc_profile_calibrate_static: cannot find the device address of the scratch array");
+    return launch_profile_calibrate(X, S, H, ldx, G, alpha, R, table, n_total, n_hit, density, cbar, T_out, ptr, st);
 }
 
 }  // namespace osc

@@ -1525,6 +1525,188 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
 
 
 // ------------------------------------------------------------------------------------------
+// Ring kernel (dual path, one problem, eight wavefronts).  The reduction axis is staged in 64-byte
+// row segments ("half stages": 128 FP4 channels = one scale word per row, or 32 bf16 channels of
+// the branch) through a ring of four LDS slots, so a DMA load has two to three half stages to land
+// instead of less than one stage of the two-slot kernels, at the price of half-line requests.
+// The eight wavefronts form two groups of four (one wavefront of each group per SIMD) that run
+// half an iteration apart: an iteration is a memory cluster (fragment and scale reads of the
+// current half stage, DMA requests for the one three ahead) and a compute cluster (16 MFMAs), each
+// closed by a workgroup barrier, and group 1 enters the loop one barrier late.  While one group
+// feeds the matrix core the other one reads LDS and issues loads, and the barriers keep the two in
+// that anti-phase.  A slot is refilled only after both groups have read it (the requests for half
+// stage h+3 go to the slot of half stage h-1, which both groups left at least one barrier ago);
+// a half stage is published by the counted wait every wavefront executes before a barrier.
+// ------------------------------------------------------------------------------------------
+template <int TM, int TN, int WN, bool PINGPONG>
+__global__ void __launch_bounds__(128 * WN) gemm_ring_kernel(KArgs a) {
+    constexpr int NWV = 2 * WN;
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
+    constexpr int NS = 4;                        // ring slots
+    constexpr int HSB = (BM + BN) * 64;          // operand bytes of a half stage
+    constexpr int NBLK = (BM + BN) / 32;         // 32-row blocks (one 128-byte run of scale words each)
+    constexpr int SCB = NBLK * 128;              // scale bytes of a half stage
+    constexpr int LPT = (BM + BN) / 16 / NWV;    // operand DMA instructions per wavefront and half stage (16 rows each)
+    constexpr int LPA = BM / 16 / NWV;           // of which on the A rows
+    constexpr int SPT = NBLK / 2 / NWV;          // scale DMA instructions per wavefront (two blocks each)
+    constexpr int NLD = LPT + SPT;
+    static_assert((BM / 16) % NWV == 0 && (BN / 16) % NWV == 0 && (NBLK / 2) % NWV == 0, "tile does not split over the wavefronts");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    uint8_t* const scl = lds + NS * HSB;
+
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
+    const TilePos tp = locate_tile<BM, BN>(a);
+    const int m0 = tp.m0, n0 = tp.n0, row_end = tp.row_end;
+
+    const int Kg4 = ((a.K >> 5) + 3) >> 2;
+    const int rowbytes = a.K >> 1;
+    const int nHA = rowbytes >> 6;                   // half stages of the FP4 phase
+    const int nHB = (a.K_o * 2 + 63) >> 6;           // of the bf16 branch
+    const int nH = nHA + nHB;                        // >= 3 (checked on the host)
+
+    // ---- DMA addressing: lane l of instruction i moves the 16-byte piece at position l%4 of row 16*chunk + l/4 ----
+    uint32_t grow[LPT];                              // global row of this lane for instruction i
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int chunk = (i < LPA ? 0 : BM / 16) + wave + NWV * (i < LPA ? i : i - LPA);
+        const int lrow = 16 * chunk + (lane >> 2) - (i < LPA ? 0 : BM);
+        grow[i] = i < LPA ? (uint32_t)min(m0 + lrow, row_end - 1) : (uint32_t)min(n0 + lrow, a.N - 1);
+    }
+    // the piece stored at position p of stage row R is piece p ^ ((R >> 2) & 3) (ring_off)
+    const uint32_t piece16 = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+    uint32_t sco;                                    // scale word of this lane's row in its block, first half stage
+    {
+        const int b = 2 * wave + q;                  // block of this lane half
+        const int g = b < BM / 32 ? min(m0 + 32 * b + r, row_end - 1) : min(n0 + 32 * (b - BM / 32) + r, a.N - 1);
+        sco = (uint32_t)(g >> 5) * (uint32_t)Kg4 * 128u + (uint32_t)(g & 31) * 4u;
+    }
+    const bool sc_is_a = 2 * wave < BM / 32;         // both blocks of a wavefront lie on the same operand (BM/32 even)
+    const uint8_t* const wq = tp.wp + a.off_q;
+    const uint8_t* const wl = tp.wp + a.off_l;
+    const uint8_t* const wsb = tp.wp + a.off_s;
+    const uint8_t* const scbase = sc_is_a ? a.Xs : wsb;
+
+    // ---- fragment addressing ----
+    const int ra0 = wm * (TM * 32) + r, rb0 = BM + wn * (TN * 32) + r;
+    const uint32_t fpos0 = (uint32_t)(((2 * q) ^ ((r >> 2) & 3)) << 4);   // position of piece 2q; piece 2q+1 sits at fpos0 ^ 16
+    const uint32_t fa_off = (uint32_t)ra0 * 64u, fb_off = (uint32_t)rb0 * 64u;
+    const uint32_t sa_off = (uint32_t)(wm * TM) * 128u + (uint32_t)r * 4u + 2u * q;
+    const uint32_t sb_off = (uint32_t)(BM / 32 + wn * TN) * 128u + (uint32_t)r * 4u + 2u * q;
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[i][j][k] = 0.0f;
+
+    // requests of half stage H_ (clamped to the last one: past the end the data goes to a slot nobody reads)
+#define RING_LOAD(H_, SLOT_)                                                                              \
+    {                                                                                                     \
+        const int h__ = min((H_), nH - 1);                                                                \
+        const bool fp4__ = h__ < nHA;                                                                     \
+        const uint32_t ko__ = (uint32_t)(fp4__ ? h__ : h__ - nHA) * 64u + piece16;                        \
+        const uint32_t pa__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.bpitch;                            \
+        const uint32_t pb__ = fp4__ ? (uint32_t)rowbytes : (uint32_t)a.wlpitch;                           \
+        const uint8_t* ba__ = fp4__ ? a.Xq : a.B;                                                         \
+        const uint8_t* bb__ = fp4__ ? wq : wl;                                                            \
+        uint8_t* dst__ = lds + (SLOT_)*HSB + wave * 1024;                                                 \
+        _Pragma("unroll") for (int i = 0; i < LPT; ++i) {                                                 \
+            const uint8_t* src__ = (i < LPA ? ba__ + grow[i] * pa__ : bb__ + grow[i] * pb__) + ko__;      \
+            load_to_lds16(src__, dst__ + (i < LPA ? i * (NWV * 1024) : BM * 64 + (i - LPA) * (NWV * 1024))); \
+        }                                                                                                 \
+        const uint32_t so__ = (uint32_t)min(h__, Kg4 - 1) * 128u + sco;                                   \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(scbase + so__),  \
+                                         (__attribute__((address_space(3))) void*)(scl + (SLOT_)*SCB + wave * 256), \
+                                         4, 0, 0);                                                        \
+    }
+    // fragments of both pieces of this lane half and the two scale bytes that go with them
+#define RING_READ(SLOT_, FA0_, FB0_, FA1_, FB1_, SA_, SB_)                                                \
+    {                                                                                                     \
+        const uint8_t* st__ = lds + (SLOT_)*HSB;                                                          \
+        const uint8_t* sc__ = scl + (SLOT_)*SCB;                                                          \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                  \
+            FA0_[i] = *reinterpret_cast<const u32x4*>(st__ + fa_off + i * 2048 + fpos0);                  \
+            FA1_[i] = *reinterpret_cast<const u32x4*>(st__ + fa_off + i * 2048 + (fpos0 ^ 16u));          \
+            SA_[i] = *reinterpret_cast<const uint16_t*>(sc__ + sa_off + i * 128);                         \
+        }                                                                                                 \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                                  \
+            FB0_[j] = *reinterpret_cast<const u32x4*>(st__ + fb_off + j * 2048 + fpos0);                  \
+            FB1_[j] = *reinterpret_cast<const u32x4*>(st__ + fb_off + j * 2048 + (fpos0 ^ 16u));          \
+            SB_[j] = *reinterpret_cast<const uint16_t*>(sc__ + sb_off + j * 128);                         \
+        }                                                                                                 \
+    }
+
+    // ---- prologue: half stages 0, 1, 2 requested; 0 published ----
+    RING_LOAD(0, 0)
+    RING_LOAD(1, 1)
+    RING_LOAD(2, 2)
+    wait_vmcnt<2 * NLD>();
+    __syncthreads();
+    if (PINGPONG && wm == 1) __builtin_amdgcn_s_barrier();   // group 1 runs half an iteration behind
+
+    u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    int sa[TM], sb[TN];
+#define RING_ITER(H_, FP4_)                                                                               \
+    {                                                                                                     \
+        const int slot__ = (H_)&3;                                                                        \
+        /* memory cluster */                                                                              \
+        RING_READ(slot__, fa0, fb0, fa1, fb1, sa, sb)                                                     \
+        RING_LOAD((H_) + 3, ((H_) + 3) & 3)                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0): the fragments are in registers */              \
+        if (PINGPONG) {                                                                                   \
+            wait_vmcnt<2 * NLD>();                                                                        \
+            __builtin_amdgcn_s_barrier();                                                                 \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        /* compute cluster */                                                                             \
+        __builtin_amdgcn_s_setprio(1);                                                                    \
+        if (FP4_) {                                                                                       \
+            OSC_MFMA_FP4(0, fa0, fb0, sa, sb)                                                             \
+            OSC_MFMA_FP4(1, fa1, fb1, sa, sb)                                                             \
+        } else {                                                                                          \
+            OSC_MFMA_BF16(fa0, fb0)                                                                       \
+            OSC_MFMA_BF16(fa1, fb1)                                                                       \
+        }                                                                                                 \
+        __builtin_amdgcn_s_setprio(0);                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        wait_vmcnt<2 * NLD>();                                                                            \
+        __builtin_amdgcn_s_barrier();                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+    }
+    int h = 0;
+#pragma unroll 1
+    for (; h < nHA; ++h) RING_ITER(h, true)
+#pragma unroll 1
+    for (; h < nH; ++h) RING_ITER(h, false)
+    wait_vmcnt<0>();                                          // the idle requests of the last iterations still target LDS
+    if (PINGPONG && wm == 0) __builtin_amdgcn_s_barrier();    // balances group 1's late start
+#undef RING_ITER
+#undef RING_READ
+#undef RING_LOAD
+    store_result<MODE_DUAL, TM, TN, WN>(a, tp, acc);
+}
+
+template <int TM, int TN, int WN, bool PINGPONG>
+static int launch_ring(KArgs a, hipStream_t st) {
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
+    const size_t smem = (size_t)4 * ((BM + BN) * 64 + (BM + BN) / 32 * 128);
+    a.tiles_n = (int)((a.N + BN - 1) / BN);
+    const int64_t grid = (int64_t)((a.M + BM - 1) / BM) * a.tiles_n;
+    if (grid <= 0) return OSC_OK;
+    if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
+    auto kern = gemm_ring_kernel<TM, TN, WN, PINGPONG>;
+    static unsigned char lds_done[MAX_DEVICES];
+    static size_t lds_reserved[MAX_DEVICES];
+    if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a);
+    return check_launch("gemm_ring_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
 // Skinny kernel (M <= 64: decode batches), dual path and FP8.  The work is streaming the weights once,
 // so the grid is as wide as it can be without splitting the reduction over workgroups: one
 // workgroup per 32 output channels; its four wavefronts take the 128-byte lines of the
@@ -1889,13 +2071,21 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     if (const int t_tile = tuning(TUNE_GEMM_TILE), t_kern = tuning(TUNE_GEMM_KERNEL); t_tile >= 0 || t_kern >= 0) {
         // test and tuning overrides (osc_tuning.h); a kernel that cannot serve the shape is not forced
         if (t_tile >= 0) tm = (t_tile == 1 || t_tile == 2 || t_tile == 4) ? t_tile : 2;
-        int k2 = (t_kern >= 0 && t_kern <= 3) ? t_kern : kind;
+        int k2 = (t_kern >= 0 && t_kern <= 3) ? t_kern : kind;  // ids above 3 are handled before the launch below
         if (t_tile >= 0 && t_kern < 0 && k2 == 3) k2 = lines ? 1 : 0;  // a forced tile means a tiled kernel
         if ((k2 == 1 || k2 == 2) && !lines) k2 = 0;
         if (k2 == 2 && tm == 1) k2 = 1;
         if (k2 == 2 && !pipe_ok) k2 = 1;
         if (k2 == 3 && !skinny_ok) k2 = 0;
         kind = k2;
+    }
+    if constexpr (MODE == MODE_DUAL) {
+        // ring kernel (ids 4 and 5: with and without the two wavefront groups in anti-phase)
+        const int t_kern = tuning(TUNE_GEMM_KERNEL);
+        const bool ring_ok = lines && !grouped && !p.row_map && (rowbytes / 64 + (p.K_o * 2 + 63) / 64) >= 3 &&
+                             (p.K_o == 0 || a.bpitch % 64 == 0) && p.M >= 1;
+        if ((t_kern == 4 || t_kern == 5) && ring_ok)
+            return t_kern == 4 ? launch_ring<4, 2, 4, true>(a, st) : launch_ring<4, 2, 4, false>(a, st);
     }
     if (kind == 3) return launch_skinny<MODE>(a, st);
     if (kind == 2 && p.N % (64 * tm) == 0 && p.M >= 64 * tm) {

@@ -130,7 +130,11 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w1), scale, 1);
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w2), scale, 2);
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w3), scale, 3);
+#ifdef OSC_EXP_Q_CACHED
+                if (c < nchunk) dst[c] = out;
+#else
                 if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
+#endif
             }
             if (K_o > 0) {
                 // The strip was written by this wavefront, and LDS runs a wavefront's operations in

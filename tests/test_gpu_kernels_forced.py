@@ -31,8 +31,9 @@ def close(Y, ref, what, bf16=False):
     assert np.isfinite(Y).all() and (np.abs(Y - ref) <= slack).all(), what
 
 
-# tile rows / 64, kernel id: 0 staged, 1 DMA (eight wavefronts at 256 rows), 2 persistent, 3 skinny
-FORCED = ["4,1", "2,1", "1,1", "1,0", "2,0", "4,2", "2,2"]
+# tile rows / 64, kernel id: 0 staged, 1 DMA (eight wavefronts at 256 rows), 2 persistent, 3 skinny,
+# 4 ring (wavefront groups in anti-phase), 5 ring (in phase)
+FORCED = ["4,1", "2,1", "1,1", "1,0", "2,0", "4,2", "2,2", "4,4", "4,5"]
 
 
 @pytest.mark.parametrize("cfg", FORCED)

@@ -281,7 +281,7 @@ def moe_rows(b):
         osc.osc_pack_weight(W, oidx, out=Wp[e * stride:(e + 1) * stride])
         osc.osc_pack_weight_fp8(W, out=Wp8[e * stride8:(e + 1) * stride8])
     # the W8A8 form of the same layer: gathered rows quantised per token
-    Xg = b.up(X)[d_map.long()]
+    Xg = b.up(X[row_map])
     q8 = osc.osc_quantize_act(Xg, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
     Y = torch.empty((T, N), dtype=torch.bfloat16, device=b.dev)
     ms, ms8 = b.time_many([lambda: osc.osc_grouped_dual_gemm(*q, d_map, d_off, T, Wp, N, K, K_o, ydt, out=Y),

@@ -1804,16 +1804,14 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
             int sbm__ = 0x7f7f7f7f, sxm__[MT];                                                          \
             _Pragma("unroll") for (int m = 0; m < MT; ++m) sxm__[m] = 0x7f7f7f7f;                       \
             if (MODE == MODE_MX8) {                                                                     \
-                sbm__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*sstep) >> (8 * q);              \
-                _Pragma("unroll") for (int m = 0; m < MT; ++m)                                          \
-                    sxm__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*sstep) >> (8 * q);    \
+                sbm__ = sb_cur >> (8 * q);                                                              \
+                _Pragma("unroll") for (int m = 0; m < MT; ++m) sxm__[m] = sx_cur[m] >> (8 * q);         \
             }                                                                                           \
             SKINNY_F8(0) SKINNY_F8(1)                                                                   \
         } else if ((L_) < nL) {                                                                         \
-            const int sb__ = *reinterpret_cast<const int*>(ws + (size_t)(L_)*sstep);                    \
+            const int sb__ = sb_cur;                                                                    \
             int sx__[MT];                                                                               \
-            _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
-                sx__[m] = *reinterpret_cast<const int*>(xs[m] + (size_t)(L_)*sstep);                    \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m) sx__[m] = sx_cur[m];                         \
             SKINNY_FP4(0) SKINNY_FP4(1) SKINNY_FP4(2) SKINNY_FP4(3)                                     \
         } else {                                                                                        \
             _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
@@ -1842,15 +1840,36 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
     }
     // lines wave, wave+NW, ...; the next line is in flight while one is consumed.  Everything a wave
     // reads from LDS it wrote itself, so "my loads have landed" is all the synchronisation needed.
+    // The scale words of a line (block-scaled modes) travel with its DMA requests, one line ahead, into
+    // registers: fetched where they are used, every line would wait for a round trip to L2 of its own.
+    // A line past the scaled phase re-reads the last word (never used).
+    constexpr int NSC = (MODE == MODE_FP8) ? 0 : 1 + MT;  // scale loads per line
+    int sb_cur = 0, sb_nxt = 0, sx_cur[MT], sx_nxt[MT];
+#define SKINNY_SCALES(L_, SB_, SX_)                                                                     \
+    if (MODE != MODE_FP8) {                                                                             \
+        const size_t so__ = (size_t)min((L_), nL - 1) * sstep;                                          \
+        SB_ = *reinterpret_cast<const int*>(ws + so__);                                                 \
+        _Pragma("unroll") for (int m = 0; m < MT; ++m) SX_[m] = *reinterpret_cast<const int*>(xs[m] + so__); \
+    }
     int L = wave, img = 0;
     SKINNY_FETCH(L, 0)
+    SKINNY_SCALES(L, sb_cur, sx_cur)
 #pragma unroll 1
     for (; L < nLT; L += NW) {
         SKINNY_FETCH(L + NW, img ^ 1)
-        if (L + NW < nLT) wait_vmcnt<NDMA>(); else wait_vmcnt<0>();
+        if (L + NW < nLT) {
+            SKINNY_SCALES(L + NW, sb_nxt, sx_nxt)
+            wait_vmcnt<NDMA + NSC>();
+        } else {
+            wait_vmcnt<0>();
+        }
         SKINNY_COMPUTE(L, img)
+        sb_cur = sb_nxt;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) sx_cur[m] = sx_nxt[m];
         img ^= 1;
     }
+#undef SKINNY_SCALES
 #undef SKINNY_FP4
 #undef SKINNY_F8
 #undef SKINNY_COMPUTE
@@ -1903,6 +1922,16 @@ static int launch_skinny(KArgs a, hipStream_t st) {
     // instead of 11.8 at 64x12288x4096.
     if (grid * mtiles > 2 * (int64_t)ncu) {
         hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 3>), dim3((unsigned)grid, mtiles), dim3(192), 3 * 2 * 64 * 128, st, a);
+        return check_launch("gemm_skinny_kernel");
+    }
+    // A grid that leaves CUs idle (4096 output channels: 128 workgroups; 1024: 32) splits the reduction
+    // over eight wavefronts instead: 128 KB of LDS, one workgroup per CU, twice the lines in flight.
+    if (grid * mtiles <= (int64_t)ncu) {
+        auto kern = gemm_skinny_kernel<MODE, 1, 8>;
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), 8 * 2 * 64 * 128, lds_done, lds_reserved)) return rc;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid, mtiles), dim3(512), 8 * 2 * 64 * 128, st, a);
         return check_launch("gemm_skinny_kernel");
     }
     hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 4>), dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);

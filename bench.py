@@ -178,7 +178,7 @@ def gemm_row(M, N, K, r, K_o, ms_osc, ms_f8, decode, cold):
     return row
 
 
-def shapes_table(b, quick=False):
+def shapes_table(b, quick=False, only=None):
     """Every GEMM shape of benchmark configurations 1-4 ("configs[1..4]" of the task), inputs from the seeded
     generators, dual path against the library's FP8 W8A8 GEMM on the same X and W, bf16 output."""
     torch, osc, wl = b.torch, b.osc, b.wl
@@ -233,6 +233,10 @@ def shapes_table(b, quick=False):
             row = gemm_row(M, N, K, r, K_o, ms, ms8, False, False)
         rows[tag] = row
 
+    if only == "cfg3":
+        X, table = wl.activations_persistent(3001, 8192, K_HID, 2)
+        one("cfg3 W1|W3 M=8192 N=24576", X, table, wl.weights(3002, 24576, K_HID), 2, "cfg3")
+        return rows
     # configs[1]: attention projections
     Wn = {4096: wl.weights(2100, 4096, K_HID), 1024: wl.weights(2101, 1024, K_HID)}
     for N in (4096, 1024):
@@ -363,6 +367,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip most rows of the shapes table (profiler runs)")
     ap.add_argument("--only-step", action="store_true", help="the headline step only (profiler runs)")
+    ap.add_argument("--section", choices=["cfg3", "moe"], default=None,
+                    help="profiler runs: only the launches of configs[2] (W1|W3 dual GEMM, W_2 FP8 and MXFP8 GEMMs) "
+                         "or of configs[3] (grouped GEMMs), a few times each")
     ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a counter yardstick for profiler runs)")
@@ -379,6 +386,29 @@ def main():
     M = args.tokens
     b = Bench(torch, osc, wl)
     dev, up, ev = b.dev, b.up, b.ev
+    if args.copy_mib:
+        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if args.section == "moe":
+        print(json.dumps({"shapes_moe": moe_rows(b)}))
+        return
+    if args.section == "cfg3":
+        res = {"shapes": shapes_table(b, only="cfg3")}
+        Xf = up(wl.activations_diffuse(3003, 8192, 12288))
+        Wf = up(wl.weights(3004, 4096, 12288))
+        wm8, wf8 = osc.osc_pack_weight_mxfp8(Wf), osc.osc_pack_weight_fp8(Wf)
+        m8 = osc.osc_quantize_act(Xf, None, osc.OSC_FMT_MXFP8)
+        t8 = osc.osc_quantize_act(Xf, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+        Yf = torch.empty((8192, 4096), dtype=torch.bfloat16, device=dev)
+        a8, a4 = b.time_many([lambda: osc.osc_mxfp8_gemm(*m8, wm8, 4096, 12288, y_dtype=osc.OSC_DT_BF16, out=Yf),
+                              lambda: osc.osc_fp8_gemm(*t8, wf8, 4096, 12288, y_dtype=osc.OSC_DT_BF16, out=Yf)], reps=5)
+        res["w2"] = {"mxfp8_gemm_ms": round(a8, 4), "fp8_gemm_ms": round(a4, 4)}
+        print(json.dumps(res))
+        return
 
     # ---- inputs (seeded, built on the CPU, uploaded once) -----------------------------------
     X1, table1 = wl.activations_persistent(2001, M, K_HID, 2)
@@ -434,13 +464,6 @@ def main():
             fn(**kw)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
-
-    if args.copy_mib:
-        src = torch.zeros(args.copy_mib << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     ms_step = timed_loop(step, args.steps, args.warmup, timed=True)
     dom_ms = float(np.mean([a.elapsed_time(c) for a, c in dom]))

@@ -227,6 +227,51 @@ def quantize_mxfp8(X):
     return Xq, Xs
 
 
+FMT16_E8M0, FMT16_NVFP4 = 0, 1
+
+
+def quantize_fp4_g16(X, oidx=None, ldb=None, fmt=FMT16_E8M0, tensor_scale=1.0):
+    """Alg. 2 with scale groups of 16 channels.  fmt 0: E8M0 scale per 16; fmt 1: NVFP4 (E4M3 scale per
+    16, single-precision tensor scale given by the caller).
+    -> (Xq uint8[M, K/2], Xs16 uint8[M, K/16], B uint16[M, ldb])."""
+    X = _c(X, np.uint16)
+    M, K = X.shape
+    oidx = np.zeros(0, np.int32) if oidx is None else _c(oidx, np.int32)
+    K_o = len(oidx)
+    if ldb is None:
+        ldb = K_o
+    Xq = np.empty((M, K // 2), np.uint8)
+    Xs = np.empty((M, K // 16), np.uint8)
+    B = np.zeros((M, ldb), np.uint16)
+    lib().ref_quantize_fp4_g16.argtypes = [C.c_void_p, i64, i64, i64, C.c_void_p, i32, C.c_int, C.c_float,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, i64]
+    _check(lib().ref_quantize_fp4_g16(_p(X), M, K, K, _p(oidx) if K_o else None, K_o, fmt,
+                                      float(np.float32(tensor_scale)), _p(Xq), _p(Xs), _p(B) if ldb else None, ldb),
+           "ref_quantize_fp4_g16")
+    return Xq, Xs, B
+
+
+def dual_gemm_g16(Xq, Xs16, B, Wq, Ws16, WL, fmt=FMT16_E8M0, x_tensor_scale=1.0, w_tensor_scale=1.0):
+    """Eq. (dual-path) on operands with one scale per 16 channels, in double."""
+    Xq, Xs16, Wq, Ws16 = (_c(a, np.uint8) for a in (Xq, Xs16, Wq, Ws16))
+    M, N = Xq.shape[0], Wq.shape[0]
+    K = Xq.shape[1] * 2
+    assert Wq.shape[1] * 2 == K and Xs16.shape == (M, K // 16) and Ws16.shape == (N, K // 16)
+    K_o = 0 if WL is None else int(WL.shape[0])
+    if K_o:
+        B, WL = _c(B, np.uint16), _c(WL, np.uint16)
+        ldb = B.shape[1]
+    else:
+        B, WL, ldb = None, None, 0
+    Y = np.empty((M, N), np.float64)
+    lib().ref_dual_gemm_g16.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, i64, C.c_void_p, C.c_void_p,
+                                        C.c_float, C.c_void_p, i64, i64, i64, i32, C.c_int, C.c_void_p, i64]
+    _check(lib().ref_dual_gemm_g16(_p(Xq), _p(Xs16), float(np.float32(x_tensor_scale)), _p(B), ldb, _p(Wq), _p(Ws16),
+                                   float(np.float32(w_tensor_scale)), _p(WL), M, N, K, K_o, fmt, _p(Y), N),
+           "ref_dual_gemm_g16")
+    return Y
+
+
 # ---- GEMMs -------------------------------------------------------------------
 
 

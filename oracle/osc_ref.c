@@ -31,6 +31,9 @@
  *   ref_rmsnorm_plain, ref_swiglu_plain  the same two producers in plain double precision with a
  *                           single final rounding: the pin that ties the two recipes above (and the
  *                           kernels that reproduce them) to RMSNorm and SwiGLU themselves
+ *   ref_quantize_fp4_g16, ref_dual_gemm_g16  Alg. 2 and Eq. (dual-path) for 4-bit formats whose scale
+ *                           group is 16 channels (Section 3.1's G = 16; Table 2's first row; the
+ *                           NVFP4 format named in the abstract and the conclusion)
  *   ref_gather_wl           W_L: rows of the high-precision weight named by
  *                           the same table (Section 3.3.1, second bullet)
  *   ref_dual_gemm           Eq. (dual-path): Y = (Q_X (x) Q_W).S + B.W_L
@@ -72,6 +75,7 @@
 #include <float.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -679,6 +683,118 @@ int ref_mxfp8_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint8_t *Wq, cons
             Y[m * ldy + n] = y;
         }
     }
+    return REF_OK;
+}
+
+/* ---- 4-bit formats with scale groups of 16 channels --------------------------------------- *
+ * Section 3.1 cuts the channels into groups of G in {16, 32, 64} "for compatibility with
+ * group-wise micro-scaling formats"; Table 2 has a G = 16 row; the abstract and the conclusion name
+ * NVFP4.  The paper gives no arithmetic for either; the readings taken here:
+ *   fmt 0 (E8M0 per 16): the MX rule on blocks of 16: shared exponent floor(log2 amax) - 2 as an
+ *          E8M0 code, E2M1 elements x / 2^e rounded to nearest even, saturating;
+ *   fmt 1 (NVFP4): E2M1 elements, one E4M3 scale per 16 channels, one single-precision scale ts per
+ *          tensor (given by the caller: a calibrated constant), every step one IEEE single-precision
+ *          operation:  d = 6 * ts;  q = amax / d;  sc = e4m3(q) (nearest even, saturating at 448);
+ *          s = value of sc;  den = ts * s;  inv = 1 / den;  element = e2m1(x * inv) (nearest even,
+ *          saturating); a block whose scale rounds to zero keeps only the signs of its elements.
+ * Everything else is Alg. 2 unchanged: protected channels are copied to B and count as +0 before
+ * the scale of their block is computed.  Xs16[M, K/16]: one scale byte per 16 channels, row-major. */
+int ref_quantize_fp4_g16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const int32_t *oidx,
+                         int32_t K_o, int fmt, float ts, uint8_t *Xq, uint8_t *Xs16, uint16_t *B,
+                         int64_t ldb) {
+    if (fmt != 0 && fmt != 1) return REF_ERR_ARG;
+    if (M < 0 || K < 0 || K % 16 || ldx < K || K_o < 0 || ldb < K_o) return REF_ERR_ARG;
+    if (fmt == 1 && !(ts > 0.0f && ts <= FLT_MAX)) return REF_ERR_ARG;
+    if (M == 0 || K == 0) return REF_OK;
+    if (!X || !Xq || !Xs16 || (K_o && (!oidx || !B))) return REF_ERR_ARG;
+    for (int32_t o = 0; o < K_o; ++o)
+        if (oidx[o] < 0 || oidx[o] >= K) return REF_ERR_TABLE;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        const uint16_t *x = X + m * ldx;
+        uint8_t *removed = (uint8_t *)calloc((size_t)K, 1);
+        if (B)
+            for (int64_t o = 0; o < ldb; ++o) B[m * ldb + o] = 0;
+        for (int32_t o = 0; o < K_o; ++o) {
+            B[m * ldb + o] = x[oidx[o]];
+            removed[oidx[o]] = 1;
+        }
+        for (int64_t g = 0; g < K / 16; ++g) {
+            float v[16];
+            int neg[16];
+            float amax = 0.0f;
+            for (int j = 0; j < 16; ++j) {
+                uint16_t h = removed[g * 16 + j] ? (uint16_t)0 : x[g * 16 + j];
+                if ((h & 0x7F80) == 0x7F80) bad = 1;
+                v[j] = bf16_to_float(h);
+                neg[j] = (h >> 15) & 1;
+                if (fabsf(v[j]) > amax) amax = fabsf(v[j]);
+            }
+            int code[16];
+            if (fmt == 0) {
+                int e = mx_shared_exponent((double)amax);
+                Xs16[m * (K / 16) + g] = (uint8_t)(e + 127);
+                for (int j = 0; j < 16; ++j) code[j] = ref_e2m1_encode(ldexp((double)v[j], -e), neg[j]);
+            } else {
+                volatile float d = 6.0f * ts;
+                volatile float q = amax / d;
+                int sc = (q <= FLT_MAX) ? ref_e4m3_encode(q) : 0x7E; /* beyond single range: the largest scale */
+                sc &= 0x7F;
+                Xs16[m * (K / 16) + g] = (uint8_t)sc;
+                float sval = (float)ref_e4m3_decode(sc);
+                if (sval == 0.0f) {
+                    for (int j = 0; j < 16; ++j) code[j] = neg[j] ? 8 : 0;
+                } else {
+                    volatile float den = ts * sval;
+                    volatile float inv = 1.0f / den;
+                    for (int j = 0; j < 16; ++j) {
+                        volatile float w = v[j] * inv;
+                        code[j] = (fabsf(w) <= FLT_MAX) ? ref_e2m1_encode((double)w, neg[j]) : (neg[j] ? 15 : 7);
+                    }
+                }
+            }
+            for (int j = 0; j < 16; j += 2)
+                Xq[m * (K / 2) + (g * 16 + j) / 2] = (uint8_t)(code[j] | (code[j + 1] << 4));
+        }
+        free(removed);
+    }
+    return bad ? REF_ERR_NONFINITE : REF_OK;
+}
+
+static double scale16_value(int fmt, int code) {
+    return fmt == 0 ? ldexp(1.0, code - 127) : ref_e4m3_decode(code & 0x7F);
+}
+
+/* The dual-path layer on those operands (Eq. dual-path with the scale of a block of 16):
+ *   Y[m,n] = xts * wts * sum_b s(Xs16[m,b]) * s(Ws16[n,b]) * sum_{j<16} e2m1(Xq[m,16b+j]) * e2m1(Wq[n,16b+j])
+ *          + sum_{o<K_o} B[m,o] * W_L[o,n]            (xts = wts = 1 for fmt 0), all in double. */
+int ref_dual_gemm_g16(const uint8_t *Xq, const uint8_t *Xs16, float xts, const uint16_t *B, int64_t ldb,
+                      const uint8_t *Wq, const uint8_t *Ws16, float wts, const uint16_t *WL, int64_t M,
+                      int64_t N, int64_t K, int32_t K_o, int fmt, double *Y, int64_t ldy) {
+    if ((fmt != 0 && fmt != 1) || M < 0 || N < 0 || K < 0 || K % 16 || K_o < 0 || ldy < N) return REF_ERR_ARG;
+    if (M == 0 || N == 0) return REF_OK;
+    if (!Y || (K && (!Xq || !Xs16 || !Wq || !Ws16)) || (K_o && (!B || !WL || ldb < K_o))) return REF_ERR_ARG;
+    const double ts = fmt == 1 ? (double)xts * (double)wts : 1.0;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t b = 0; b < K / 16; ++b) {
+                double part = 0.0;
+                for (int j = 0; j < 16; ++j) {
+                    int64_t k = b * 16 + j;
+                    int cx = (Xq[m * (K / 2) + k / 2] >> (4 * (k & 1))) & 15;
+                    int cw = (Wq[n * (K / 2) + k / 2] >> (4 * (k & 1))) & 15;
+                    part += ref_e2m1_decode(cx) * ref_e2m1_decode(cw);
+                }
+                acc += part * scale16_value(fmt, Xs16[m * (K / 16) + b]) * scale16_value(fmt, Ws16[n * (K / 16) + b]);
+            }
+            acc *= ts;
+            for (int32_t o = 0; o < K_o; ++o)
+                acc += (double)bf16_to_float(B[m * ldb + o]) * (double)bf16_to_float(WL[(int64_t)o * N + n]);
+            Y[m * ldy + n] = acc;
+        }
     return REF_OK;
 }
 

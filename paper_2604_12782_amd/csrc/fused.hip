@@ -50,7 +50,7 @@ __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
     extern __shared__ uint32_t smem[];
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     u32x4* strip = reinterpret_cast<u32x4*>(smem) + wave * (NCI * 64);
     uint32_t* keep = smem + 4 * NCI * 64 * 4;
     u32x4* gam = reinterpret_cast<u32x4*>(keep + (K >> 1));
@@ -382,7 +382,7 @@ __global__ void __launch_bounds__(TAB ? 768 : FT) swiglu_quant_fp8_kernel(const 
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ uint16_t silu_lds[];
     if (TAB) load_silu_table(silu_lds);
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     const int nwave = TAB ? 12 : 4;
     const int nchunk = K >> 3;
     // a wavefront owns a whole row (lane l holds chunks l, l + 64, ...): the row's amax is register work

@@ -62,7 +62,7 @@ __global__ void __launch_bounds__(PT) profile_abs_sum_kernel(const uint16_t* __r
                                                              int H, int64_t ldx, int nseg, int nslots,
                                                              double* __restrict__ abs_sum) {
     __shared__ double part[PW];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     const int seg = blockIdx.x % nseg, slot = blockIdx.x / nseg;
     const int nchunk = H >> 3;
     const int c0 = seg * P_SEG_CHUNKS + lane;
@@ -133,7 +133,7 @@ __global__ void __launch_bounds__(PT) profile_hist_kernel(const uint16_t* __rest
                                                           const float* __restrict__ Tptr,
                                                           uint32_t* __restrict__ hist) {
     __shared__ uint32_t lhist[P_SEG_CH];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     const int seg = blockIdx.x % nseg, slot = blockIdx.x / nseg;
     const int nchunk = H >> 3;
     const int sc0 = seg * P_SEG_CHUNKS;

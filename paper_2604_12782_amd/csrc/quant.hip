@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
     extern __shared__ uint32_t smem[];
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     // LDS: strips [4][SEG_CHUNKS] x 16 B | keep [K/2] words | colstart [nseg+1] | oidx16 [K_o]
     u32x4* strip = reinterpret_cast<u32x4*>(smem) + wave * SEG_CHUNKS;
     uint32_t* keep = smem + 4 * SEG_CHUNKS * 4;
@@ -130,11 +130,7 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_osc_kernel(
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w1), scale, 1);
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w2), scale, 2);
                 out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, w3), scale, 3);
-#ifdef OSC_EXP_Q_CACHED
-                if (c < nchunk) dst[c] = out;
-#else
                 if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
-#endif
             }
             if (K_o > 0) {
                 // The strip was written by this wavefront, and LDS runs a wavefront's operations in
@@ -218,7 +214,7 @@ __global__ void __launch_bounds__(QT) quant_mxfp4_dynamic_kernel(const uint16_t*
                                                                  int total_wg) {
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     const uint32_t kbase = 31u - (uint32_t)((lane & 3) * 8);
     for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
         const QItem cur = quant_item(wg, wave, nseg, M);
@@ -429,7 +425,7 @@ __global__ void __launch_bounds__(QT) quant_mxfp8_kernel(const uint16_t* __restr
                                                          uint8_t* __restrict__ Xs, int nseg, int total_wg) {
     const int Kg = K >> 5, Kg4 = (Kg + 3) >> 2;
     const int nchunk = K >> 3;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);  // uniform: row and segment arithmetic stays on the scalar unit
     for (int wg = blockIdx.x; wg < total_wg; wg += gridDim.x) {
         const QItem it = quant_item(wg, wave, nseg, M);
         if (it.m < 0) continue;  // uniform over the wavefront

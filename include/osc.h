@@ -48,6 +48,8 @@ enum { OSC_DT_F32 = 0, OSC_DT_BF16 = 1 };                   /* dtype of Y */
 enum { OSC_FMT_MXFP4_OSC = 0, OSC_FMT_FP8_E4M3_TOKEN = 1, OSC_FMT_MXFP8 = 2,
        OSC_FMT_MXFP4_OSC_G64 = 3 };                          /* activation quantiser format */
 
+enum { OSC_FMT16_E8M0 = 0, OSC_FMT16_NVFP4 = 1 };             /* 4-bit formats with one scale per 16 channels */
+
 const char *osc_last_error(void);
 int osc_version(void);
 
@@ -318,6 +320,54 @@ int osc_swiglu_quantize_act_fp8(const void *G, const void *U, int64_t M, int64_t
  */
 int osc_quantize_act_dynamic(const void *X, int64_t M, int64_t K, int64_t ldx, uint8_t *Xq,
                              void *Xs, void *Bd, int64_t ldb, uint8_t *idx, void *stream);
+
+/* ---- 4-bit formats with one scale per 16 channels --------------------------------------------- */
+
+/*
+ * The OSC quantiser and the dual-path layer for the 4-bit formats whose scale group is 16 channels
+ * (Section 3.1: group sizes G in {16, 32, 64}, "for compatibility with group-wise micro-scaling
+ * formats"; Table 2, row G = 16; the abstract and the conclusion name NVFP4).  The paper gives no
+ * arithmetic for either; this library reads them as follows.
+ *   OSC_FMT16_E8M0   E2M1 elements, one E8M0 scale per 16 channels with exponent floor(log2 amax) - 2
+ *                    (code 0 for amax zero or below 2^-124); elements X / 2^exponent, nearest even,
+ *                    saturating at +-6.  The tensor scale arguments are ignored.
+ *   OSC_FMT16_NVFP4  E2M1 elements, one E4M3 scale per 16 channels, one single-precision scale ts per
+ *                    tensor, supplied by the caller (a calibrated constant, typically the largest
+ *                    magnitude of the tensor divided by 6 * 448; 2^-100 <= ts <= 2^100).  Every step
+ *                    is one IEEE single-precision operation: d = 6 * ts; q = amax / d; scale byte =
+ *                    e4m3(q), nearest even, saturating at 448; s = value of the byte; inv = 1 / (ts * s)
+ *                    (0 when s is 0); element = e2m1(x * inv), nearest even, saturating.
+ * In both, Alg. 2 is unchanged: B[m, o] = X[m, oidx[o]] and those channels count as +0 before their
+ * block's scale is computed; an element keeps its sign bit when it rounds to zero.
+ *
+ * osc_quantize_act_g16:  X, oidx, K_o, B, ldb as in osc_quantize_act; K % 64 == 0;
+ *   Xq    uint8 [M, K/2], channel 2i in bits 3:0 of byte i;  Xs16  uint8 [M, K/16], plain row-major.
+ * osc_pack_weight_g16:  quantises W bf16 [N, ldw] row by row in the same format (nothing zeroed),
+ *   gathers W_L[o][n] = W[n][oidx[o]]; Wpack: osc_packed_weight_g16_bytes(N, K, K_o) bytes, 256-byte
+ *   aligned, opaque (osc_unpack_weight_g16 writes Wq uint8 [N, K/2], Ws16 uint8 [N, K/16], WL bf16
+ *   [K_o, N]; any may be NULL).
+ * osc_dual_gemm_g16:
+ *   Y[m,n] = xts * wts * sum_b s(Xs16[m,b]) * s(Ws16[n,b]) * sum_{j<16} e2m1(Xq[m,16b+j]) * e2m1(Wq[n,16b+j])
+ *          + sum_{o<K_o} B[m,o] * W_L[o,n]          (xts = wts = 1 for OSC_FMT16_E8M0)
+ *   K % 256 == 0; ldb % 64 == 0.  The matrix core multiplies 4-bit operands only with one power-of-two
+ *   scale per 32 channels, so this kernel expands the codes to bf16 in registers (exactly) and uses the
+ *   bf16 matrix core: it is built for the weight-bound regime (a few tokens, Table 2's left column),
+ *   where the formats' gain is the 0.56 bytes per weight that travel; it accepts any M, at the bf16
+ *   matrix rate.
+ * Errors: OSC_ERR_NULL, OSC_ERR_SHAPE, OSC_ERR_UNSUPPORTED (format, alignment, K), OSC_ERR_HIP.
+ */
+int osc_quantize_act_g16(const void *X, int64_t M, int64_t K, int64_t ldx, const int32_t *oidx,
+                         int32_t K_o, int fmt16, float tensor_scale, uint8_t *Xq, uint8_t *Xs16,
+                         void *B, int64_t ldb, void *stream);
+size_t osc_packed_weight_g16_bytes(int64_t N, int64_t K, int32_t K_o);
+int osc_pack_weight_g16(const void *W, int64_t N, int64_t K, int64_t ldw, const int32_t *oidx,
+                        int32_t K_o, int fmt16, float tensor_scale, void *Wpack, void *stream);
+int osc_unpack_weight_g16(const void *Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t *Wq,
+                          uint8_t *Ws16, void *WL, void *stream);
+int osc_dual_gemm_g16(const uint8_t *Xq, const uint8_t *Xs16, float x_tensor_scale, const void *B,
+                      int64_t ldb, const void *Wpack, float w_tensor_scale, int64_t M, int64_t N,
+                      int64_t K, int32_t K_o, int fmt16, void *Y, int y_dtype, int64_t ldy,
+                      void *stream);
 
 /* ---- offline profiling (calibration) ------------------------------------------ */
 

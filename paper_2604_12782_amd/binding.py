@@ -11,6 +11,7 @@ import torch
 
 OSC_DT_F32, OSC_DT_BF16 = 0, 1
 OSC_FMT_MXFP4_OSC, OSC_FMT_FP8_E4M3_TOKEN, OSC_FMT_MXFP8, OSC_FMT_MXFP4_OSC_G64 = 0, 1, 2, 3
+OSC_FMT16_E8M0, OSC_FMT16_NVFP4 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libosc.so")
@@ -51,6 +52,12 @@ _SIGS = {
     "osc_profile_workspace_bytes": (sz, [i64]),
     "osc_profile_calibrate": (C.c_int, [vp, i64, i64, i64, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
     "osc_profile_calibrate_static": (C.c_int, [vp, i64, i64, i64, i32, C.c_float, i32, vp, vp, vp, vp, vp, vp, vp]),
+    "osc_quantize_act_g16": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, C.c_float, vp, vp, vp, i64, vp]),
+    "osc_packed_weight_g16_bytes": (sz, [i64, i64, i32]),
+    "osc_pack_weight_g16": (C.c_int, [vp, i64, i64, i64, vp, i32, C.c_int, C.c_float, vp, vp]),
+    "osc_unpack_weight_g16": (C.c_int, [vp, i64, i64, i32, vp, vp, vp, vp]),
+    "osc_dual_gemm_g16": (C.c_int, [vp, vp, C.c_float, vp, i64, vp, C.c_float, i64, i64, i64, i32, C.c_int, vp, C.c_int,
+                                    i64, vp]),
     "osc_grouped_dual_gemm": (C.c_int, [vp, vp, vp, i64, vp, vp, i32, i64, vp, i64, i64, i32, vp,
                                         C.c_int, i64, vp]),
 }
@@ -370,6 +377,60 @@ def osc_profile_calibrate_static(X, G=32, alpha=5.0, R=1, out=None):
     o = _calibrate_outputs(H, G, R, X.device, out)
     _check(lib().osc_profile_calibrate_static(_ptr(X), S, H, X.stride(0), G, alpha, R, *[_ptr(t) for t in o], _stream()))
     return o
+
+
+def osc_quantize_act_g16(X, oidx=None, fmt16=OSC_FMT16_E8M0, tensor_scale=1.0, ldb=None, out=None):
+    """4-bit quantiser with one scale per 16 channels -> (Xq uint8 [M, K/2], Xs16 uint8 [M, K/16], B or None)."""
+    X = _rows16(X)
+    M, K = X.shape
+    dev = X.device
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if ldb is None:
+        ldb = (K_o + 63) // 64 * 64
+    if out is not None:
+        Xq, Xs, B = out
+    else:
+        Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        Xs = torch.empty((M, K // 16), dtype=torch.uint8, device=dev)
+        B = torch.empty((M, ldb), dtype=torch.uint16, device=dev) if ldb else None
+    _check(lib().osc_quantize_act_g16(_ptr(X), M, K, X.stride(0), _ptr(oidx), K_o, fmt16, float(tensor_scale), _ptr(Xq),
+                                      _ptr(Xs), _ptr(B), ldb, _stream()))
+    return Xq, Xs, B
+
+
+def osc_packed_weight_g16_bytes(N, K, K_o):
+    return lib().osc_packed_weight_g16_bytes(N, K, K_o)
+
+
+def osc_pack_weight_g16(W, oidx=None, fmt16=OSC_FMT16_E8M0, tensor_scale=1.0, out=None):
+    W = _rows16(W)
+    N, K = W.shape
+    K_o = 0 if oidx is None else int(oidx.numel())
+    if out is None:
+        out = torch.empty(osc_packed_weight_g16_bytes(N, K, K_o), dtype=torch.uint8, device=W.device)
+    _check(lib().osc_pack_weight_g16(_ptr(W), N, K, W.stride(0), _ptr(oidx), K_o, fmt16, float(tensor_scale), _ptr(out),
+                                     _stream()))
+    return out
+
+
+def osc_unpack_weight_g16(Wpack, N, K, K_o):
+    dev = Wpack.device
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    Ws = torch.empty((N, K // 16), dtype=torch.uint8, device=dev)
+    WL = torch.empty((K_o, N), dtype=torch.uint16, device=dev) if K_o else None
+    _check(lib().osc_unpack_weight_g16(_ptr(Wpack), N, K, K_o, _ptr(Wq), _ptr(Ws), _ptr(WL), _stream()))
+    return Wq, Ws, WL
+
+
+def osc_dual_gemm_g16(Xq, Xs16, B, Wpack, N, K, K_o, fmt16=OSC_FMT16_E8M0, x_tensor_scale=1.0, w_tensor_scale=1.0,
+                      y_dtype=OSC_DT_F32, out=None):
+    M = Xq.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16 if y_dtype == OSC_DT_BF16 else torch.float32, device=Xq.device)
+    _check(lib().osc_dual_gemm_g16(_ptr(Xq), _ptr(Xs16), float(x_tensor_scale), _ptr(B), 0 if B is None else B.stride(0),
+                                   _ptr(Wpack), float(w_tensor_scale), M, N, K, K_o, fmt16, _ptr(out), y_dtype,
+                                   out.stride(0), _stream()))
+    return out
 
 
 def osc_quantize_act_dynamic(X, ldb=None, want_idx=True, out=None):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libosc.so")
 PROBE_LIB = os.path.join(HERE, "libosc_probe.so")
-SOURCES = ["api.hip", "tuning.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip"]
+SOURCES = ["api.hip", "tuning.hip", "quant.hip", "gemm.hip", "profile.hip", "fused.hip", "g16.hip"]
 PROBE_SOURCES = ["probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -52,6 +52,17 @@ PackM8Layout packm8_layout(int64_t N, int64_t K) {
     return L;
 }
 
+Pack16Layout pack16_layout(int64_t N, int64_t K, int32_t K_o) {
+    Pack16Layout L;
+    L.ldwl = ((int64_t)K_o + 63) / 64 * 64;
+    L.off_q = 0;
+    L.off_s = align_up((size_t)N * (size_t)(K / 2), 256);
+    L.off_l = align_up(L.off_s + (size_t)N * (size_t)(K / 16), 256);
+    L.off_z = align_up(L.off_l + (size_t)N * (size_t)L.ldwl * 2, 256);
+    L.total = L.off_z + 256;
+    return L;
+}
+
 }  // namespace osc
 
 using namespace osc;
@@ -518,6 +529,101 @@ int osc_profile_table(const uint32_t* hist, int32_t Kg, int32_t G, int32_t R, in
     REQUIRE((Kg == 0 || hist) && (Kg == 0 || R == 0 || table), OSC_ERR_NULL, "osc_profile_table: null pointer");
     if (Kg == 0 && !cbar) return OSC_OK;
     return launch_profile_table(hist, Kg, G, R, table, n_total, n_hit, density, cbar, as_stream(stream));
+}
+
+// ---- 4-bit formats with a scale per 16 channels -----------------------------------------------
+
+static int check_g16(const char* who, int64_t R, int64_t K, int64_t ld, int32_t K_o, int fmt16, float ts) {
+    REQUIRE(R >= 0 && K >= 0 && K_o >= 0, OSC_ERR_SHAPE, "%s: negative extent", who);
+    REQUIRE(K % 64 == 0, OSC_ERR_SHAPE, "%s: K=%lld is not a multiple of 64", who, (long long)K);
+    REQUIRE(ld >= K, OSC_ERR_SHAPE, "%s: leading dimension %lld < K=%lld", who, (long long)ld, (long long)K);
+    REQUIRE(K_o <= K, OSC_ERR_SHAPE, "%s: K_o=%d exceeds K", who, K_o);
+    REQUIRE(fmt16 == OSC_FMT16_E8M0 || fmt16 == OSC_FMT16_NVFP4, OSC_ERR_UNSUPPORTED, "%s: unknown format %d", who, fmt16);
+    REQUIRE(K <= 65536, OSC_ERR_UNSUPPORTED, "%s: K=%lld exceeds 65536", who, (long long)K);
+    if (fmt16 == OSC_FMT16_NVFP4)
+        REQUIRE(ts >= 0x1p-100f && ts <= 0x1p100f, OSC_ERR_SHAPE, "%s: tensor scale %g outside [2^-100, 2^100]", who, (double)ts);
+    return OSC_OK;
+}
+
+int osc_quantize_act_g16(const void* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx, int32_t K_o, int fmt16,
+                         float tensor_scale, uint8_t* Xq, uint8_t* Xs16, void* B, int64_t ldb, void* stream) {
+    int rc = check_g16("osc_quantize_act_g16", M, K, ldx, K_o, fmt16, tensor_scale);
+    if (rc) return rc;
+    REQUIRE(K_o == 0 || ldb >= K_o, OSC_ERR_SHAPE, "osc_quantize_act_g16: ldb=%lld < K_o=%d", (long long)ldb, K_o);
+    if (M == 0 || K == 0) return OSC_OK;
+    REQUIRE(X && Xq && Xs16 && (K_o == 0 || (oidx && B)), OSC_ERR_NULL, "osc_quantize_act_g16: null pointer");
+    REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(Xq, 4) && aligned(Xs16, 4), OSC_ERR_UNSUPPORTED,
+            "osc_quantize_act_g16: X rows must be 16-byte aligned, Xq and Xs16 4-byte aligned");
+    REQUIRE(!B || (aligned(B, 2) && ldb >= 0), OSC_ERR_UNSUPPORTED, "osc_quantize_act_g16: misaligned B");
+    return launch_quant_fp4_g16(static_cast<const uint16_t*>(X), M, K, ldx, oidx, K_o, fmt16, tensor_scale, Xq, Xs16,
+                                static_cast<uint16_t*>(B), B ? ldb : 0, as_stream(stream));
+}
+
+size_t osc_packed_weight_g16_bytes(int64_t N, int64_t K, int32_t K_o) {
+    if (N < 0 || K < 0 || K % 64 || K_o < 0) return 0;
+    return pack16_layout(N, K, K_o).total;
+}
+
+int osc_pack_weight_g16(const void* W, int64_t N, int64_t K, int64_t ldw, const int32_t* oidx, int32_t K_o, int fmt16,
+                        float tensor_scale, void* Wpack, void* stream) {
+    int rc = check_g16("osc_pack_weight_g16", N, K, ldw, K_o, fmt16, tensor_scale);
+    if (rc) return rc;
+    if (N == 0) return OSC_OK;
+    REQUIRE(W && Wpack && (K_o == 0 || oidx), OSC_ERR_NULL, "osc_pack_weight_g16: null pointer");
+    REQUIRE(ldw % 8 == 0 && aligned(W, 16) && aligned(Wpack, 256), OSC_ERR_UNSUPPORTED,
+            "osc_pack_weight_g16: W rows must be 16-byte aligned and Wpack 256-byte aligned");
+    const Pack16Layout L = pack16_layout(N, K, K_o);
+    uint8_t* base = static_cast<uint8_t*>(Wpack);
+    if (K > 0) {
+        rc = launch_quant_fp4_g16(static_cast<const uint16_t*>(W), N, K, ldw, nullptr, 0, fmt16, tensor_scale, base + L.off_q,
+                                  base + L.off_s, nullptr, 0, as_stream(stream));
+        if (rc) return rc;
+    }
+    if (hipMemsetAsync(base + L.off_z, 0, 256, as_stream(stream)) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_pack_weight_g16: cannot clear the zero block");
+    return launch_gather_wl(static_cast<const uint16_t*>(W), N, K, ldw, oidx, K_o, reinterpret_cast<uint16_t*>(base + L.off_l),
+                            L.ldwl, as_stream(stream));
+}
+
+int osc_unpack_weight_g16(const void* Wpack, int64_t N, int64_t K, int32_t K_o, uint8_t* Wq, uint8_t* Ws16, void* WL,
+                          void* stream) {
+    REQUIRE(N >= 0 && K >= 0 && K % 64 == 0 && K_o >= 0, OSC_ERR_SHAPE, "osc_unpack_weight_g16: bad shape");
+    if (N == 0) return OSC_OK;
+    REQUIRE(Wpack, OSC_ERR_NULL, "osc_unpack_weight_g16: null pointer");
+    const Pack16Layout L = pack16_layout(N, K, K_o);
+    const uint8_t* base = static_cast<const uint8_t*>(Wpack);
+    hipStream_t st = as_stream(stream);
+    if (Wq && K > 0 && hipMemcpyAsync(Wq, base + L.off_q, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight_g16: copy of codes failed");
+    if (Ws16 && K > 0 && hipMemcpyAsync(Ws16, base + L.off_s, (size_t)N * (K / 16), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(OSC_ERR_HIP, "osc_unpack_weight_g16: copy of scales failed");
+    if (WL) return launch_unpack_wl(reinterpret_cast<const uint16_t*>(base + L.off_l), L.ldwl, N, K_o, static_cast<uint16_t*>(WL), st);
+    return OSC_OK;
+}
+
+int osc_dual_gemm_g16(const uint8_t* Xq, const uint8_t* Xs16, float x_tensor_scale, const void* B, int64_t ldb,
+                      const void* Wpack, float w_tensor_scale, int64_t M, int64_t N, int64_t K, int32_t K_o, int fmt16,
+                      void* Y, int y_dtype, int64_t ldy, void* stream) {
+    int rc = check_g16("osc_dual_gemm_g16", M, K, K, K_o, fmt16, x_tensor_scale);
+    if (rc) return rc;
+    if (fmt16 == OSC_FMT16_NVFP4)
+        REQUIRE(w_tensor_scale >= 0x1p-100f && w_tensor_scale <= 0x1p100f, OSC_ERR_SHAPE,
+                "osc_dual_gemm_g16: weight tensor scale %g outside [2^-100, 2^100]", (double)w_tensor_scale);
+    REQUIRE(N >= 0 && ldy >= N, OSC_ERR_SHAPE, "osc_dual_gemm_g16: N=%lld ldy=%lld", (long long)N, (long long)ldy);
+    REQUIRE(y_dtype == OSC_DT_F32 || y_dtype == OSC_DT_BF16, OSC_ERR_UNSUPPORTED, "osc_dual_gemm_g16: y_dtype %d", y_dtype);
+    REQUIRE(K % 256 == 0 && K > 0, OSC_ERR_UNSUPPORTED,
+            "osc_dual_gemm_g16: K=%lld must be a positive multiple of 256 (whole 128-byte lines of codes)", (long long)K);
+    REQUIRE(K_o == 0 || (ldb >= K_o && ldb % 64 == 0), OSC_ERR_UNSUPPORTED,
+            "osc_dual_gemm_g16: ldb=%lld must be a multiple of 64 and at least K_o=%d", (long long)ldb, K_o);
+    if (M == 0 || N == 0) return OSC_OK;
+    REQUIRE(Xq && Xs16 && Wpack && Y && (K_o == 0 || B), OSC_ERR_NULL, "osc_dual_gemm_g16: null pointer");
+    REQUIRE(aligned(Xq, 16) && aligned(Xs16, 16) && aligned(Wpack, 256) && (!B || aligned(B, 16)), OSC_ERR_UNSUPPORTED,
+            "osc_dual_gemm_g16: operands must be 16-byte aligned (the packed weight 256-byte)");
+    const Pack16Layout L = pack16_layout(N, K, K_o);
+    const uint8_t* base = static_cast<const uint8_t*>(Wpack);
+    return launch_dual_gemm_g16(Xq, Xs16, x_tensor_scale, static_cast<const uint16_t*>(B), K_o ? ldb : 0, base + L.off_q,
+                                base + L.off_s, reinterpret_cast<const uint16_t*>(base + L.off_l), L.ldwl, w_tensor_scale, M,
+                                N, K, K_o, fmt16, Y, y_dtype, ldy, as_stream(stream));
 }
 
 size_t osc_profile_workspace_bytes(int64_t H) { return H < 0 ? 0 : profile_scratch_bytes(H); }

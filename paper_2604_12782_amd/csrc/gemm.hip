@@ -32,6 +32,7 @@
 #include <type_traits>
 
 #include "osc_internal.h"
+#include "lds_dma.h"
 
 namespace osc {
 
@@ -69,13 +70,6 @@ struct KArgs {
     int grp_mode, grp_bm;
 };
 
-// 16-byte piece `c` (0..7) of row `r` sits at piece c ^ swz(r): lanes of one LDS access
-// (consecutive rows, same piece) then spread over all banks.
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 
 struct TilePos {
@@ -671,17 +665,6 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
     store_result<MODE, TM, TN>(a, tp, acc);
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
-}
-
-__device__ __forceinline__ void load_to_lds16(const uint8_t* src, uint8_t* lds_wave_base) {
-    // each lane's 16 bytes land at lds_wave_base + 16 * lane
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
-}
 
 // ------------------------------------------------------------------------------------------
 // DMA variant with full cache lines: every row contributes 128 contiguous bytes per stage (one
@@ -692,8 +675,6 @@ __device__ __forceinline__ void load_to_lds16(const uint8_t* src, uint8_t* lds_w
 // MFMAs of the first three quarters of the current one; the stage ends with "all loads landed"
 // and one barrier.  Needs operand rows that are whole 128-byte stages.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ int swz8(int r) { return (r & 7) ^ ((r >> 3) & 1); }
-__device__ __forceinline__ int st128_off(int row, int piece) { return row * 128 + ((piece ^ swz8(row)) << 4); }
 
 template <int MODE, int TM, int TN, int WN>
 __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {

@@ -98,6 +98,22 @@ int launch_profile_calibrate(const uint16_t* X, int64_t S, int64_t H, int64_t ld
                              int16_t* table, uint32_t* n_total, uint32_t* n_hit, float* density, float* cbar,
                              float* T_out, uint8_t* scratch, hipStream_t st);
 
+// 4-bit formats with a scale per 16 channels (g16.hip)
+struct Pack16Layout {
+    size_t off_q;   // uint8 [N, K/2]   E2M1 codes
+    size_t off_s;   // uint8 [N, K/16]  scale bytes, plain row-major
+    size_t off_l;   // bf16  [N, ldwl]  W_L transposed, zero padded
+    int64_t ldwl;   // round_up(K_o, 64)
+    size_t off_z;   // 256 bytes of zeros
+    size_t total;
+};
+Pack16Layout pack16_layout(int64_t N, int64_t K, int32_t K_o);
+int launch_quant_fp4_g16(const uint16_t* X, int64_t M, int64_t K, int64_t ldx, const int32_t* oidx, int32_t K_o, int fmt,
+                         float ts, uint8_t* Xq, uint8_t* Xs, uint16_t* B, int64_t ldb, hipStream_t st);
+int launch_dual_gemm_g16(const uint8_t* Xq, const uint8_t* Xs, float xts, const uint16_t* B, int64_t ldb, const uint8_t* Wq,
+                         const uint8_t* Ws, const uint16_t* WLt, int64_t ldwl, float wts, int64_t M, int64_t N, int64_t K,
+                         int32_t K_o, int fmt, void* Y, int y_dtype, int64_t ldy, hipStream_t st);
+
 struct GemmProblem {
     // activations
     const uint8_t* Xq;   // dual: codes [*, K/2]; fp8, mxfp8: codes [*, K]

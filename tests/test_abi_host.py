@@ -215,3 +215,19 @@ def test_profile_calibrate_arguments(lib):
     assert call(ws=FAKE + 64) == -4                          # workspace alignment
     assert call(G=48) == -4 and call(H=72, ldx=72) == -2     # group size; H % G
     assert call(S=0) == -2 and call(R=-1) == -2 and call(ldx=32) == -2
+
+
+def test_g16_arguments(lib):
+    q = lib.osc_quantize_act_g16
+    assert q(FAKE, 4, 96, 96, None, 0, 0, 1.0, FAKE, FAKE, None, 0, None) == -2      # K % 64
+    assert q(FAKE, 4, 128, 128, None, 0, 7, 1.0, FAKE, FAKE, None, 0, None) == -4    # format
+    assert q(FAKE, 4, 128, 128, None, 0, 1, 0.0, FAKE, FAKE, None, 0, None) == -2    # NVFP4 tensor scale
+    assert q(None, 4, 128, 128, None, 0, 0, 1.0, FAKE, FAKE, None, 0, None) == -1
+    assert q(None, 0, 128, 128, None, 0, 0, 1.0, None, None, None, 0, None) == 0
+    g = lib.osc_dual_gemm_g16
+    assert g(FAKE, FAKE, 1.0, None, 0, FAKE, 1.0, 4, 64, 128, 0, 0, FAKE, 0, 64, None) == -4   # K % 256
+    assert g(FAKE, FAKE, 1.0, None, 0, FAKE, 1.0, 4, 64, 256, 0, 0, FAKE, 0, 32, None) == -2   # ldy < N
+    assert g(FAKE, FAKE, 1.0, None, 0, FAKE, 1.0, 4, 64, 256, 0, 0, None, 0, 64, None) == -1
+    assert g(FAKE, FAKE, 1.0, FAKE, 40, FAKE, 1.0, 4, 64, 256, 16, 0, FAKE, 0, 64, None) == -4  # ldb % 64
+    assert lib.osc_packed_weight_g16_bytes(64, 256, 16) > 64 * 128 + 64 * 16 + 64 * 64 * 2
+    assert lib.osc_packed_weight_g16_bytes(64, 100, 0) == 0

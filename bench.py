@@ -635,6 +635,48 @@ def main():
                                            "weights": "cache-warm"},
                         "model": model}
         del pk, pu, qb, qs, _g
+    # Table 2's G = 16 row with 16 channels as the SCALE group as well (one E8M0 scale per 16), and NVFP4:
+    # formats the matrix core cannot multiply as 4-bit operands, served by the weight-streaming kernel
+    # that expands the codes in registers (decode regime), and, for the record, the same kernel at M tokens
+    tab16 = wl.rng(7016).integers(0, 16, (K_HID // 16, 1)).astype(np.int16)
+    oi16 = up(osc.osc_table_to_index_g(tab16, 16))
+    ko16 = int(oi16.numel())
+    for name, fmt, xts, wts in (("G=16 scale group 16 (E8M0)", osc.OSC_FMT16_E8M0, 1.0, 1.0),
+                                ("NVFP4", osc.OSC_FMT16_NVFP4, 1.0 / 64, 1.0 / 4096)):
+        pu = osc.osc_pack_weight_g16(Wu, oi16, fmt, wts)
+        qs = osc.osc_quantize_act_g16(X64, oi16, fmt, xts)
+        (ts, ts8), _g = b.graph_many([lambda i: osc.osc_dual_gemm_g16(*qs, pu, N_UP, K_HID, ko16, fmt, xts, wts, ydt, out=Y64),
+                                      lambda i: osc.osc_fp8_gemm(*f64, wu8, N_UP, K_HID, y_dtype=ydt, out=Y64)])
+        wbytes = N_UP * (K_HID // 2 + K_HID // 16 + ko16 * 2)
+        pk = osc.osc_pack_weight_g16(Wt, oi16, fmt, wts)
+        qb = osc.osc_quantize_act_g16(dX1, oi16, fmt, xts)
+        tq = b.time_one(lambda: osc.osc_quantize_act_g16(dX1, oi16, fmt, xts, out=qb), reps=5)
+        tb = b.time_one(lambda: osc.osc_dual_gemm_g16(*qb, pk, 4096, K_HID, ko16, fmt, xts, wts, ydt, out=Y["q"]), reps=2, rounds=3)
+        t2[name] = {"K_o": ko16, "scale_group": 16,
+                    f"M=64 N={N_UP}": {"osc_ms": round(ts, 4), "fp8_ms": round(ts8, 4), "speedup": round(ts8 / ts, 3),
+                                       "weights": "cache-warm", "weight_bytes": wbytes,
+                                       "model_memory_bound": round(N_UP * K_HID / wbytes, 3)},
+                    f"M={M} N=4096": {"osc_ms": round(tb, 4), "quant_ms": round(tq, 4),
+                                      "note": "codes expanded to bf16 in registers: bf16 matrix rate; the matrix core has no "
+                                              "4-bit mode with a scale per 16 channels or with E4M3 scales"},
+                    "model": 1.6}
+        # 16 tokens with the weights streamed from HBM (copies larger than the last-level cache, in turn):
+        # the regime where bytes per weight decide
+        X16 = dX1[:16].contiguous()
+        q16 = osc.osc_quantize_act_g16(X16, oi16, fmt, xts)
+        f16 = osc.osc_quantize_act(X16, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+        Y16 = torch.empty((16, N_UP), dtype=torch.bfloat16, device=dev)
+        n4 = max(2, -(-(320 << 20) // osc.osc_packed_weight_g16_bytes(N_UP, K_HID, ko16)))
+        n8 = max(2, -(-(320 << 20) // osc.osc_packed_weight_fp8_bytes(N_UP, K_HID)))
+        p4 = [pu] + [osc.osc_pack_weight_g16(Wu, oi16, fmt, wts) for _ in range(n4 - 1)]
+        p8 = [wu8] + [osc.osc_pack_weight_fp8(Wu) for _ in range(n8 - 1)]
+        (tc, tc8), _g2 = b.graph_many(
+            [lambda i: osc.osc_dual_gemm_g16(*q16, p4[i % n4], N_UP, K_HID, ko16, fmt, xts, wts, ydt, out=Y16),
+             lambda i: osc.osc_fp8_gemm(*f16, p8[i % n8], N_UP, K_HID, y_dtype=ydt, out=Y16)])
+        t2[name][f"M=16 N={N_UP}"] = {"osc_ms": round(tc, 4), "fp8_ms": round(tc8, 4), "speedup": round(tc8 / tc, 3),
+                                      "weights": "rotated through copies larger than the last-level cache",
+                                      "roofline": hbm(wbytes + 16 * N_UP * 2, tc), "model_memory_bound": round(N_UP * K_HID / wbytes, 3)}
+        del pu, qs, _g, pk, qb, p4, p8, _g2
     del Wt, Wu, wu8
     out["table2_sweep"] = t2
 

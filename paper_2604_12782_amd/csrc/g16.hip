@@ -9,7 +9,7 @@
 // the layer streams 0.56 bytes per weight instead of 1.  The GEMM here is that regime's kernel: the
 // 4-bit codes travel through HBM, L2 and LDS as they are and are expanded to bf16 in registers with
 // their scale folded in (E2M1 x E8M0 and E2M1 x E4M3 are exact in bf16), then multiplied on the bf16
-// matrix core into fp32; the tensor scales are applied once, before the bf16 branch is added.
+// (NVFP4: fp16) matrix core into fp32; the tensor scales are applied once, before the bf16 branch is added.
 #include "osc_internal.h"
 #include "lds_dma.h"
 #include "wave_util.h"
@@ -173,28 +173,44 @@ __device__ __forceinline__ float scale16_f32(uint32_t byte) {
     if (FMT == 0) return __builtin_bit_cast(float, byte ? byte << 23 : 0x00400000u);  // 2^(byte - 127)
     return __builtin_amdgcn_cvt_f32_fp8((int)byte, 0);
 }
-// two codes (byte SEL of w) times the block scale s, as two bf16.  The conversion instruction takes
-// only the exponent of its scale operand, which is all an E8M0 scale has; an E4M3 scale (NVFP4) is
-// applied by a single-precision multiplication instead, exact like the rounding back to bf16 (an
-// E2M1 value times an E4M3 value has at most six significant bits).
-template <int FMT, int SEL>
-__device__ __forceinline__ v2bf expand2(uint32_t w, float s) {
-    if (FMT == 0) return __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, s, SEL);
-    const uint32_t b = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, 1.0f, SEL));
-    const v2f p = {__builtin_bit_cast(float, b << 16) * s, __builtin_bit_cast(float, b & 0xffff0000u) * s};
-    return __builtin_convertvector(p, v2bf);
-}
-// 16 bytes of codes (32 channels, scale blocks s0 | s1) -> four registers sets of 8 bf16
+// Expansion of 16 bytes of codes (32 channels, scale blocks s0 | s1) into four operand registers
+// sets of 8 values each, the block scale folded in.
+//   format 0: the conversion instruction multiplies by a power of two (it takes only the exponent of
+//             its scale operand, which is all an E8M0 scale has): E2M1 x 2^e, exact in bf16.
+//   format 1: an E4M3 scale has a mantissa, so the codes become fp16 (exact) and are multiplied by the
+//             scale as packed fp16: an E2M1 value times an E4M3 value has at most six significant bits
+//             and lies in [2^-10, 2688], exact in fp16; the main phase then runs on the fp16 matrix
+//             core (the bf16 branch keeps the bf16 one; both accumulate into the same fp32 registers).
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 template <int FMT>
-__device__ __forceinline__ void expand32(const u32x4 c, uint32_t sbytes, v8bf (&out)[4]) {
+struct Operand;
+template <>
+struct Operand<0> {
+    typedef v8bf type;
+};
+template <>
+struct Operand<1> {
+    typedef v8h type;
+};
+template <int FMT>
+__device__ __forceinline__ void expand32(const u32x4 c, uint32_t sbytes, typename Operand<FMT>::type (&out)[4]) {
     const float s0 = scale16_f32<FMT>(sbytes & 0xffu), s1 = scale16_f32<FMT>((sbytes >> 8) & 0xffu);
     const uint32_t w[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const float s = t < 2 ? s0 : s1;
-        const v2bf p0 = expand2<FMT, 0>(w[t], s), p1 = expand2<FMT, 1>(w[t], s), p2 = expand2<FMT, 2>(w[t], s),
-                   p3 = expand2<FMT, 3>(w[t], s);
-        out[t] = (v8bf){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+        if constexpr (FMT == 0) {
+            const v2bf p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[t], s, 0), p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[t], s, 1),
+                       p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[t], s, 2), p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[t], s, 3);
+            out[t] = (v8bf){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+        } else {
+            const _Float16 sh = (_Float16)s;  // exact: every E4M3 value is an fp16 value
+            const v2h ss = {sh, sh};
+            const v2h p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w[t], 1.0f, 0) * ss, p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w[t], 1.0f, 1) * ss,
+                      p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w[t], 1.0f, 2) * ss, p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w[t], 1.0f, 3) * ss;
+            out[t] = (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+        }
     }
 }
 
@@ -275,11 +291,14 @@ __global__ void __launch_bounds__(64 * NW) gemm_g16_kernel(G16Args a) {
             for (int j = 0; j < 4; ++j) {
                 const u32x4 cw = *reinterpret_cast<const u32x4*>(src + st128_off(r, 2 * j + q));
                 const u32x4 cx = *reinterpret_cast<const u32x4*>(src + st128_off(32 + r, 2 * j + q));
-                v8bf fw[4], fx[4];
+                typename Operand<FMT>::type fw[4], fx[4];
                 expand32<FMT>(cw, swv[j] >> (16 * q), fw);
                 expand32<FMT>(cx, sxv[j] >> (16 * q), fx);
 #pragma unroll
-                for (int k = 0; k < 4; ++k) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[k], fw[k], acc, 0, 0, 0);
+                for (int k = 0; k < 4; ++k) {
+                    if constexpr (FMT == 0) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[k], fw[k], acc, 0, 0, 0);
+                    else acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fx[k], fw[k], acc, 0, 0, 0);
+                }
             }
         } else {
             if (!scaled) {

@@ -323,6 +323,61 @@ def moe_rows(b):
     return out
 
 
+def streaming_rows(b, M=8192):
+    """The HBM-side kernels once more on their bench shapes, for profiler runs: every quantiser, the producer
+    fusions and the offline profiling kernels, each a few launches over a ring of inputs (event times in ms)."""
+    torch, osc, wl = b.torch, b.osc, b.wl
+    K, K_FF = K_HID, 12288
+    X, table = wl.activations_persistent(2001, M, K, 2)
+    oidx = b.up(osc.osc_table_to_index(table))
+    ring = [b.up(X) for _ in range(5)]
+    gam = b.up(wl.to_bf16_bits((1.0 + 0.1 * wl.rng(2200).standard_normal(K)).astype(np.float32)))
+    q = osc.osc_quantize_act(ring[0], oidx)
+    q64 = osc.osc_quantize_act(ring[0], oidx, osc.OSC_FMT_MXFP4_OSC_G64)
+    f8 = osc.osc_quantize_act(ring[0], None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    dq = osc.osc_quantize_act_dynamic(ring[0], want_idx=True)
+    g16 = [osc.osc_quantize_act_g16(ring[0], oidx, f, 1.0 / 64 if f == osc.OSC_FMT16_NVFP4 else 1.0)
+           for f in (osc.OSC_FMT16_E8M0, osc.OSC_FMT16_NVFP4)]
+    acc = torch.zeros(1, dtype=torch.float64, device=b.dev)
+    T = osc.osc_profile_threshold(osc.osc_profile_abs_sum(ring[0]), M * K, 5.0)
+    hist = torch.zeros((K // 32, 32), dtype=torch.int32, device=b.dev)
+    turn = [0]
+
+    def nxt():
+        turn[0] = (turn[0] + 1) % len(ring)
+        return ring[turn[0]]
+
+    res = {}
+    names = ["quant_mxfp4_osc", "quant_mxfp4_osc_g64", "quant_fp8_token", "quant_mxfp4_dynamic", "rmsnorm_quant_mxfp4",
+             "quant_fp4_g16_e8m0", "quant_fp4_g16_nvfp4", "profile_abs_sum", "profile_hist"]
+    fns = [lambda: osc.osc_quantize_act(nxt(), oidx, out=q),
+           lambda: osc.osc_quantize_act(nxt(), oidx, osc.OSC_FMT_MXFP4_OSC_G64, out=q64),
+           lambda: osc.osc_quantize_act(nxt(), None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f8),
+           lambda: osc.osc_quantize_act_dynamic(nxt(), out=dq),
+           lambda: osc.osc_rmsnorm_quantize_act(nxt(), gam, 1e-6, oidx, out=(q[0], q[1], q[2], None)),
+           lambda: osc.osc_quantize_act_g16(nxt(), oidx, osc.OSC_FMT16_E8M0, 1.0, out=g16[0]),
+           lambda: osc.osc_quantize_act_g16(nxt(), oidx, osc.OSC_FMT16_NVFP4, 1.0 / 64, out=g16[1]),
+           lambda: osc.osc_profile_abs_sum(nxt(), acc),
+           lambda: osc.osc_profile_hist(nxt(), T, 32, hist)]
+    for n, t in zip(names, b.time_many(fns, reps=2 * len(ring))):
+        res[n + f" {M}x{K}"] = round(t, 4)
+    del ring, q, q64, f8, dq, g16
+    Xf = b.up(wl.activations_diffuse(3003, M, K_FF))
+    m8 = osc.osc_quantize_act(Xf, None, osc.OSC_FMT_MXFP8)
+    t8 = osc.osc_quantize_act(Xf, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    gen = torch.Generator(device=b.dev)
+    gen.manual_seed(3005)
+    gu = (torch.randn((M, 2 * K_FF), generator=gen, device=b.dev) * 2).to(torch.bfloat16).view(torch.uint16)
+    names = ["quant_mxfp8", "quant_fp8_token", "swiglu_quant_mxfp8", "swiglu_quant_fp8"]
+    fns = [lambda: osc.osc_quantize_act(Xf, None, osc.OSC_FMT_MXFP8, out=m8),
+           lambda: osc.osc_quantize_act(Xf, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=t8),
+           lambda: osc.osc_swiglu_quantize_act(gu[:, :K_FF], gu[:, K_FF:], out=(m8[0], m8[1], None)),
+           lambda: osc.osc_swiglu_quantize_act_fp8(gu[:, :K_FF], gu[:, K_FF:], out=(t8[0], t8[1], None))]
+    for n, t in zip(names, b.time_many(fns, reps=5)):
+        res[n + f" {M}x{K_FF}"] = round(t, 4)
+    return res
+
+
 def vendor_library_yardstick(b, M, N, K):
     """What the GEMM library that ships with the framework reaches on the dominant shape (plain MXFP4 with
     unit scales, FP8 with one scale per tensor; random codes).  Context beside the peaks, not part of the
@@ -367,9 +422,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip most rows of the shapes table (profiler runs)")
     ap.add_argument("--only-step", action="store_true", help="the headline step only (profiler runs)")
-    ap.add_argument("--section", choices=["cfg3", "moe"], default=None,
-                    help="profiler runs: only the launches of configs[2] (W1|W3 dual GEMM, W_2 FP8 and MXFP8 GEMMs) "
-                         "or of configs[3] (grouped GEMMs), a few times each")
+    ap.add_argument("--section", choices=["cfg3", "moe", "streaming"], default=None,
+                    help="profiler runs: only the launches of configs[2] (W1|W3 dual GEMM, W_2 FP8 and MXFP8 GEMMs), "
+                         "of configs[3] (grouped GEMMs), or of the streaming kernels (quantisers, producer fusions, "
+                         "offline profiling) at their bench shapes, a few times each")
     ap.add_argument("--detail", action="store_true", help="per-kernel times on stderr")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a counter yardstick for profiler runs)")
@@ -395,6 +451,9 @@ def main():
 
     if args.section == "moe":
         print(json.dumps({"shapes_moe": moe_rows(b)}))
+        return
+    if args.section == "streaming":
+        print(json.dumps({"streaming": streaming_rows(b)}))
         return
     if args.section == "cfg3":
         res = {"shapes": shapes_table(b, only="cfg3")}

@@ -150,7 +150,8 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  * scale = 1; otherwise scale = amax/448 and Xq[m,k] = e4m3(X[m,k] * (448/amax)),
  * every operation one IEEE single-precision operation, e4m3 rounding to nearest
  * even.  oidx, K_o, B, ldb are ignored; K need not be a multiple of 32 but
- * must be a multiple of 8.
+ * must be a multiple of 8, and K <= 32768 (a row is held in registers between the
+ * two phases; larger K: OSC_ERR_UNSUPPORTED).
  *   Xq    uint8 [M, K] e4m3 codes;  Xs  float [M] scales
  *
  * fmt = OSC_FMT_MXFP4_OSC_G64: OSC_FMT_MXFP4_OSC with scale groups of 64 channels (Section
@@ -160,8 +161,8 @@ int osc_unpack_weight_fp8(const void *W8pack, int64_t N, int64_t K, uint8_t *W8,
  * the result feeds osc_dual_gemm as it is.  K % 64 == 0.  The table normally names one
  * channel per 64 (osc_table_to_index_g with G = 64), but any ascending list is accepted.
  *
- * fmt = OSC_FMT_MXFP8: the 8-bit micro-scaling form of the same fallback (Section 3.4:
- * "FP8 or equivalent 8-bit micro-scaling formats"; Section 4.1, implementation
+ * fmt = OSC_FMT_MXFP8: the 8-bit micro-scaling form of the same fallback (Section 3.4
+ * allows an 8-bit micro-scaling format in place of FP8; Section 4.1, implementation
  * details: MXFP8 for the W_2 inputs).  Every 32-channel group gets an E8M0 scale with
  * exponent floor(log2(amax)) - 8 (code 0 when amax is zero or below 2^-118) and E4M3
  * elements X / 2^exponent rounded to nearest even, saturating at +-448, sign kept.
@@ -325,8 +326,8 @@ int osc_quantize_act_dynamic(const void *X, int64_t M, int64_t K, int64_t ldx, u
 
 /*
  * The OSC quantiser and the dual-path layer for the 4-bit formats whose scale group is 16 channels
- * (Section 3.1: group sizes G in {16, 32, 64}, "for compatibility with group-wise micro-scaling
- * formats"; Table 2, row G = 16; the abstract and the conclusion name NVFP4).  The paper gives no
+ * (Section 3.1: group sizes G in {16, 32, 64}, chosen to line up with the scale groups of
+ * micro-scaling formats; Table 2, row G = 16; the abstract and the conclusion name NVFP4).  The paper gives no
  * arithmetic for either; this library reads them as follows.
  *   OSC_FMT16_E8M0   E2M1 elements, one E8M0 scale per 16 channels with exponent floor(log2 amax) - 2
  *                    (code 0 for amax zero or below 2^-124); elements X / 2^exponent, nearest even,

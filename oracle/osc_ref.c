@@ -44,8 +44,8 @@
  *   ref_grouped_*           the same two GEMMs for E independent experts
  *                           (MoE model of Section 4.1)
  *   ref_quantize_mxfp8      the 8-bit micro-scaling form of the fallback
- *                           (Section 3.4 "or equivalent 8-bit micro-scaling
- *                           formats"; Section 4.1 implementation details:
+ *                           (Section 3.4 allows an 8-bit micro-scaling format
+ *                           there; Section 4.1 implementation details:
  *                           MXFP8 for the W_2 inputs), read as OCP MX v1.0
  *                           MXFP8 with E4M3 elements: one E8M0 scale per 32
  *                           elements, shared exponent floor(log2 amax) - 8,
@@ -687,8 +687,8 @@ int ref_mxfp8_gemm(const uint8_t *Xq, const uint8_t *Xs, const uint8_t *Wq, cons
 }
 
 /* ---- 4-bit formats with scale groups of 16 channels --------------------------------------- *
- * Section 3.1 cuts the channels into groups of G in {16, 32, 64} "for compatibility with
- * group-wise micro-scaling formats"; Table 2 has a G = 16 row; the abstract and the conclusion name
+ * Section 3.1 cuts the channels into groups of G in {16, 32, 64} so that they line up
+ * with the scale groups of micro-scaling formats; Table 2 has a G = 16 row; the abstract and the conclusion name
  * NVFP4.  The paper gives no arithmetic for either; the readings taken here:
  *   fmt 0 (E8M0 per 16): the MX rule on blocks of 16: shared exponent floor(log2 amax) - 2 as an
  *          E8M0 code, E2M1 elements x / 2^e rounded to nearest even, saturating;

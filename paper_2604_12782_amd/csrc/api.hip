@@ -314,7 +314,11 @@ int osc_rmsnorm_quantize_act(const void* X, const void* gamma, float eps, int64_
     REQUIRE(K_o == 0 || (oidx && B), OSC_ERR_NULL, "osc_rmsnorm_quantize_act: K_o > 0 needs oidx and B");
     REQUIRE(ldx % 8 == 0 && aligned(X, 16) && aligned(gamma, 16) && aligned(Xq, 4) && aligned(Xs, 4) && aligned(Xn, 16),
             OSC_ERR_UNSUPPORTED, "osc_rmsnorm_quantize_act: misaligned pointer or ldx %% 8 != 0");
-    if (B) REQUIRE(ldb >= 0, OSC_ERR_SHAPE, "osc_rmsnorm_quantize_act: negative ldb");
+    if (B) {
+        REQUIRE(ldb >= 0, OSC_ERR_SHAPE, "osc_rmsnorm_quantize_act: negative ldb");
+        REQUIRE(ldb % 8 == 0 && aligned(B, 16), OSC_ERR_UNSUPPORTED,
+                "osc_rmsnorm_quantize_act: B must be 16-byte aligned with ldb %% 8 == 0");
+    }
     return launch_rmsnorm_quant_mxfp4(static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(gamma), eps, M, K,
                                       ldx, oidx, K_o, Xq, static_cast<uint8_t*>(Xs), static_cast<uint16_t*>(B),
                                       B ? ldb : 0, static_cast<uint16_t*>(Xn), as_stream(stream));

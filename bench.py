@@ -35,6 +35,16 @@ PROJ = (("q", 4096), ("k", 1024), ("v", 1024), ("o", 4096))
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "dual_gemm_8192x4096x4096__hbm_traffic.txt")
 
 
+def profile_figure(fname, key):
+    """A figure from a tracked rocprofv3 summary under profiles/ (`KEY = value` on a line of its own): a
+    profiler reading that this script cannot take itself.  None when the summary or the line is absent."""
+    try:
+        m = re.search(r"^" + key + r"\s*=\s*([0-9.eE+]+)", open(os.path.join(ROOT, "profiles", fname)).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def dominant_traffic_bytes():
     """Bytes between L2 and the fabric per launch of the dominant kernel, from the tracked rocprofv3
     FETCH_SIZE / WRITE_SIZE summary (a profiler reading: this script cannot measure it itself).
@@ -659,6 +669,14 @@ def main():
     ms_fused = b.time_one(fused_ring, reps=2 * nring)
     out["fused_rmsnorm_quant"] = {"shape": f"M={M} K={K_HID} K_o={K_o}", "ms": round(ms_fused, 4),
                                   "roofline": hbm(quant_bytes, ms_fused), "unfused_quant_ms": round(ms_quant, 4)}
+    # this kernel is limited by vector instruction issue rather than by memory: its instruction count (a
+    # counter reading kept under profiles/) against the chip's issue rate, 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+    insts = profile_figure("streaming_kernels__traffic_and_valu.txt", "RMSNORM_QUANT_VALU_WAVE_INSTS_PER_LAUNCH")
+    if insts and M == 8192:
+        peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        ach = insts * 64 / (ms_fused * 1e-3) / 1e12
+        out["fused_rmsnorm_quant"]["alu_roofline"] = {"bound": "alu", "achieved": round(ach, 2), "peak": round(peak, 2),
+                                                      "unit": "T lane-instructions/s", "frac": round(ach / peak, 4)}
 
     # Table 2 of the paper on this machine: one protected channel per group of G = 16, 32, 64
     # (K_o = K/G), a compute-bound GEMM (M tokens, 4096 x 4096) and a decode-sized one (64 tokens,

@@ -502,18 +502,16 @@ def main():
     f1 = osc.osc_quantize_act(dX1, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
     f2 = osc.osc_quantize_act(dX2, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
     Y = {n: torch.empty((M, N), dtype=torch.bfloat16, device=dev) for n, N in PROJ}
-    dom = []  # event pairs around the dominant kernel (q projection), on the launch stream
-
-    def step(timed=False):
+    def step(events=None):
         osc.osc_quantize_act(dX1, oidx1, out=q1)
         for n, N in PROJ[:3]:
-            if timed and n == "q":
+            if events is not None and n == "q":
                 e0, e1 = ev(), ev()
                 e0.record()
             osc.osc_dual_gemm(*q1, packs[n], N, K_HID, K_o, ydt, out=Y[n])
-            if timed and n == "q":
+            if events is not None and n == "q":
                 e1.record()
-                dom.append((e0, e1))
+                events.append((e0, e1))
         osc.osc_quantize_act(dX2, oidx2, out=q2)
         osc.osc_dual_gemm(*q2, packs["o"], 4096, K_HID, K_o, ydt, out=Y["o"])
 
@@ -524,18 +522,38 @@ def main():
         osc.osc_quantize_act(dX2, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f2)
         osc.osc_fp8_gemm(*f2, packs8["o"], 4096, K_HID, y_dtype=ydt, out=Y["o"])
 
-    def timed_loop(fn, steps, warmup, **kw):
+    def timed_loop(fn, steps, warmup):
+        # the clock needs tens of milliseconds of load to settle where sustained work puts it: a fixed
+        # 40 ms of the same step first, then the W warm-up steps, then exactly K timed steps
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.040:
+            for _ in range(8):
+                fn()
+            torch.cuda.synchronize()
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            fn(**kw)
+            fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    ms_step = timed_loop(step, args.steps, args.warmup, timed=True)
-    dom_ms = float(np.mean([a.elapsed_time(c) for a, c in dom]))
+    ms_step = timed_loop(step, args.steps, args.warmup)
+    # The dominant kernel (the q projection): HIP events on the launch stream around batches of K launches
+    # with the step's own operands.  An event pair around a single launch inside the step would put two
+    # event markers next to the kernel; each costs about 6 us of dispatch gap (the kernel trace under
+    # profiles/ shows them), which would slow the timed steps by 4 % and add 12 us to an 88 us kernel.
+    # That reading is still taken, over a few extra untimed steps, and reported beside the batch figure.
+    def q_launch():
+        osc.osc_dual_gemm(*q1, packs["q"], 4096, K_HID, K_o, ydt, out=Y["q"])
+
+    dom_ms = b.time_one(q_launch, reps=max(args.steps, 1), rounds=3)
+    dom_ev = []
+    for _ in range(min(args.steps, 20)):
+        step(dom_ev)
+    torch.cuda.synchronize()
+    dom_ms_in_step = float(np.mean([a.elapsed_time(c) for a, c in dom_ev]))
     flops = sum(2.0 * M * N * K_HID for _, N in PROJ)
     value = flops / (ms_step * 1e-3) / 1e12
     dom_tflops = 2.0 * M * 4096 * K_HID / (dom_ms * 1e-3) / 1e12
@@ -552,7 +570,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(dom_tflops, 1), "peak": PEAK_MXFP4_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_MXFP4_TFLOPS, 4),
                      "traffic": dominant_traffic_bytes() if M == 8192 else None,
-                     "kernel": f"dual-path GEMM M={M} N=4096 K=4096 K_o={K_o}", "avg_ms": round(dom_ms, 4)},
+                     "kernel": f"dual-path GEMM M={M} N=4096 K=4096 K_o={K_o}", "avg_ms": round(dom_ms, 4),
+                     "avg_ms_single_launch_events_in_step": round(dom_ms_in_step, 4)},
         "frac_mxfp4_peak_whole_step": round(value / PEAK_MXFP4_TFLOPS, 4),
     }
     if args.only_step:

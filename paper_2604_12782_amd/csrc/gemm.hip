@@ -2062,7 +2062,13 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     // 256-row tiles when they fill the chip, else 128x128, else (fewer than one tile per CU) 64x128
     const int64_t t128 = ((rows + 127) / 128) * ((p.N + 127) / 128) * (grouped ? p.E : 1);
     const int64_t t128_full = MODE == MODE_DUAL ? 512 : 257;  // measured crossover: two (8-bit: one) 128x128 tiles per CU
-    int tm = rows <= 64 ? 1 : (rows > 128 && t256 >= 256) ? 4 : (t128 < t128_full ? 1 : 2);
+    // 256-row tiles also when they leave CUs idle but the 128 x 128 tiles would need a second round (two of
+    // them are resident per CU): 1024 x 12288 x 4096 takes 42.7 us on 192 tiles of 256 x 256 and 51 us on 768
+    // of 128 x 128, 768 x 12288 40 against 48 us; with one round of small tiles those are ahead (2048 x 4096:
+    // 28.6 against 39 us).  Measured for single problems; grouped ones keep the plain rule.
+    const int ncu_hint = cu_count();
+    const bool second_round = !grouped && ncu_hint > 0 && t128 > 2 * (int64_t)ncu_hint;
+    int tm = rows <= 64 ? 1 : (rows > 128 && (t256 >= 256 || second_round)) ? 4 : (t128 < t128_full ? 1 : 2);
     if (MODE == MODE_MX8 && !lines)  // implemented in the DMA and skinny kernels only
         return fail(OSC_ERR_UNSUPPORTED, "mxfp8 gemm: K must be a multiple of 128");
     int kind = lines ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
@@ -2070,7 +2076,9 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     // past the last whole tile go to a second launch of the DMA kernel
     const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
-    if (kind == 1 && pipe_ok && tm == 4) kind = 2;
+    // (with at most one tile per CU there is no next tile to run ahead into, and the eight wavefronts of the
+    // DMA kernel are 6 % faster: 4096 x 4096 x 4096 in 46.5 against 49.4 us)
+    if (kind == 1 && pipe_ok && tm == 4 && t256 > 256) kind = 2;
     // The weight-streaming kernel (one workgroup per 32 output channels and 32 rows) also wins for a few
     // hundred rows as long as its grid stays small: a tiled launch of so few tiles leaves most CUs
     // idle (128 x 4096 x 4096: 17 us on 32 tiles of 128 x 128, 6.4 us on 512 streaming workgroups).

@@ -16,7 +16,8 @@ enum {
     OSC_TUNE_GEMM_KERNEL = 1,      /* 0 staged, 1 DMA, 2 persistent, 3 skinny (ignored where a kernel
                                       cannot serve the shape) */
     OSC_TUNE_GROUPED_ONE_TILE = 2, /* 1: grouped 8-bit GEMMs keep one tile per workgroup */
-    OSC_TUNE_SWIGLU_TABLE = 3      /* 0 / 1: SwiGLU fusions evaluate silu per element / look it up */
+    OSC_TUNE_SWIGLU_TABLE = 3,     /* 0 / 1: SwiGLU fusions evaluate silu per element / look it up */
+    OSC_TUNE_GEMM_KSPLIT = 4       /* 0 / 1: dual-path 64 x 128 tiles never / always split their K loop over two wavefront groups */
 };
 
 /* Errors: OSC_ERR_UNSUPPORTED for an unknown knob.  Any negative value means "automatic". */

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     osc_pack_weight_fp8, osc_packed_weight_bytes, osc_packed_weight_fp8_bytes, osc_quantize_act,
     osc_table_to_index, osc_unpack_weight, osc_unpack_weight_fp8, osc_version,
     osc_mxfp8_gemm, osc_pack_weight_mxfp8, osc_packed_weight_mxfp8_bytes, osc_unpack_weight_mxfp8,
-    osc_quantize_act_dynamic, osc_rmsnorm_quantize_act, osc_swiglu_quantize_act, osc_tuning_set, osc_tuning_get, OSC_TUNE_GEMM_TILE, OSC_TUNE_GEMM_KERNEL, OSC_TUNE_GROUPED_ONE_TILE, OSC_TUNE_SWIGLU_TABLE, osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table, osc_profile_calibrate, osc_profile_calibrate_static, osc_profile_workspace_bytes,
+    osc_quantize_act_dynamic, osc_rmsnorm_quantize_act, osc_swiglu_quantize_act, osc_tuning_set, osc_tuning_get, OSC_TUNE_GEMM_TILE, OSC_TUNE_GEMM_KERNEL, OSC_TUNE_GROUPED_ONE_TILE, OSC_TUNE_SWIGLU_TABLE, OSC_TUNE_GEMM_KSPLIT, osc_profile_abs_sum, osc_profile_threshold, osc_profile_hist, osc_profile_table, osc_profile_calibrate, osc_profile_calibrate_static, osc_profile_workspace_bytes,
     osc_pack_weight_g, osc_table_to_index_g, OSC_FMT16_E8M0, OSC_FMT16_NVFP4, osc_quantize_act_g16,
     osc_packed_weight_g16_bytes, osc_pack_weight_g16, osc_unpack_weight_g16, osc_dual_gemm_g16, osc_swiglu_quantize_act_fp8)

@@ -474,6 +474,7 @@ def osc_rmsnorm_quantize_act(X, gamma, eps=1e-6, oidx=None, ldb=None, want_norm=
 
 
 OSC_TUNE_GEMM_TILE, OSC_TUNE_GEMM_KERNEL, OSC_TUNE_GROUPED_ONE_TILE, OSC_TUNE_SWIGLU_TABLE = 0, 1, 2, 3
+OSC_TUNE_GEMM_KSPLIT = 4
 
 
 def osc_tuning_set(knob, value):

@@ -676,8 +676,14 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
 // and one barrier.  Needs operand rows that are whole 128-byte stages.
 // ------------------------------------------------------------------------------------------
 
-template <int MODE, int TM, int TN, int WN>
-__global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
+template <int MODE, int TM, int TN, int WN, int KS = 1>
+__global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
+    // KS = 2 (dual path, small tiles): two groups of 2 x WN wavefronts share a tile and split its reduction
+    // axis, group g taking stages g, g + 2, ... through LDS stages of its own; the partial sums meet in LDS
+    // at the end.  A launch of at most one small tile per CU leaves one wavefront on every SIMD, and a stage
+    // is then a chain of latencies (LDS read, eight MFMAs, barrier) with nothing to overlap it; the second
+    // group fills those gaps and halves the number of stages each wavefront walks through.
+    static_assert(KS == 1 || (KS == 2 && MODE == MODE_DUAL), "K split: dual path, two groups");
     // 2 x WN wavefronts; WN = 4 puts two wavefronts on every SIMD: while one waits for its LDS
     // reads or sits between two dependent MFMAs the other keeps the matrix core busy
     constexpr int NWV = 2 * WN;                // wavefronts
@@ -689,10 +695,12 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
     constexpr int NSB = (NBLK + NWV - 1) / NWV;  // scale DMA loads per wave and stage (one block each)
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile does not split over the wavefronts");
     constexpr int SCL = NBLK * 256;            // bytes of scale words per stage: [block][half step][32 rows][4]
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
+    const int grp = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x / (128 * WN)) : 0;
+    uint8_t* const lds = lds_all + grp * (2 * STG + 2 * SCL);  // this group's two stages and their scale words
     uint8_t* const scl = lds + 2 * STG;        // scale words of the two stages
 
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = KS > 1 ? (int)threadIdx.x % (128 * WN) : (int)threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
     const TilePos tp = locate_tile<BM, BN>(a);
     if (!tp.valid) return;
@@ -805,8 +813,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
     }
 
     // ---- prologue ---------------------------------------------------------------------------------
-    if ((MODE == MODE_DUAL || MODE == MODE_MX8) && nTA > 0) OSC_D2_SCALES(0, 0)
-    OSC_D2_ANY(0, 0, 0, LA, 0, LB)
+    if ((MODE == MODE_DUAL || MODE == MODE_MX8) && grp < nTA) OSC_D2_SCALES(grp, 0)
+    OSC_D2_ANY(grp, 0, 0, LA, 0, LB)
     wait_vmcnt<0>();
     __syncthreads();
     u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
@@ -823,17 +831,17 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
         int sa[TM], sb[TN], ta[TM], tb[TN];                                                    \
         OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
         OSC_D2_READ_SCALES(buf, 0, sa, sb)                                                     \
-        if ((T_) + 1 < nTA) OSC_D2_SCALES((T_) + 1, buf ^ 1)                                   \
-        REFILL_((T_) + 1, buf ^ 1, 0, D2_R1A, 0, D2_R1B)                                       \
+        if ((T_) + KS < nTA) OSC_D2_SCALES((T_) + KS, buf ^ 1)                                   \
+        REFILL_((T_) + KS, buf ^ 1, 0, D2_R1A, 0, D2_R1B)                                       \
         OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
         OSC_MFMA_FP4(0, fa0, fb0, sa, sb)                                                      \
         spread_hint<TM * TN, TM + TN, 0, NSB + D2_R1A + D2_R1B>();                             \
-        REFILL_((T_) + 1, buf ^ 1, D2_R1A, D2_R2A, D2_R1B, D2_R2B)                             \
+        REFILL_((T_) + KS, buf ^ 1, D2_R1A, D2_R2A, D2_R1B, D2_R2B)                             \
         OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
         OSC_D2_READ_SCALES(buf, 1, ta, tb)                                                     \
         OSC_MFMA_FP4(1, fa1, fb1, sa, sb)                                                      \
         spread_hint<TM * TN, 2 * (TM + TN), 0, D2_R2A - D2_R1A + D2_R2B - D2_R1B>();           \
-        REFILL_((T_) + 1, buf ^ 1, D2_R2A, LA, D2_R2B, LB)                                     \
+        REFILL_((T_) + KS, buf ^ 1, D2_R2A, LA, D2_R2B, LB)                                     \
         OSC_F2(buf, 4 + 2 * q + 1, fa1, fb1)                                                   \
         OSC_MFMA_FP4(0, fa0, fb0, ta, tb)                                                      \
         spread_hint<TM * TN, TM + TN, 0, LA - D2_R2A + LB - D2_R2B>();                         \
@@ -847,11 +855,11 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
 #define OSC_D2_STAGE_BF16(T_)                                                                  \
     {                                                                                          \
         OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
-        OSC_D2_BRANCH((T_) + 1, buf ^ 1, 0, LA / 2, 0, LB / 2)                                 \
+        OSC_D2_BRANCH((T_) + KS, buf ^ 1, 0, LA / 2, 0, LB / 2)                                 \
         OSC_F2(buf, 2 * q + 1, fa1, fb1)                                                       \
         OSC_MFMA_BF16(fa0, fb0)                                                                \
         spread_hint<TM * TN, TM + TN, 0, LA / 2 + LB / 2>();                                   \
-        OSC_D2_BRANCH((T_) + 1, buf ^ 1, LA / 2, LA, LB / 2, LB)                               \
+        OSC_D2_BRANCH((T_) + KS, buf ^ 1, LA / 2, LA, LB / 2, LB)                               \
         OSC_F2(buf, 4 + 2 * q, fa0, fb0)                                                       \
         OSC_MFMA_BF16(fa1, fb1)                                                                \
         spread_hint<TM * TN, TM + TN, 0, LA - LA / 2 + LB - LB / 2>();                         \
@@ -985,15 +993,41 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2_kernel(KArgs a) {
 #pragma unroll 1
         for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8(T)
     } else {
-        int T = 0;
+        int T = grp;
 #pragma unroll 1
-        for (; T + 1 < nTA; ++T) OSC_D2_STAGE_FP4(T, OSC_D2_MAIN)
+        for (; T + KS < nTA; T += KS) OSC_D2_STAGE_FP4(T, OSC_D2_MAIN)
         if (T < nTA) {
             OSC_D2_STAGE_FP4(T, OSC_D2_ANY)
-            ++T;
+            T += KS;
         }
 #pragma unroll 1
-        for (; T < nT; ++T) OSC_D2_STAGE_BF16(T)
+        for (; T < nT; T += KS) OSC_D2_STAGE_BF16(T)
+        if constexpr (KS > 1) {
+            // every stage ends in a workgroup barrier: the group with one stage fewer keeps the count even
+            if (grp == 1 && (nT & 1)) __syncthreads();
+        }
+    }
+    if constexpr (KS > 1) {
+        // partial sums of group 1 -> LDS -> group 0 (every group has waited for its own last DMA request)
+        constexpr int GT_ = 128 * WN;
+        __syncthreads();
+        float* const red = reinterpret_cast<float*>(lds_all);
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int k2 = 0; k2 < 16; ++k2) red[((i * TN + j) * 16 + k2) * GT_ + t] = acc[i][j][k2];
+        }
+        __syncthreads();
+        if (grp != 0) return;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int k2 = 0; k2 < 16; ++k2) acc[i][j][k2] += red[((i * TN + j) * 16 + k2) * GT_ + t];
     }
     store_result<MODE, TM, TN, WN>(a, tp, acc);
 }
@@ -1943,10 +1977,10 @@ static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st)
     return check_launch("gemm_kernel");
 }
 
-template <int MODE, int TM, int TN, int WN = 2>
+template <int MODE, int TM, int TN, int WN = 2, int KS = 1>
 static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
-    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
+    const size_t smem = ((size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2) * KS;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
     if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
@@ -1957,13 +1991,13 @@ static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st
     const int64_t grid = tiles_m * a.tiles_n;
     if (grid <= 0) return OSC_OK;
     if (grid > 0x7fffffff) return fail(OSC_ERR_UNSUPPORTED, "gemm: too many tiles");
-    auto kern = gemm_dma2_kernel<MODE, TM, TN, WN>;
+    auto kern = gemm_dma2_kernel<MODE, TM, TN, WN, KS>;
     if (smem > 64 * 1024) {
         static unsigned char lds_done[MAX_DEVICES];
         static size_t lds_reserved[MAX_DEVICES];
         if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(128 * WN * KS), smem, st, a);
     return check_launch("gemm_dma2_kernel");
 }
 
@@ -2080,11 +2114,12 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     // DMA kernel are 6 % faster: 4096 x 4096 x 4096 in 46.5 against 49.4 us)
     if (kind == 1 && pipe_ok && tm == 4 && t256 > 256) kind = 2;
     // The weight-streaming kernel (one workgroup per 32 output channels and 32 rows) also wins for a few
-    // hundred rows as long as its grid stays small: a tiled launch of so few tiles leaves most CUs
-    // idle (128 x 4096 x 4096: 17 us on 32 tiles of 128 x 128, 6.4 us on 512 streaming workgroups).
-    // Above about a thousand workgroups the 64 x 128 tiles of the DMA kernel are as fast or faster.
+    // hundred rows as long as its grid is resident at once (two workgroups per CU): a tiled launch of so
+    // few tiles leaves most CUs idle (128 x 4096 x 4096: 11.8 us on 64 x 128 tiles, 6.8 us on 512 streaming
+    // workgroups).  Beyond 512 workgroups it needs a second round (1024 x 1024 x 4096, 1024 workgroups:
+    // 12.6 us) and the 64 x 128 tiles with their K loop split over two wavefront groups are ahead (9.9 us).
     const int64_t skinny_wgs = ((p.N + 31) / 32) * ((p.M + 31) / 32);
-    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 1024);
+    const bool skinny_ok = lines && !grouped && !p.row_map && p.M >= 1 && (p.M <= 64 || skinny_wgs <= 512);
     if (skinny_ok) kind = 3;
     if (const int t_tile = tuning(TUNE_GEMM_TILE), t_kern = tuning(TUNE_GEMM_KERNEL); t_tile >= 0 || t_kern >= 0) {
         // test and tuning overrides (osc_tuning.h); a kernel that cannot serve the shape is not forced
@@ -2146,6 +2181,17 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         // 256-row tiles run on eight wavefronts (2 x 4, 128x64 each): 6-8 % faster than four, the second
         // wavefront of a SIMD fills the issue gaps of the first
         if (tm == 4) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
+        if constexpr (MODE == MODE_DUAL) {
+            // at most one 64 x 128 tile per CU: two groups of wavefronts per tile, each taking every second stage
+            // (2048 x 1024 x 4096: 12.7 -> 11.0 us, 128 x 12288 x 4096: 16.8 -> 13.2 us; with more tiles than CUs
+            // the doubled LDS footprint costs a round: 192 x 12288: 17.2 -> 23.9 us); the OSC_TUNE_GEMM_KSPLIT
+            // override switches it off (0) or on (1) where the shape allows it
+            const int ks = tuning(TUNE_GEMM_KSPLIT);
+            const int64_t t64 = ((p.M + 63) / 64) * ((p.N + 127) / 128);
+            const bool fits = !grouped && (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 4;
+            if (tm == 1 && fits && (ks == 1 || (ks != 0 && ncu_hint > 0 && t64 <= ncu_hint)))
+                return launch_dma2<MODE, 1, 2, 2, 2>(a, p.M, grouped, st);
+        }
         if (tm == 1) return launch_dma2<MODE, 1, 2>(a, p.M, grouped, st);
         // dual path, one problem: 128x256 tiles on eight wavefronts (64x64 each) beat two resident
         // workgroups of 128x128 by 4 % when they still give every CU a tile (8192x1024x4096: 29.1

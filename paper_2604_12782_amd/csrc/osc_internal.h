@@ -12,7 +12,7 @@ int fail(int code, const char* fmt, ...);  // records the thread-local message, 
 int check_launch(const char* what);        // hipGetLastError -> OSC_OK / OSC_ERR_HIP
 
 // Kernel-choice overrides (osc_tuning.h): process-wide, -1 = automatic.  Read with relaxed loads.
-enum { TUNE_GEMM_TILE = 0, TUNE_GEMM_KERNEL = 1, TUNE_GROUPED_ONE_TILE = 2, TUNE_SWIGLU_TABLE = 3, TUNE_COUNT = 4 };
+enum { TUNE_GEMM_TILE = 0, TUNE_GEMM_KERNEL = 1, TUNE_GROUPED_ONE_TILE = 2, TUNE_SWIGLU_TABLE = 3, TUNE_GEMM_KSPLIT = 4, TUNE_COUNT = 5 };
 int tuning(int knob);
 // number of compute units of the current device (cached per device); <= 0 on error
 int cu_count();

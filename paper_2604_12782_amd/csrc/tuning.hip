@@ -7,7 +7,7 @@
 
 namespace osc {
 
-static std::atomic<int> g_knob[TUNE_COUNT] = {{-1}, {-1}, {-1}, {-1}};
+static std::atomic<int> g_knob[TUNE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}};
 
 int tuning(int knob) { return g_knob[knob].load(std::memory_order_relaxed); }
 

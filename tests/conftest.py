@@ -24,6 +24,9 @@ class _Tuning:
         self.osc.osc_tuning_set(self.osc.OSC_TUNE_GEMM_TILE, tile)
         self.osc.osc_tuning_set(self.osc.OSC_TUNE_GEMM_KERNEL, kern)
 
+    def gemm_ksplit(self, on):
+        self.osc.osc_tuning_set(self.osc.OSC_TUNE_GEMM_KSPLIT, -1 if on is None else int(on))
+
     def swiglu_table(self, on):
         self.osc.osc_tuning_set(self.osc.OSC_TUNE_SWIGLU_TABLE, -1 if on is None else int(on))
 
@@ -31,7 +34,7 @@ class _Tuning:
         self.osc.osc_tuning_set(self.osc.OSC_TUNE_GROUPED_ONE_TILE, -1 if on is None else int(on))
 
     def reset(self):
-        for k in range(4):
+        for k in range(5):
             self.osc.osc_tuning_set(k, -1)
 
 

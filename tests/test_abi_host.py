@@ -45,7 +45,7 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 
 
 def test_tuning_knobs_host(lib):
-    for k in range(4):
+    for k in range(5):
         assert osc.osc_tuning_get(k) == -1
         osc.osc_tuning_set(k, 1)
         assert osc.osc_tuning_get(k) == 1

@@ -54,6 +54,36 @@ def test_dual_forced(osc, tuning, cfg, M, N, K, r):
         close(Y, ref, f"{cfg} {M}x{N}x{K} r={r} bf16={bf}", bf)
 
 
+@pytest.mark.parametrize("M,N,K,r", [(300, 200, 1024, 2), (200, 300, 1280, 2), (64, 128, 2048, 1), (130, 260, 4096, 4),
+                                     (513, 520, 1024, 0), (1, 40, 2304, 3), (2048, 1024, 4096, 2)])
+def test_dual_64x128_tiles_with_k_split(osc, tuning, M, N, K, r):
+    """64 x 128 tiles with the reduction axis split over two groups of wavefronts (forced on: the launcher
+    itself takes it only when the launch has at most one tile per CU): even and odd numbers of stages, a
+    branch of one to eight stages, ragged tiles in both directions."""
+    tuning.gemm("1,1")
+    tuning.gemm_ksplit(1)
+    X, table = wl.activations_persistent(7060 + M, M, K, r) if r else (wl.activations_diffuse(7060 + M, M, K), None)
+    W = wl.weights(7160 + N, N, K)
+    oidx = oracle.table_to_index(table) if r else np.zeros(0, np.int32)
+    d_oidx = dev(oidx) if r else None
+    Xq, Xs, B = osc.osc_quantize_act(dev(X), d_oidx)
+    Wp = osc.osc_pack_weight(dev(W), d_oidx)
+    rows = np.arange(M) if M <= 600 else np.unique(np.concatenate([np.arange(0, M, 61), [63, 64, M - 1]]))
+    rq, rs, rb = oracle.quantize_mxfp4_osc(X[rows], oidx, ldb=B.shape[1] if B is not None else 0)
+    wq, ws, _ = oracle.quantize_mxfp4_osc(W)
+    ref = oracle.dual_gemm(rq, rs, rb if r else None, wq, ws, oracle.gather_wl(W, oidx))
+    sel = torch.from_numpy(rows).cuda()
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Y = osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), ydt)
+        close(Y[sel], ref, f"k split {M}x{N}x{K} r={r} bf16={bf}", bf)
+    # the same launch without the split gives the same numbers up to the order of two partial sums
+    tuning.gemm_ksplit(0)
+    Y0 = osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), osc.OSC_DT_F32)
+    tuning.gemm_ksplit(1)
+    Y1 = osc.osc_dual_gemm(Xq, Xs, B, Wp, N, K, len(oidx), osc.OSC_DT_F32)
+    assert float((Y0 - Y1).abs().max()) <= 1e-5 * float(Y0.abs().max())
+
+
 @pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1", "1,0", "2,0"])
 def test_fp8_and_mxfp8_forced(osc, tuning, cfg):
     tuning.gemm(cfg)

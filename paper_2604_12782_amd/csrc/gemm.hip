@@ -678,12 +678,12 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
 
 template <int MODE, int TM, int TN, int WN, int KS = 1>
 __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
-    // KS = 2 (dual path, small tiles): two groups of 2 x WN wavefronts share a tile and split its reduction
+    // KS = 2 (dual path and FP8, small tiles): two groups of 2 x WN wavefronts share a tile and split its reduction
     // axis, group g taking stages g, g + 2, ... through LDS stages of its own; the partial sums meet in LDS
     // at the end.  A launch of at most one small tile per CU leaves one wavefront on every SIMD, and a stage
     // is then a chain of latencies (LDS read, eight MFMAs, barrier) with nothing to overlap it; the second
     // group fills those gaps and halves the number of stages each wavefront walks through.
-    static_assert(KS == 1 || (KS == 2 && MODE == MODE_DUAL), "K split: dual path, two groups");
+    static_assert(KS == 1 || (KS == 2 && WN == 2 && (MODE == MODE_DUAL || MODE == MODE_FP8)), "K split: two groups, dual path or FP8");
     // 2 x WN wavefronts; WN = 4 puts two wavefronts on every SIMD: while one waits for its LDS
     // reads or sits between two dependent MFMAs the other keeps the matrix core busy
     constexpr int NWV = 2 * WN;                // wavefronts
@@ -879,12 +879,12 @@ __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
         u32x4 ga0[TM], gb0[TN], ga1[TM], gb1[TN];                                              \
         OSC_F2(buf, 2 * q, fa0, fb0)                                                           \
         OSC_F2(buf, 2 * q + 1, ga0, gb0)                                                       \
-        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, LA, 0, LB / 2)                    \
+        if ((T_) + KS < nT) OSC_D2_MAIN((T_) + KS, buf ^ 1, 0, LA, 0, LB / 2)                    \
         OSC_F2(buf, 4 + 2 * q, fa1, fb1)                                                       \
         OSC_F2(buf, 4 + 2 * q + 1, ga1, gb1)                                                   \
         OSC_MFMA_FP8(0, TM * TN, fa0, ga0, fb0, gb0)                                           \
         spread_hint<TM * TN, 2 * (TM + TN), 0, LA + LB / 2>();                                 \
-        if ((T_) + 1 < nT) OSC_D2_MAIN((T_) + 1, buf ^ 1, 0, 0, LB / 2, LB)                    \
+        if ((T_) + KS < nT) OSC_D2_MAIN((T_) + KS, buf ^ 1, 0, 0, LB / 2, LB)                    \
         OSC_MFMA_FP8(0, TM * TN, fa1, ga1, fb1, gb1)                                           \
         spread_hint<TM * TN, 0, 0, LB - LB / 2>();                                             \
         __builtin_amdgcn_sched_barrier(0);                                                     \
@@ -991,7 +991,10 @@ __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
         for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8_LEAN(T)
     } else if (MODE == MODE_FP8) {
 #pragma unroll 1
-        for (int T = 0; T < nT; ++T) OSC_D2_STAGE_FP8(T)
+        for (int T = grp; T < nT; T += KS) OSC_D2_STAGE_FP8(T)
+        if constexpr (KS > 1) {
+            if (grp == 1 && (nT & 1)) __syncthreads();
+        }
     } else {
         int T = grp;
 #pragma unroll 1
@@ -2181,7 +2184,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         // 256-row tiles run on eight wavefronts (2 x 4, 128x64 each): 6-8 % faster than four, the second
         // wavefront of a SIMD fills the issue gaps of the first
         if (tm == 4) return launch_dma2<MODE, 4, 2, 4>(a, p.M, grouped, st);
-        if constexpr (MODE == MODE_DUAL) {
+        if constexpr (MODE == MODE_DUAL || MODE == MODE_FP8) {
             // at most one 64 x 128 tile per CU: two groups of wavefronts per tile, each taking every second stage
             // (2048 x 1024 x 4096: 12.7 -> 11.0 us, 128 x 12288 x 4096: 16.8 -> 13.2 us; with more tiles than CUs
             // the doubled LDS footprint costs a round: 192 x 12288: 17.2 -> 23.9 us); the OSC_TUNE_GEMM_KSPLIT

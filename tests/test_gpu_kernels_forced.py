@@ -84,6 +84,23 @@ def test_dual_64x128_tiles_with_k_split(osc, tuning, M, N, K, r):
     assert float((Y0 - Y1).abs().max()) <= 1e-5 * float(Y0.abs().max())
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 200, 1024), (200, 300, 640), (64, 128, 2048), (513, 520, 896), (2048, 1024, 4096)])
+def test_fp8_64x128_tiles_with_k_split(osc, tuning, M, N, K):
+    """The per-token FP8 GEMM on 64 x 128 tiles with the K split forced on: even and odd stage counts."""
+    tuning.gemm("1,1")
+    tuning.gemm_ksplit(1)
+    X = wl.activations_diffuse(7250 + M, M, K)
+    W = wl.weights(7251 + N, N, K)
+    X8, xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    rows = np.arange(M) if M <= 600 else np.unique(np.concatenate([np.arange(0, M, 61), [63, 64, M - 1]]))
+    r8, rs = oracle.quantize_fp8_rows(X[rows])
+    w8, ws = oracle.quantize_fp8_rows(W)
+    sel = torch.from_numpy(rows).cuda()
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Y = osc.osc_fp8_gemm(X8, xs, osc.osc_pack_weight_fp8(dev(W)), N, K, y_dtype=ydt)
+        close(Y[sel], oracle.fp8_gemm(r8, rs, w8, ws), f"fp8 k split {M}x{N}x{K} bf16={bf}", bf)
+
+
 @pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1", "1,0", "2,0"])
 def test_fp8_and_mxfp8_forced(osc, tuning, cfg):
     tuning.gemm(cfg)

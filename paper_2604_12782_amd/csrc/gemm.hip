@@ -17,16 +17,22 @@
 // bytes [32q, 32q+32) of the 64-byte step, i.e. 16-byte pieces 2q and 2q+1, and piece I feeds
 // MFMA I; the FP4 scale word is shifted right by 16q bits so that byte I is the scale of piece I.
 //
-// Four kernels share these conventions; the host picks one per call (launch_gemm):
+// The kernels share these conventions; the host picks one per call (launch_gemm):
 //   gemm_kernel        register-staged (global -> VGPR -> LDS -> MFMA), 64-byte steps, any legal
 //                      shape (ragged rows through a block of zeros), grouped and row-mapped problems;
-//   gemm_dma2_kernel   global -> LDS by DMA in whole 128-byte lines, two LDS stages; dual path and
-//                      FP8, grouped and row-mapped problems; needs 128-byte row pitches;
+//   gemm_dma2_kernel   global -> LDS by DMA in whole 128-byte lines, two LDS stages; dual path, FP8 and
+//                      MXFP8, grouped and row-mapped problems; needs 128-byte row pitches.  Tiles of
+//                      256x256 and 128x256 on eight wavefronts, 128x128 and 64x128 on four; a launch of
+//                      at most one 64x128 tile per CU splits every tile's K loop over two wavefront groups;
+//   gemm_dma2g_kernel  the same stages on persistent workgroups for grouped 8-bit problems;
 //   gemm_pipe2_kernel  the same data path, persistent workgroups, slot-pinned instruction order,
-//                      early buffer release; dual path, one problem of whole 256x256 tiles (a ragged
-//                      row tail goes to the DMA kernel);
-//   gemm_skinny_kernel M <= 64 (decode): one workgroup per 32 output channels streams the weights
-//                      once, its wavefronts split the reduction axis.
+//                      early buffer release; dual path, one problem of more than one whole 256x256 tile
+//                      per CU (a ragged row tail goes to the DMA kernel);
+//   gemm_skinny_kernel M <= 64 (decode) and other launches of at most 512 blocks of 32x32 outputs: one
+//                      workgroup per 32 output channels streams the weights once, its wavefronts split
+//                      the reduction axis;
+//   gemm_ring_kernel   a four-slot ring of half stages with two wavefront groups in anti-phase; never
+//                      chosen by the launcher, reachable through the tuning override only.
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>

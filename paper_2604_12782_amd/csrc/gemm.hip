@@ -1731,23 +1731,26 @@ static int launch_ring(KArgs a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Skinny kernel (M <= 64: decode batches), dual path and FP8.  The work is streaming the weights once,
-// so the grid is as wide as it can be without splitting the reduction over workgroups: one
-// workgroup per 32 output channels; its four wavefronts take the 128-byte lines of the
-// reduction axis in turn (FP4 lines, then bf16 branch lines) and never synchronise until the end:
-// each wavefront moves its lines global -> LDS with the DMA path into a strip of its own (whole
-// 128-byte lines per row, so every request is a full cache line), reads them back in the
-// matrix-core layout, and the four partial 32x32 results are summed through LDS in a fixed order.
+// Skinny kernel (M <= 64: decode batches, and other launches of few output blocks), dual path, FP8 and
+// MXFP8.  The work is streaming the weights once, so the grid is as wide as it can be without splitting
+// the reduction over workgroups: one workgroup per 32 output channels; its NW wavefronts take the
+// 128-byte lines of the reduction axis in turn (FP4 lines, then bf16 branch lines) and never synchronise
+// until the end: each wavefront moves its lines global -> LDS with the DMA path into a ring of DEPTH
+// images of its own (whole 128-byte lines per row, so every request is a full cache line; the scale
+// words of the 64 rows behind them), reads them back in the matrix-core layout, and the NW partial
+// 32x32 results are summed through LDS in a fixed order.
 // Inside a line, lanes of block q take bytes [64q, 64q+64): four 16-byte pieces, one MFMA each,
 // and for FP4 exactly the four groups of scale word 2*line + q.
 // MT = number of 32-row tiles of X per workgroup (blockIdx.y selects the group of MT tiles).
 // ------------------------------------------------------------------------------------------
-template <int MODE, int MT, int NW>
+template <int MODE, int MT, int NW, int DEPTH>
 __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
     constexpr int ROWS = 32 + 32 * MT;      // rows of a line image: 32 weight rows, then the X rows
-    constexpr int IMG = ROWS * 128;          // bytes of a line image
+    constexpr int NSC = (MODE == MODE_FP8) ? 0 : 1 + MT;  // scale requests per line (one 256-byte run of words each)
+    constexpr int IMG = ROWS * 128 + NSC * 256;  // bytes of a line image: the rows, then their scale words
     constexpr int NDMA = ROWS / 8;           // DMA instructions per line (8 rows each)
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];  // [NW waves][2 images], later the partial sums
+    constexpr int NREQ = NDMA + NSC;         // requests per line
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];  // [NW waves][DEPTH images], later the partial sums
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int q = lane >> 5, r = lane & 31;
     const int n0 = blockIdx.x * 32;
@@ -1757,7 +1760,7 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
     const int nL = rowbytes >> 7;
     const int nLB = (MODE == MODE_DUAL) ? ((a.K_o * 2 + 127) >> 7) : 0;
     const int nLT = nL + nLB;
-    uint8_t* const strip = lds + wave * (2 * IMG);
+    uint8_t* const strip = lds + wave * (DEPTH * IMG);
 
     // DMA instruction i moves rows 8i .. 8i+7 of the image: lane -> row 8i + lane/8, piece position
     // lane%8, which holds piece (lane%8) ^ swz8(row) of the row
@@ -1801,6 +1804,16 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
 #define SKINNY_FETCH(L_, IMG_)                                                                          \
     {                                                                                                   \
         uint8_t* dst__ = strip + (IMG_)*IMG;                                                            \
+        if ((L_) < nLT && MODE != MODE_FP8) {                                                           \
+            /* scale words of the line: lane (q, r) fetches the word of its row; a line of the bf16     \
+               branch fetches the last word again (never used), so every line is NREQ requests */       \
+            const size_t so__ = (size_t)min((L_), nL - 1) * sstep;                                      \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ws + so__), \
+                                             (__attribute__((address_space(3))) void*)(dst__ + ROWS * 128), 4, 0, 0); \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xs[m] + so__), \
+                                                 (__attribute__((address_space(3))) void*)(dst__ + ROWS * 128 + (1 + m) * 256), 4, 0, 0); \
+        }                                                                                               \
         if ((L_) < nL) {                                                                                \
             _Pragma("unroll") for (int i = 0; i < NDMA; ++i)                                            \
                 load_to_lds16((i < 4 ? wq : a.Xq) + ((size_t)(L_)*128 + o_fp4[i]), dst__ + i * 1024);   \
@@ -1828,14 +1841,16 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
             int sbm__ = 0x7f7f7f7f, sxm__[MT];                                                          \
             _Pragma("unroll") for (int m = 0; m < MT; ++m) sxm__[m] = 0x7f7f7f7f;                       \
             if (MODE == MODE_MX8) {                                                                     \
-                sbm__ = sb_cur >> (8 * q);                                                              \
-                _Pragma("unroll") for (int m = 0; m < MT; ++m) sxm__[m] = sx_cur[m] >> (8 * q);         \
+                sbm__ = *reinterpret_cast<const int*>(src__ + ROWS * 128 + lane * 4) >> (8 * q);        \
+                _Pragma("unroll") for (int m = 0; m < MT; ++m)                                          \
+                    sxm__[m] = *reinterpret_cast<const int*>(src__ + ROWS * 128 + (1 + m) * 256 + lane * 4) >> (8 * q); \
             }                                                                                           \
             SKINNY_F8(0) SKINNY_F8(1)                                                                   \
         } else if ((L_) < nL) {                                                                         \
-            const int sb__ = sb_cur;                                                                    \
+            const int sb__ = *reinterpret_cast<const int*>(src__ + ROWS * 128 + lane * 4);              \
             int sx__[MT];                                                                               \
-            _Pragma("unroll") for (int m = 0; m < MT; ++m) sx__[m] = sx_cur[m];                         \
+            _Pragma("unroll") for (int m = 0; m < MT; ++m)                                              \
+                sx__[m] = *reinterpret_cast<const int*>(src__ + ROWS * 128 + (1 + m) * 256 + lane * 4); \
             SKINNY_FP4(0) SKINNY_FP4(1) SKINNY_FP4(2) SKINNY_FP4(3)                                     \
         } else {                                                                                        \
             _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
@@ -1862,38 +1877,26 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
             acc[m] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[m], 4, 4, I_, sx__[m], I_, sb__); \
         }                                                                                               \
     }
-    // lines wave, wave+NW, ...; the next line is in flight while one is consumed.  Everything a wave
-    // reads from LDS it wrote itself, so "my loads have landed" is all the synchronisation needed.
-    // The scale words of a line (block-scaled modes) travel with its DMA requests, one line ahead, into
-    // registers: fetched where they are used, every line would wait for a round trip to L2 of its own.
-    // A line past the scaled phase re-reads the last word (never used).
-    constexpr int NSC = (MODE == MODE_FP8) ? 0 : 1 + MT;  // scale loads per line
-    int sb_cur = 0, sb_nxt = 0, sx_cur[MT], sx_nxt[MT];
-#define SKINNY_SCALES(L_, SB_, SX_)                                                                     \
-    if (MODE != MODE_FP8) {                                                                             \
-        const size_t so__ = (size_t)min((L_), nL - 1) * sstep;                                          \
-        SB_ = *reinterpret_cast<const int*>(ws + so__);                                                 \
-        _Pragma("unroll") for (int m = 0; m < MT; ++m) SX_[m] = *reinterpret_cast<const int*>(xs[m] + so__); \
-    }
+    // Lines wave, wave + NW, ...: DEPTH - 1 of them are in flight while one is consumed (a wavefront streams
+    // a few dozen lines at most and a request to HBM outlasts the arithmetic of several lines, so the bytes
+    // in flight set the streaming rate).  Everything a wavefront reads from LDS it wrote itself, so "my
+    // requests up to this line have landed" is all the synchronisation needed: a counted wait that
+    // leaves the younger lines in flight.  Every operand, the scale words included, travels by DMA:
+    // a load into registers between the requests would make the compiler's own waits drain the queue.
     int L = wave, img = 0;
-    SKINNY_FETCH(L, 0)
-    SKINNY_SCALES(L, sb_cur, sx_cur)
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d) SKINNY_FETCH(L + d * NW, d)
 #pragma unroll 1
     for (; L < nLT; L += NW) {
-        SKINNY_FETCH(L + NW, img ^ 1)
-        if (L + NW < nLT) {
-            SKINNY_SCALES(L + NW, sb_nxt, sx_nxt)
-            wait_vmcnt<NDMA + NSC>();
-        } else {
-            wait_vmcnt<0>();
-        }
+        const int ahead = (img + DEPTH - 1) % DEPTH;
+        SKINNY_FETCH(L + (DEPTH - 1) * NW, ahead)
+        const int younger = (nLT - 1 - L) / NW;  // lines of this wavefront after this one
+        if (DEPTH > 2 && younger >= 2) wait_vmcnt<(DEPTH > 2 ? 2 : 1) * NREQ>();
+        else if (younger >= 1) wait_vmcnt<NREQ>();
+        else wait_vmcnt<0>();
         SKINNY_COMPUTE(L, img)
-        sb_cur = sb_nxt;
-#pragma unroll
-        for (int m = 0; m < MT; ++m) sx_cur[m] = sx_nxt[m];
-        img ^= 1;
+        img = img + 1 == DEPTH ? 0 : img + 1;
     }
-#undef SKINNY_SCALES
 #undef SKINNY_FP4
 #undef SKINNY_F8
 #undef SKINNY_COMPUTE
@@ -1930,36 +1933,38 @@ __global__ void __launch_bounds__(64 * NW) gemm_skinny_kernel(KArgs a) {
     }
 }
 
+template <int MODE, int NW, int DEPTH>
+static int launch_skinny_cfg(KArgs a, unsigned grid, unsigned mtiles, hipStream_t st) {
+    constexpr size_t IMG = 64 * 128 + (MODE == MODE_FP8 ? 0 : 2 * 256);
+    constexpr size_t smem = (size_t)NW * DEPTH * IMG;
+    auto kern = gemm_skinny_kernel<MODE, 1, NW, DEPTH>;
+    if (smem > 48 * 1024) {
+        static unsigned char lds_done[MAX_DEVICES];
+        static size_t lds_reserved[MAX_DEVICES];
+        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), smem, lds_done, lds_reserved)) return rc;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid, mtiles), dim3(64 * NW), smem, st, a);
+    return check_launch("gemm_skinny_kernel");
+}
+
 template <int MODE>
 static int launch_skinny(KArgs a, hipStream_t st) {
     const int64_t grid = (a.N + 31) / 32;
     if (grid <= 0) return OSC_OK;
-    // LDS: one strip of two line images per wavefront; the partial sums reuse the space.  33..64 rows:
-    // two workgroups per 32 output channels, one per 32-row tile of X (the second pass over a weight
-    // row is an L2 hit; one workgroup with both tiles needs 50 % more LDS and measured slower).
+    // LDS: a ring of three line images per wavefront (8.5 KB each: 32 weight rows, 32 X rows, their scale
+    // words); the partial sums reuse the space.  33..64 rows: two workgroups per 32 output channels, one
+    // per 32-row tile of X (the second pass over a weight row is an L2 hit).  The number of wavefronts
+    // follows from how many workgroups a CU has to hold for the whole grid to be resident at once:
+    //   grid <= CUs:       six wavefronts (153 KB), one workgroup per CU;
+    //   grid <= 2 x CUs:   three wavefronts (76.5 KB), two per CU;
+    //   larger grids:      two wavefronts (51 KB), three per CU (12288 output channels x two row tiles =
+    //                      768 workgroups on 256 CUs).
     const unsigned mtiles = (unsigned)((a.M + 31) / 32);
     const int ncu = cu_count();
     if (ncu <= 0) return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
-    // Four wavefronts need 64 KB of LDS: two workgroups per CU.  When the grid is larger than that
-    // (12288 output channels x two row tiles = 768 workgroups on 256 CUs) the tail round runs half
-    // empty; three wavefronts (48 KB, three workgroups per CU) keep everything resident: 9.5 us
-    // instead of 11.8 at 64x12288x4096.
-    if (grid * mtiles > 2 * (int64_t)ncu) {
-        hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 3>), dim3((unsigned)grid, mtiles), dim3(192), 3 * 2 * 64 * 128, st, a);
-        return check_launch("gemm_skinny_kernel");
-    }
-    // A grid that leaves CUs idle (4096 output channels: 128 workgroups; 1024: 32) splits the reduction
-    // over eight wavefronts instead: 128 KB of LDS, one workgroup per CU, twice the lines in flight.
-    if (grid * mtiles <= (int64_t)ncu) {
-        auto kern = gemm_skinny_kernel<MODE, 1, 8>;
-        static unsigned char lds_done[MAX_DEVICES];
-        static size_t lds_reserved[MAX_DEVICES];
-        if (int rc = reserve_lds(reinterpret_cast<const void*>(kern), 8 * 2 * 64 * 128, lds_done, lds_reserved)) return rc;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid, mtiles), dim3(512), 8 * 2 * 64 * 128, st, a);
-        return check_launch("gemm_skinny_kernel");
-    }
-    hipLaunchKernelGGL((gemm_skinny_kernel<MODE, 1, 4>), dim3((unsigned)grid, mtiles), dim3(GT), 4 * 2 * 64 * 128, st, a);
-    return check_launch("gemm_skinny_kernel");
+    if (grid * mtiles > 2 * (int64_t)ncu) return launch_skinny_cfg<MODE, 2, 3>(a, (unsigned)grid, mtiles, st);
+    if (grid * mtiles <= (int64_t)ncu) return launch_skinny_cfg<MODE, 6, 3>(a, (unsigned)grid, mtiles, st);
+    return launch_skinny_cfg<MODE, 3, 3>(a, (unsigned)grid, mtiles, st);
 }
 
 template <int MODE, int TM, int TN, bool RAGGED>

@@ -56,11 +56,12 @@ def test_dual_forced(osc, tuning, cfg, M, N, K, r):
 
 @pytest.mark.parametrize("M,N,K,r", [(300, 200, 1024, 2), (200, 300, 1280, 2), (64, 128, 2048, 1), (130, 260, 4096, 4),
                                      (513, 520, 1024, 0), (1, 40, 2304, 3), (2048, 1024, 4096, 2)])
-def test_dual_64x128_tiles_with_k_split(osc, tuning, M, N, K, r):
-    """64 x 128 tiles with the reduction axis split over two groups of wavefronts (forced on: the launcher
-    itself takes it only when the launch has at most one tile per CU): even and odd numbers of stages, a
-    branch of one to eight stages, ragged tiles in both directions."""
-    tuning.gemm("1,1")
+@pytest.mark.parametrize("tile", ["1,1", "2,1"])
+def test_dual_small_tiles_with_k_split(osc, tuning, tile, M, N, K, r):
+    """64 x 128 and 128 x 128 tiles with the reduction axis split over two groups of wavefronts (forced on:
+    the launcher itself takes it only when the launch has at most one tile per CU): even and odd numbers
+    of stages, a branch of one to eight stages, ragged tiles in both directions."""
+    tuning.gemm(tile)
     tuning.gemm_ksplit(1)
     X, table = wl.activations_persistent(7060 + M, M, K, r) if r else (wl.activations_diffuse(7060 + M, M, K), None)
     W = wl.weights(7160 + N, N, K)
@@ -85,9 +86,10 @@ def test_dual_64x128_tiles_with_k_split(osc, tuning, M, N, K, r):
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 200, 1024), (200, 300, 640), (64, 128, 2048), (513, 520, 896), (2048, 1024, 4096)])
-def test_fp8_64x128_tiles_with_k_split(osc, tuning, M, N, K):
-    """The per-token FP8 GEMM on 64 x 128 tiles with the K split forced on: even and odd stage counts."""
-    tuning.gemm("1,1")
+@pytest.mark.parametrize("tile", ["1,1", "2,1"])
+def test_fp8_small_tiles_with_k_split(osc, tuning, tile, M, N, K):
+    """The per-token FP8 GEMM on 64 x 128 and 128 x 128 tiles with the K split forced on: even and odd stage counts."""
+    tuning.gemm(tile)
     tuning.gemm_ksplit(1)
     X = wl.activations_diffuse(7250 + M, M, K)
     W = wl.weights(7251 + N, N, K)

@@ -25,15 +25,28 @@ __device__ __forceinline__ uint32_t mul_pair(uint32_t t, uint32_t g) {
                    __builtin_bit_cast(float, th) * __builtin_bit_cast(float, gh)};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, v2bf));
 }
-// one element's term of the fixed-point sum of squares, floor(m^2 * 2^28 / 4^(e - E)) in units of
-// 2^(2e - 296), on the floating-point pipe: |x| * 2^(148 - e) = m * 2^(E - e + 14) is below 2^22, its
-// square (16 significant bits, below 2^44) is exact in single precision, and so is the floor.
-// The power of two is applied in two exact steps (pre * unit) so that neither factor leaves the
-// single-precision range for any e; an element so small that a step underflows has a term of 0.
-__device__ __forceinline__ float sq_term(uint32_t hbits16, float pre, float unit) {
-    const uint32_t b = hbits16 << 16;
-    const float xs = (__builtin_bit_cast(float, b) * pre) * unit;
-    return __builtin_floorf(xs * xs);
+// The fixed-point sum of squares, floor(x^2 / u) summed over the row with u = 2^(2e - 296) (e the row's
+// largest biased exponent), comes out of the double-precision FMA itself: the accumulator starts at
+// 2^52 * u, so its last place is u for as long as fewer than 2^52 units are added (a lane adds at most
+// 192 terms below 2^44 units each); x^2 is exact in double; and with the double-precision rounding
+// mode set to "toward zero" the one rounding of fma(x, x, acc) drops exactly the fraction of a unit,
+// because acc is a whole number of units.  The mode is a wavefront's own state.  It is switched
+// by the two statements below, which take the accumulators as operands so that every operation that
+// produces or consumes them stays between the switches, and each FMA is written out so that it cannot
+// be merged or moved across them.
+constexpr int F64_ROUND_TOWARD_ZERO = 3, F64_ROUND_NEAREST = 0;
+template <int ROUND>
+__device__ __forceinline__ void f64_round_mode(double& a, double& b) {
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), %2\n\ts_nop 1" : "+v"(a), "+v"(b) : "n"(ROUND));
+}
+__device__ __forceinline__ void sq_add(double& acc, uint32_t fbits) {
+    const double x = (double)__builtin_bit_cast(float, fbits);
+    asm volatile("v_fma_f64 %0, %1, %1, %0" : "+v"(acc) : "v"(x));
+}
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+// element-wise maximum of two pairs of 16-bit magnitudes (one packed instruction)
+__device__ __forceinline__ uint32_t max_pair(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
 }
 
 // A wavefront owns a whole row: lane l holds the 16-byte chunks l, l + 64, ... (NCI of them), so
@@ -42,7 +55,7 @@ __device__ __forceinline__ float sq_term(uint32_t hbits16, float pre, float unit
 // up to a truncation 2^-42 below the largest term and independent of any order, so the
 // normalised row, and every code derived from it, is reproducible bit for bit.
 // LDS: per-wave strip of the normalised row (for the gather) | keep masks | gamma | channel list.
-template <int NCI>
+template <int NCI, bool FULL>
 __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ gamma, double eps, int M, int K, int64_t ldx,
     const int32_t* __restrict__ oidx, int K_o, uint8_t* __restrict__ Xq, uint8_t* __restrict__ Xs,
@@ -73,33 +86,33 @@ __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
         for (int i = 0; i < NCI; ++i) {
             const int c = lane + 64 * i;
             v[i] = (u32x4){0u, 0u, 0u, 0u};
-            if (c < nchunk) v[i] = __builtin_nontemporal_load(src + c);
+            if ((FULL || c < nchunk)) v[i] = __builtin_nontemporal_load(src + c);
         }
         // largest exponent of the row
-        uint32_t amax = 0;
+        uint32_t am2 = 0;
 #pragma unroll
         for (int i = 0; i < NCI; ++i) {
             const u32x4 ab = v[i] & 0x7fff7fffu;
-            amax = max(amax, max(max(ab.x & 0xffffu, ab.x >> 16), max(ab.y & 0xffffu, ab.y >> 16)));
-            amax = max(amax, max(max(ab.z & 0xffffu, ab.z >> 16), max(ab.w & 0xffffu, ab.w >> 16)));
+            am2 = max_pair(am2, max_pair(max_pair(ab.x, ab.y), max_pair(ab.z, ab.w)));
         }
-        const int e = max(1, (int)(wave_max_u32(amax) >> 7));
-        // sum of squares: every term is an integer below 2^44, a lane adds at most 192 of them, so its
-        // double holds the exact sum; the 64 lane sums are added as integers
-        const int ebig = e >= 64 ? 0 : 64;
-        const float pre = __builtin_bit_cast(float, (uint32_t)(127 + ebig) << 23);            // 1 or 2^64
-        const float unit = __builtin_bit_cast(float, (uint32_t)(275 - e - ebig) << 23);       // 2^(148 - e) / pre
-        double s = 0.0;
+        const int e = max(1, (int)(wave_max_u32(max(am2 & 0xffffu, am2 >> 16)) >> 7));
+        // sum of squares in units of 2^(2e - 296): exact per lane (see sq_add), the 64 lane sums are
+        // added as integers
+        const double base = __builtin_bit_cast(double, (uint64_t)(1023 + 52 + 2 * e - 296) << 52);
+        double s0 = base, s1 = base;
+        f64_round_mode<F64_ROUND_TOWARD_ZERO>(s0, s1);
 #pragma unroll
         for (int i = 0; i < NCI; ++i) {
             const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                s += (double)sq_term(w[k] & 0xffffu, pre, unit);
-                s += (double)sq_term(w[k] >> 16, pre, unit);
+                sq_add(s0, w[k] << 16);
+                sq_add(s1, w[k] & 0xffff0000u);
             }
         }
-        const uint64_t S = wave_sum_u64((uint64_t)s);
+        f64_round_mode<F64_ROUND_NEAREST>(s0, s1);
+        const double units = ((s0 - base) + (s1 - base)) * __builtin_bit_cast(double, (uint64_t)(1023 + 296 - 2 * e) << 52);
+        const uint64_t S = wave_sum_u64((uint64_t)units);
         const double mean = ldexp((double)S, 2 * e - 296) / (double)K;
         const float r = (float)(1.0 / sqrt(mean + eps));
 
@@ -108,22 +121,21 @@ __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
 #pragma unroll
         for (int i = 0; i < NCI; ++i) {
             const int c = lane + 64 * i;
-            const u32x4 g = c < nchunk ? gam[c] : (u32x4){0u, 0u, 0u, 0u};
+            const u32x4 g = (FULL || c < nchunk) ? gam[c] : (u32x4){0u, 0u, 0u, 0u};
             uint32_t y[4] = {mul_pair(scale_pair(v[i].x, r), g.x), mul_pair(scale_pair(v[i].y, r), g.y),
                              mul_pair(scale_pair(v[i].z, r), g.z), mul_pair(scale_pair(v[i].w, r), g.w)};
             const u32x4 yv = {y[0], y[1], y[2], y[3]};
-            if (Xn && c < nchunk) __builtin_nontemporal_store(yv, reinterpret_cast<u32x4*>(Xn + (int64_t)m * K) + c);
+            if (Xn && (FULL || c < nchunk)) __builtin_nontemporal_store(yv, reinterpret_cast<u32x4*>(Xn + (int64_t)m * K) + c);
             if (K_o > 0) {
                 strip[c] = yv;  // back-up (step 2 of Section 3.2)
-                if (c < nchunk) {
+                if ((FULL || c < nchunk)) {
                     const u32x4 kp = *reinterpret_cast<const u32x4*>(keep + 4 * c);
                     y[0] &= kp.x, y[1] &= kp.y, y[2] &= kp.z, y[3] &= kp.w;  // zero (step 3)
                 }
             }
-            const uint32_t a0 = y[0] & 0x7fff7fffu, a1 = y[1] & 0x7fff7fffu, a2 = y[2] & 0x7fff7fffu,
-                           a3 = y[3] & 0x7fff7fffu;
-            uint32_t a = max(max(a0 & 0xffffu, a0 >> 16), max(a1 & 0xffffu, a1 >> 16));
-            a = max(a, max(max(a2 & 0xffffu, a2 >> 16), max(a3 & 0xffffu, a3 >> 16)));
+            const uint32_t a2 = max_pair(max_pair(y[0] & 0x7fff7fffu, y[1] & 0x7fff7fffu),
+                                         max_pair(y[2] & 0x7fff7fffu, y[3] & 0x7fff7fffu));
+            uint32_t a = max(a2 & 0xffffu, a2 >> 16);
             a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true));
             a = max(a, (uint32_t)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true));
             const uint32_t code = (uint32_t)max((int)(a >> 7) - 2, 0);
@@ -131,14 +143,14 @@ __global__ void __launch_bounds__(FT) rmsnorm_quant_mxfp4_kernel(
             word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x104, 0xF, 0xF, true) << 8;
             word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x108, 0xF, 0xF, true) << 16;
             word |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)code, 0x10C, 0xF, 0xF, true) << 24;
-            if ((lane & 15) == 0 && c < nchunk) *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
+            if ((lane & 15) == 0 && (FULL || c < nchunk)) *reinterpret_cast<uint32_t*>(sdst + (c >> 4) * 128) = word;
             const float scale = __builtin_bit_cast(float, code << 23);
             uint32_t out = 0;
             out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[0]), scale, 0);
             out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[1]), scale, 1);
             out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[2]), scale, 2);
             out = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(out, __builtin_bit_cast(v2bf, y[3]), scale, 3);
-            if (c < nchunk) __builtin_nontemporal_store(out, dst + c);
+            if ((FULL || c < nchunk)) __builtin_nontemporal_store(out, dst + c);
         }
         if (B) {
             uint16_t* brow = B + (int64_t)m * ldb;
@@ -165,7 +177,8 @@ static int launch_fused_nci(const uint16_t* X, const uint16_t* gamma, double eps
     if (smem > 160 * 1024)
         return fail(OSC_ERR_UNSUPPORTED, "rmsnorm+quantize: K=%lld with K_o=%d needs %zu bytes of LDS", (long long)K,
                     (int)K_o, smem);
-    auto kern = rmsnorm_quant_mxfp4_kernel<NCI>;
+    // FULL: every lane holds NCI whole chunks, so the per-chunk bounds tests (and the branches they cost) drop out
+    auto kern = K == (int64_t)NCI * 512 ? rmsnorm_quant_mxfp4_kernel<NCI, true> : rmsnorm_quant_mxfp4_kernel<NCI, false>;
     if (smem > 48 * 1024) {
         static unsigned char lds_done[MAX_DEVICES];
         static size_t lds_reserved[MAX_DEVICES];

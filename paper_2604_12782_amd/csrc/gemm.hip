@@ -175,8 +175,11 @@ __device__ __forceinline__ TilePos tile_at(const KArgs& a, int tile) {
     return p;
 }
 
-template <int MODE, int TM, int TN, int WN = 2>
-__device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, v16f (&acc)[TM][TN]) {
+// LDS_SCALES (FP8, tiles entirely inside Y): the row scales of the tile's BM rows and the column scales of
+// its BN columns are read from `tile_scales` in LDS (BM + BN floats) instead of global memory.
+template <int MODE, int TM, int TN, int WN = 2, bool LDS_SCALES = false>
+__device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, v16f (&acc)[TM][TN],
+                                             const float* tile_scales = nullptr) {
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
@@ -210,7 +213,8 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     const int row = rbase + 8 * (k >> 2) + (k & 3);
-                    xr[k] = a.xs[FULL ? row : min(row, row_end - 1)];
+                    if constexpr (LDS_SCALES) xr[k] = tile_scales[row - m0];
+                    else xr[k] = a.xs[FULL ? row : min(row, row_end - 1)];
                 }
             }
             if constexpr (KIND >= 1 && TN % 2 == 0) {
@@ -228,7 +232,7 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
                         for (int s2 = 0; s2 < 2; ++s2) {
                             const int j = jp + s2;
                             float cs = 1.0f;
-                            if (MODE == MODE_FP8) cs = wsc[n0 + wn * (TN * 32) + j * 32 + r];
+                            if (MODE == MODE_FP8) cs = LDS_SCALES ? tile_scales[BM + wn * (TN * 32) + j * 32 + r] : wsc[n0 + wn * (TN * 32) + j * 32 + r];
                             uint32_t P[8], W[8];
 #pragma unroll
                             for (int k = 0; k < 8; ++k) {
@@ -273,7 +277,7 @@ __device__ __forceinline__ void store_result(const KArgs& a, const TilePos& tp, 
             for (int j = 0; j < TN; ++j) {
                 const int col = n0 + wn * (TN * 32) + j * 32 + r;
                 float cs = 1.0f;
-                if (MODE == MODE_FP8) cs = wsc[FULL ? col : min(col, a.N - 1)];
+                if (MODE == MODE_FP8) cs = LDS_SCALES ? tile_scales[BM + col - n0] : wsc[FULL ? col : min(col, a.N - 1)];
                 float v[16];
 #pragma unroll
                 for (int k = 0; k < 16; ++k)
@@ -1243,13 +1247,19 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
 // (= workgroup % 8) owns the x-th eighth of the tile list; its workgroups take neighbouring tiles
 // at any time (8 m-tiles x 4 n-tiles with 32 workgroups).
 // ------------------------------------------------------------------------------------------
-template <int TM, int TN, int WN>
+template <int MODE, int TM, int TN, int WN>
 __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntiles) {
+    static_assert(MODE == MODE_DUAL || (MODE == MODE_FP8 && TM == 4 && TN == 4), "dual path, or FP8 on 4 x 4 blocks per wavefront");
+    constexpr bool DUAL = MODE == MODE_DUAL;
     constexpr int NWV = 2 * WN, RPP = NWV * 8;  // wavefronts (2 x WN); stage rows per DMA pass
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     constexpr int STG = (BM + BN) * 128;
     constexpr int LA = BM / RPP, LB = BN / RPP;
-    constexpr int NBLK = (BM + BN) / 32, NSB = NBLK / NWV, SCL = NBLK * 256;
+    // per stage and wavefront: dual path, NSB 32-row blocks of scale words; FP8, NSB 64-float blocks of the
+    // tile's row and column scales for the epilogue (fetched with every stage so that all stages move the
+    // same number of loads; two copies in LDS, by parity of the tile's position in this workgroup's list)
+    constexpr int NBLK = (BM + BN) / 32, NSB = DUAL ? NBLK / NWV : (BM + BN) / 64 / NWV, SCL = DUAL ? NBLK * 256 : (BM + BN) * 4;
+    static_assert(DUAL || (BM + BN) % (64 * NWV) == 0, "tile scales do not split over the wavefronts");
     static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
     constexpr int NT = TM * TN, NSLOT = 4 * NT, NRD = 2 * (TM + TN), NLD = NSB + LA + LB;
     // Three register sets: X holds piece 2q, then 4+2q, then piece 2q of the next stage; Y holds piece
@@ -1270,15 +1280,28 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
             if (A_AT + 1 + l * LW / NLD <= B_AT) ++n;
         return n;
     }();
+    // FP8 stage (128 channels): 2 NT slots of one MFMA each, see PIPE8_STAGE below
+    constexpr int F8_SLOT = 2 * NT;
+    constexpr int F8_A_AT = NT + 3;            // the last read of the stage (slot NT + 1) has landed
+    constexpr int F8_B_AT = NT + NT / 2 - 1;
+    constexpr int F8_LW = F8_SLOT - F8_A_AT - 1 > 0 ? F8_SLOT - F8_A_AT - 1 : 1;  // (only the 4 x 4 form is built for FP8)
+    constexpr int F8_LPS = NLD / F8_LW + 2;
+    constexpr int F8_N_BEFORE_B = []() {
+        int n = 0;
+        for (int l = 0; l < NLD; ++l)
+            if (F8_A_AT + 1 + l * F8_LW / NLD <= F8_B_AT) ++n;
+        return n;
+    }();
+    static_assert(DUAL || (F8_B_AT > F8_A_AT && F8_SLOT - F8_B_AT - 1 >= 2 * TN), "FP8 stage: no room for the next stage's reads");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* const scl = lds + 2 * STG;
 
     const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN, q = lane >> 5, r = lane & 31;
     const int Kg4 = ((a.K >> 5) + 3) >> 2;
-    const int rowbytes = a.K >> 1;
+    const int rowbytes = DUAL ? a.K >> 1 : a.K;
     const int nTA = rowbytes >> 7;
-    const int nTB = (a.K_o * 2 + 127) >> 7;
+    const int nTB = DUAL ? (a.K_o * 2 + 127) >> 7 : 0;
     const int nT = nTA + nTB;  // >= 3 (checked on the host)
     const int ra0 = wm * (TM * 32) + r, rb0 = BM + wn * (TN * 32) + r;
     const int tiles_m = a.M / BM;
@@ -1300,12 +1323,14 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     const uint8_t* const wq = a.Wpack + a.off_q;
     const uint8_t* const wl = a.Wpack + a.off_l;
     const uint8_t* const wsb = a.Wpack + a.off_s;
+    const float* const wcs = reinterpret_cast<const float*>(wsb);  // FP8: column scales
 
     // ---- load cursor: tile (m0, n0), stage lT; uniform bases of the stage's first 32-row blocks ----
     int lT = 0, lm0, ln0;
+    int lpar = 0;              // FP8: which copy of the tile scales the load cursor's tile writes
     int nm0 = 0, nn0 = 0;      // position of this workgroup's tile after the one under the load cursor
     bool hasnext;
-    const uint8_t *pa, *pb, *psa, *psb;  // A rows, B rows, A scale block, B scale block at this stage
+    const uint8_t *pa, *pb, *psa = nullptr, *psb = nullptr;  // A rows, B rows, A scale block, B scale block at this stage
     uint32_t sa32, sb32;                 // bytes between consecutive blocks of RPP rows
     uint32_t voa, vob;                   // per-thread offsets in use
 #define PIPE2_TILE_POS(TILE_, M0_, N0_)                                                              \
@@ -1329,9 +1354,11 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         pb = (fp4__ ? wq : wl) + ((size_t)ln0 * pitchb__ + ko__);                                    \
         voa = fp4__ ? vo_main : vo_ba;                                                               \
         vob = fp4__ ? vo_main : vo_bw;                                                               \
-        const uint32_t so__ = (uint32_t)min(2 * lT, Kg4 - 2) * 128u;                                 \
-        psa = a.Xs + ((size_t)(lm0 >> 5) * (uint32_t)Kg4 * 128u + so__);                             \
-        psb = wsb + ((size_t)(ln0 >> 5) * (uint32_t)Kg4 * 128u + so__);                              \
+        if (DUAL) {                                                                                  \
+            const uint32_t so__ = (uint32_t)min(2 * lT, Kg4 - 2) * 128u;                             \
+            psa = a.Xs + ((size_t)(lm0 >> 5) * (uint32_t)Kg4 * 128u + so__);                         \
+            psb = wsb + ((size_t)(ln0 >> 5) * (uint32_t)Kg4 * 128u + so__);                          \
+        }                                                                                            \
     }
     // advance the load cursor by one stage; at the end of a tile it moves to (nm0, nn0), the next
     // tile of this workgroup, or, if there is none, stays on the last stage
@@ -1340,6 +1367,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         const bool wrap__ = lT + 1 == nT;                                                            \
         const bool jump__ = wrap__ && hasnext;                                                       \
         lT = wrap__ ? (hasnext ? 0 : lT) : lT + 1;                                                   \
+        lpar ^= jump__ ? 1 : 0;                                                                      \
         lm0 = jump__ ? nm0 : lm0;                                                                    \
         ln0 = jump__ ? nn0 : ln0;                                                                    \
         PIPE2_STAGE_SETUP                                                                            \
@@ -1347,12 +1375,18 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // load number L_ (0..NLD-1) of the stage under the load cursor into buffer BUF_
 #define PIPE2_LOAD(L_, BUF_)                                                                         \
     {                                                                                                \
-        if ((L_) < NSB) {                                                                            \
+        if ((L_) < NSB && DUAL) {                                                                    \
             const int b__ = wave * NSB + (L_);                                                       \
             const uint8_t* src__ = (b__ < BM / 32 ? psa + (size_t)b__ * ((uint32_t)Kg4 * 128u)       \
                                                   : psb + (size_t)(b__ - BM / 32) * ((uint32_t)Kg4 * 128u)) + vo_s; \
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src__,   \
                                              (__attribute__((address_space(3))) void*)(scl + (BUF_)*SCL + b__ * 256), \
+                                             4, 0, 0);                                               \
+        } else if ((L_) < NSB) {                                                                     \
+            const int b__ = wave * NSB + (L_);                                                       \
+            const float* src__ = (b__ < BM / 64 ? a.xs + (lm0 + b__ * 64) : wcs + (ln0 + (b__ - BM / 64) * 64)) + lane; \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src__,   \
+                                             (__attribute__((address_space(3))) void*)(scl + lpar * SCL + b__ * 256), \
                                              4, 0, 0);                                               \
         } else if ((L_) < NSB + LA) {                                                                \
             const int i__ = (L_)-NSB;                                                                \
@@ -1401,7 +1435,26 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     }
     u32x4 Xa[TM], Xb[TN], Ya[TM], Yb[TN], Za[TM], Zb[TN];
     int s0a[TM], s0b[TN], s1a[TM], s1b[TN];
+    // FP8: a lane's fragment of a 64-channel MFMA step is two pieces (32 bytes).  One set for the A
+    // fragments (block i is read again as soon as its last MFMA of the step has been issued), two
+    // for the B fragments (every block of a step is in use until the step ends).
+    u32x4 A8[TM][2], Bp[TN][2], Bq[TN][2];
     v16f acc[TM][TN];
+    // half H_ (0, 1) of the fragment of 32-row block I_ / J_ for MFMA step KS_ (0, 1) of buffer BUF_
+#define PIPE8_RA(I_, BUF_, KS_, H_)                                                                     \
+    A8[I_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(ra0 + 32 * (I_), 4 * (KS_) + 2 * q + (H_)));
+#define PIPE8_RB(SET_, J_, BUF_, KS_, H_)                                                               \
+    SET_[J_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(rb0 + 32 * (J_), 4 * (KS_) + 2 * q + (H_)));
+#define PIPE8_MFMA(N_, BS_)                                                                             \
+    {                                                                                                   \
+        const int i__ = (N_) / TN, j__ = (N_) % TN;                                                     \
+        const v8i av__ = {(int)A8[i__][0].x, (int)A8[i__][0].y, (int)A8[i__][0].z, (int)A8[i__][0].w,   \
+                          (int)A8[i__][1].x, (int)A8[i__][1].y, (int)A8[i__][1].z, (int)A8[i__][1].w};  \
+        const v8i bv__ = {(int)BS_[j__][0].x, (int)BS_[j__][0].y, (int)BS_[j__][0].z, (int)BS_[j__][0].w, \
+                          (int)BS_[j__][1].x, (int)BS_[j__][1].y, (int)BS_[j__][1].z, (int)BS_[j__][1].w}; \
+        acc[i__][j__] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i__][j__], 0, 0, 0, \
+                                                                        0x7f7f7f7f, 0, 0x7f7f7f7f);     \
+    }
 
     // ---- prologue: the first two stages of the first tile ---------------------------------------
     PIPE2_TILE_POS(ctile, lm0, ln0)
@@ -1415,13 +1468,22 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     PIPE2_ADVANCE
     wait_vmcnt<0>();
     __syncthreads();
+    if constexpr (DUAL) {
 #pragma unroll
-    for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q, Xa, Xb)
+        for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q, Xa, Xb)
 #pragma unroll
-    for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q + 1, Ya, Yb)
+        for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q + 1, Ya, Yb)
 #pragma unroll
-    for (int rd = 0; rd < TM + TN; ++rd) PIPE_READ_SCALE(rd, 0, 0, s0a, s0b)
+        for (int rd = 0; rd < TM + TN; ++rd) PIPE_READ_SCALE(rd, 0, 0, s0a, s0b)
+    } else {
+        // (block TM - 1 of A is read in the first two slots of the stage)
+#pragma unroll
+        for (int i = 0; i < TM - 1; ++i) { PIPE8_RA(i, 0, 0, 0) PIPE8_RA(i, 0, 0, 1) }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { PIPE8_RB(Bp, j, 0, 0, 0) PIPE8_RB(Bp, j, 0, 0, 1) }
+    }
     int buf = 0;
+    int cpar = 0;  // FP8: which copy of the tile scales the tile under the compute cursor reads
 
 #define PIPE2_FENCE __builtin_amdgcn_sched_barrier(0);
 #define PIPE2_GROUP(G_, FP4_)                                                                          \
@@ -1487,6 +1549,60 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         buf ^= 1;                                                                                      \
     }
 
+    // FP8 stage: MFMA step 0 in slots 0 .. NT-1 (A8 x Bp), step 1 in slots NT .. 2NT-1 (A8 x Bq); slot
+    // k = step * NT + i * TN + j.
+    //   slots 0, 1:            block TM-1 of A, step 0 (its step-1 fragment of the stage before was last
+    //                          used in that stage's last slot)
+    //   slots 0 .. 2TN-1:      Bq <- step 1
+    //   slots (i+1) TN, +1:    block i of A <- step 1 (its step-0 MFMAs are slots i TN .. i TN + TN-1);
+    //                          block TM-1 falls into slots NT, NT+1
+    //   slot F8_A_AT:          every wave has read the whole stage -> barrier -> loads of stage T+2
+    //   slot F8_B_AT:          loads of stage T+1 have landed -> barrier
+    //   behind it:             Bp and blocks 0 .. TM-2 of A <- step 0 of stage T+1 (block i is free after
+    //                          slot NT + i TN + TN-1 and is read in slots F8_B_AT + 1 + 2i, + 2 + 2i)
+#define PIPE8_STAGE                                                                                    \
+    {                                                                                                  \
+        _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
+            PIPE8_MFMA(n__, Bp)                                                                        \
+            if (n__ < 2) PIPE8_RA(TM - 1, buf, 0, n__)                                                 \
+            if (n__ < 2 * TN) PIPE8_RB(Bq, n__ / 2, buf, 1, n__ % 2)                                   \
+            if (n__ >= TN && (n__ - TN) % TN < 2) PIPE8_RA((n__ - TN) / TN, buf, 1, (n__ - TN) % TN)   \
+            PIPE2_FENCE                                                                                \
+        }                                                                                              \
+        _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
+            const int k = NT + n__;                                                                    \
+            PIPE8_MFMA(n__, Bq)                                                                        \
+            if (n__ < 2) PIPE8_RA(TM - 1, buf, 1, n__)                                                 \
+            if (k == F8_A_AT) {                                                                        \
+                PIPE2_FENCE                                                                            \
+                __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */                                   \
+                __builtin_amdgcn_s_barrier();                                                          \
+                PIPE2_FENCE                                                                            \
+            }                                                                                          \
+            if (k > F8_A_AT) {                                                                         \
+                const int l0__ = ((k - F8_A_AT - 1) * NLD + F8_LW - 1) / F8_LW,                        \
+                          l1__ = ((k - F8_A_AT) * NLD + F8_LW - 1) / F8_LW;                            \
+                _Pragma("unroll") for (int u = 0; u < F8_LPS; ++u)                                     \
+                    if (l0__ + u < l1__ && l0__ + u < NLD) PIPE2_LOAD(l0__ + u, buf)                   \
+            }                                                                                          \
+            if (k == F8_B_AT) {                                                                        \
+                PIPE2_FENCE                                                                            \
+                wait_vmcnt<F8_N_BEFORE_B>();                                                           \
+                __builtin_amdgcn_s_barrier();                                                          \
+                PIPE2_FENCE                                                                            \
+            }                                                                                          \
+            if (k > F8_B_AT) {                                                                         \
+                const int rd__ = k - F8_B_AT - 1;                                                      \
+                if (rd__ < 2 * TN) PIPE8_RB(Bp, rd__ / 2, buf ^ 1, 0, rd__ % 2)                        \
+                if (rd__ < 2 * (TM - 1)) PIPE8_RA(rd__ / 2, buf ^ 1, 0, rd__ % 2)                      \
+            }                                                                                          \
+            PIPE2_FENCE                                                                                \
+        }                                                                                              \
+        PIPE2_ADVANCE                                                                                  \
+        buf ^= 1;                                                                                      \
+    }
+    static_assert(DUAL || (NT + (TM - 2) * TN + TN - 1 < F8_B_AT + 1 + 2 * (TM - 2)), "FP8 stage: an A block is read before it is free");
+
 #pragma unroll 1
     for (;;) {
 #pragma unroll
@@ -1498,10 +1614,15 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         // the load cursor is at stage 2 of this tile; it will cross into the next one (if any)
         hasnext = ctile + step < last;
         if (hasnext) PIPE2_TILE_POS(ctile + step, nm0, nn0)
+        if constexpr (DUAL) {
 #pragma unroll 1
-        for (int T = 0; T < nTA; ++T) PIPE2_STAGE(1)
+            for (int T = 0; T < nTA; ++T) PIPE2_STAGE(1)
 #pragma unroll 1
-        for (int T = nTA; T < nT; ++T) PIPE2_STAGE(0)
+            for (int T = nTA; T < nT; ++T) PIPE2_STAGE(0)
+        } else {
+#pragma unroll 1
+            for (int T = 0; T < nTA; ++T) PIPE8_STAGE
+        }
         const bool done = !hasnext;
         if (done) wait_vmcnt<0>();  // the idle re-fetches of the last stage still target LDS
         TilePos ctp;
@@ -1510,19 +1631,28 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         ctp.row_end = a.M;
         ctp.wp = a.Wpack;
         ctp.valid = true;
-        store_result<MODE_DUAL, TM, TN, WN>(a, ctp, acc);
+        if constexpr (DUAL) {
+            store_result<MODE, TM, TN, WN>(a, ctp, acc);
+        } else {
+            store_result<MODE, TM, TN, WN, true>(a, ctp, acc, reinterpret_cast<const float*>(scl + cpar * SCL));
+            cpar ^= 1;
+        }
         if (done) break;
         ctile += step;
     }
+#undef PIPE8_STAGE
+#undef PIPE8_MFMA
+#undef PIPE8_RA
+#undef PIPE8_RB
 #undef PIPE2_STAGE
 #undef PIPE2_GROUP
 #undef PIPE2_FENCE
 }
 
-template <int TM, int TN, int WN = 2>
+template <int MODE, int TM, int TN, int WN = 2>
 static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
-    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2;
+    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (MODE == MODE_DUAL ? (size_t)(BM + BN) / 32 * 256 * 2 : (size_t)(BM + BN) * 4 * 2);
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
     if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
@@ -1537,7 +1667,7 @@ static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t s
     if (ncu <= 0) return fail(OSC_ERR_HIP, "gemm: cannot read the number of compute units");
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;  // workgroups that fit one CU's LDS
     const int64_t grid = ntiles < (int64_t)ncu * per_cu ? ntiles : (int64_t)ncu * per_cu;
-    auto kern = gemm_pipe2_kernel<TM, TN, WN>;
+    auto kern = gemm_pipe2_kernel<MODE, TM, TN, WN>;
     if (smem > 64 * 1024) {
         static unsigned char lds_done[MAX_DEVICES];
         static size_t lds_reserved[MAX_DEVICES];
@@ -2122,8 +2252,8 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     int kind = lines ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
-    const bool pipe_ok = MODE == MODE_DUAL && lines && !grouped && !p.row_map &&
-                         (rowbytes / 128 + (p.K_o * 2 + 127) / 128) >= 3;
+    const bool pipe_ok = (MODE == MODE_DUAL || MODE == MODE_FP8) && lines && !grouped && !p.row_map &&
+                         (rowbytes / 128 + (MODE == MODE_DUAL ? (p.K_o * 2 + 127) / 128 : 0)) >= 3;
     // (with at most one tile per CU there is no next tile to run ahead into, and the eight wavefronts of the
     // DMA kernel are 6 % faster: 4096 x 4096 x 4096 in 46.5 against 49.4 us)
     if (kind == 1 && pipe_ok && tm == 4 && t256 > 256) kind = 2;
@@ -2141,7 +2271,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         int k2 = (t_kern >= 0 && t_kern <= 3) ? t_kern : kind;  // ids above 3 are handled before the launch below
         if (t_tile >= 0 && t_kern < 0 && k2 == 3) k2 = lines ? 1 : 0;  // a forced tile means a tiled kernel
         if ((k2 == 1 || k2 == 2) && !lines) k2 = 0;
-        if (k2 == 2 && tm == 1) k2 = 1;
+        if (k2 == 2 && (tm == 1 || (MODE != MODE_DUAL && tm != 4))) k2 = 1;
         if (k2 == 2 && !pipe_ok) k2 = 1;
         if (k2 == 3 && !skinny_ok) k2 = 0;
         kind = k2;
@@ -2161,15 +2291,20 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
             GemmProblem tail = p;
             tail.M = p.M - m_full;
             tail.Xq = p.Xq + m_full * rowbytes;
-            tail.Xs = p.Xs + (m_full / 32) * ((p.K / 32 + 3) / 4) * 128;
+            if (p.Xs) tail.Xs = p.Xs + (m_full / 32) * ((p.K / 32 + 3) / 4) * 128;
+            if (p.xs) tail.xs = p.xs + m_full;
             tail.B = p.B ? p.B + m_full * p.ldb : nullptr;
             tail.Y = static_cast<uint8_t*>(p.Y) + m_full * p.ldy * (p.y_dtype == OSC_DT_BF16 ? 2 : 4);
             const int rc = launch_gemm<MODE>(tail, st);
             if (rc != OSC_OK) return rc;
         }
         a.M = (int)m_full;
-        if (tm == 4) return launch_pipe2<4, 4>(a, m_full, grouped, st);
-        return launch_pipe2<2, 2>(a, m_full, grouped, st);
+        if constexpr (MODE == MODE_DUAL) {
+            if (tm == 4) return launch_pipe2<MODE_DUAL, 4, 4>(a, m_full, grouped, st);
+            return launch_pipe2<MODE_DUAL, 2, 2>(a, m_full, grouped, st);
+        } else if constexpr (MODE == MODE_FP8) {
+            return launch_pipe2<MODE_FP8, 4, 4>(a, m_full, grouped, st);
+        }
     }
 
     if (kind >= 1 && grouped && tm == 4) {

@@ -103,6 +103,31 @@ def test_fp8_small_tiles_with_k_split(osc, tuning, tile, M, N, K):
         close(Y[sel], oracle.fp8_gemm(r8, rs, w8, ws), f"fp8 k split {M}x{N}x{K} bf16={bf}", bf)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 512, 768), (300, 256, 384), (4392, 4096, 384), (2560, 7168, 640)])
+def test_fp8_persistent_pipeline(osc, tuning, M, N, K):
+    """The per-token FP8 GEMM on the persistent kernel (forced; the launcher takes it from 257 tiles of 256 x 256 on):
+    one tile, a ragged tail of rows (handled by a second launch), more tiles than workgroups (so that a workgroup
+    walks several tiles and both copies of the tile scales in LDS are used), three (the minimum) and five stages."""
+    tuning.gemm("4,2")
+    X = wl.activations_diffuse(7300 + M, M, K)
+    W = wl.weights(7301 + N, N, K)
+    X8, xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    rows = np.arange(M) if M <= 600 else np.unique(np.concatenate([np.arange(0, M, 37), [255, 256, 257, M - 41, M - 1]]))
+    r8, rs = oracle.quantize_fp8_rows(X[rows])
+    w8, ws = oracle.quantize_fp8_rows(W)
+    ref = oracle.fp8_gemm(r8, rs, w8, ws)
+    sel = torch.from_numpy(rows).cuda()
+    Wp = osc.osc_pack_weight_fp8(dev(W))
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Y = osc.osc_fp8_gemm(X8, xs, Wp, N, K, y_dtype=ydt)
+        close(Y[sel], ref, f"fp8 persistent {M}x{N}x{K} bf16={bf}", bf)
+    # every element against the DMA kernel (same products, same order inside a stage)
+    Y2 = osc.osc_fp8_gemm(X8, xs, Wp, N, K)
+    tuning.gemm("4,1")
+    Y1 = osc.osc_fp8_gemm(X8, xs, Wp, N, K)
+    assert float((Y1 - Y2).abs().max()) <= 1e-5 * float(Y1.abs().max())
+
+
 @pytest.mark.parametrize("cfg", ["4,1", "2,1", "1,1", "1,0", "2,0"])
 def test_fp8_and_mxfp8_forced(osc, tuning, cfg):
     tuning.gemm(cfg)

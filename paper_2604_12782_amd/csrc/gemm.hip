@@ -1249,17 +1249,20 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
 // ------------------------------------------------------------------------------------------
 template <int MODE, int TM, int TN, int WN>
 __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntiles) {
-    static_assert(MODE == MODE_DUAL || (MODE == MODE_FP8 && TM == 4 && TN == 4), "dual path, or FP8 on 4 x 4 blocks per wavefront");
-    constexpr bool DUAL = MODE == MODE_DUAL;
+    static_assert(MODE == MODE_DUAL || ((MODE == MODE_FP8 || MODE == MODE_MX8) && TM == 4 && TN == 4),
+                  "dual path, or 8-bit operands on 4 x 4 blocks per wavefront");
+    constexpr bool DUAL = MODE == MODE_DUAL, MX = MODE == MODE_MX8;
+    constexpr bool BLKSC = DUAL || MX;  // block scales travel with the stages
     constexpr int NWV = 2 * WN, RPP = NWV * 8;  // wavefronts (2 x WN); stage rows per DMA pass
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
     constexpr int STG = (BM + BN) * 128;
     constexpr int LA = BM / RPP, LB = BN / RPP;
-    // per stage and wavefront: dual path, NSB 32-row blocks of scale words; FP8, NSB 64-float blocks of the
-    // tile's row and column scales for the epilogue (fetched with every stage so that all stages move the
-    // same number of loads; two copies in LDS, by parity of the tile's position in this workgroup's list)
-    constexpr int NBLK = (BM + BN) / 32, NSB = DUAL ? NBLK / NWV : (BM + BN) / 64 / NWV, SCL = DUAL ? NBLK * 256 : (BM + BN) * 4;
-    static_assert(DUAL || (BM + BN) % (64 * NWV) == 0, "tile scales do not split over the wavefronts");
+    // per stage and wavefront: dual path and MXFP8, NSB 32-row blocks of scale words (MXFP8: one word per row
+    // and stage, fetched by both lane halves); FP8, NSB 64-float blocks of the tile's row and column scales
+    // for the epilogue (fetched with every stage so that all stages move the same number of loads; two copies
+    // in LDS, by parity of the tile's position in this workgroup's list)
+    constexpr int NBLK = (BM + BN) / 32, NSB = BLKSC ? NBLK / NWV : (BM + BN) / 64 / NWV, SCL = BLKSC ? NBLK * 256 : (BM + BN) * 4;
+    static_assert(BLKSC || (BM + BN) % (64 * NWV) == 0, "tile scales do not split over the wavefronts");
     static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
     constexpr int NT = TM * TN, NSLOT = 4 * NT, NRD = 2 * (TM + TN), NLD = NSB + LA + LB;
     // Three register sets: X holds piece 2q, then 4+2q, then piece 2q of the next stage; Y holds piece
@@ -1319,7 +1322,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     const uint32_t vo_main = (uint32_t)(t >> 3) * (uint32_t)rowbytes + c8;       // FP4 phase, both operands
     const uint32_t vo_ba = (uint32_t)(t >> 3) * (uint32_t)a.bpitch + c8;         // branch phase, B rows
     const uint32_t vo_bw = (uint32_t)(t >> 3) * (uint32_t)a.wlpitch + c8;        // branch phase, W_L rows
-    const uint32_t vo_s = (uint32_t)(r * 4 + q * 128);                            // scale word of row r, half step q
+    const uint32_t vo_s = (uint32_t)(r * 4 + (DUAL ? q * 128 : 0));               // scale word of row r (dual path: of half step q)
     const uint8_t* const wq = a.Wpack + a.off_q;
     const uint8_t* const wl = a.Wpack + a.off_l;
     const uint8_t* const wsb = a.Wpack + a.off_s;
@@ -1354,8 +1357,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         pb = (fp4__ ? wq : wl) + ((size_t)ln0 * pitchb__ + ko__);                                    \
         voa = fp4__ ? vo_main : vo_ba;                                                               \
         vob = fp4__ ? vo_main : vo_bw;                                                               \
-        if (DUAL) {                                                                                  \
-            const uint32_t so__ = (uint32_t)min(2 * lT, Kg4 - 2) * 128u;                             \
+        if (BLKSC) {                                                                                 \
+            const uint32_t so__ = (uint32_t)(DUAL ? min(2 * lT, Kg4 - 2) : min(lT, Kg4 - 1)) * 128u; \
             psa = a.Xs + ((size_t)(lm0 >> 5) * (uint32_t)Kg4 * 128u + so__);                         \
             psb = wsb + ((size_t)(ln0 >> 5) * (uint32_t)Kg4 * 128u + so__);                          \
         }                                                                                            \
@@ -1375,7 +1378,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // load number L_ (0..NLD-1) of the stage under the load cursor into buffer BUF_
 #define PIPE2_LOAD(L_, BUF_)                                                                         \
     {                                                                                                \
-        if ((L_) < NSB && DUAL) {                                                                    \
+        if ((L_) < NSB && BLKSC) {                                                                   \
             const int b__ = wave * NSB + (L_);                                                       \
             const uint8_t* src__ = (b__ < BM / 32 ? psa + (size_t)b__ * ((uint32_t)Kg4 * 128u)       \
                                                   : psb + (size_t)(b__ - BM / 32) * ((uint32_t)Kg4 * 128u)) + vo_s; \
@@ -1439,21 +1442,43 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // fragments (block i is read again as soon as its last MFMA of the step has been issued), two
     // for the B fragments (every block of a step is in use until the step ends).
     u32x4 A8[TM][2], Bp[TN][2], Bq[TN][2];
+    // MXFP8: this lane's scale bytes of the stage (byte 2 KS_ = scale of MFMA step KS_) and the words of the next
+    int m8a[TM], m8b[TN];
+    uint32_t m8an[TM], m8bn[TN];
     v16f acc[TM][TN];
     // half H_ (0, 1) of the fragment of 32-row block I_ / J_ for MFMA step KS_ (0, 1) of buffer BUF_
+    // (per-token FP8: lane half q supplies bytes 32q .. 32q+31 of the step, pieces 2q and 2q+1; MXFP8: elements
+    // 16q .. 16q+15 of each of the step's two scale blocks, pieces q and 2+q, see the DMA kernel)
+#define PIPE8_PIECE(KS_, H_) (MX ? 4 * (KS_) + q + 2 * (H_) : 4 * (KS_) + 2 * q + (H_))
 #define PIPE8_RA(I_, BUF_, KS_, H_)                                                                     \
-    A8[I_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(ra0 + 32 * (I_), 4 * (KS_) + 2 * q + (H_)));
+    A8[I_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(ra0 + 32 * (I_), PIPE8_PIECE(KS_, H_)));
 #define PIPE8_RB(SET_, J_, BUF_, KS_, H_)                                                               \
-    SET_[J_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(rb0 + 32 * (J_), 4 * (KS_) + 2 * q + (H_)));
-#define PIPE8_MFMA(N_, BS_)                                                                             \
+    SET_[J_][H_] = *reinterpret_cast<const u32x4*>(lds + (BUF_)*STG + st128_off(rb0 + 32 * (J_), PIPE8_PIECE(KS_, H_)));
+    // scale word number R_ (0..TM+TN-1) of the stage in buffer BUF_
+#define PIPE8_READ_SCALE(R_, BUF_)                                                                      \
+    {                                                                                                   \
+        const uint8_t* sc__ = scl + (BUF_)*SCL + r * 4;                                                 \
+        if ((R_) < TM) m8an[(R_) < TM ? (R_) : 0] = *reinterpret_cast<const uint32_t*>(sc__ + (wm * TM + (R_)) * 256); \
+        else m8bn[(R_) >= TM ? (R_)-TM : 0] = *reinterpret_cast<const uint32_t*>(sc__ + (BM / 32 + wn * TN + (R_)-TM) * 256); \
+    }
+#define PIPE8_TAKE_SCALES                                                                               \
+    {                                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) m8a[i] = (int)(m8an[i] >> (8 * q));              \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) m8b[j] = (int)(m8bn[j] >> (8 * q));              \
+    }
+#define PIPE8_MFMA(N_, BS_, KS_)                                                                        \
     {                                                                                                   \
         const int i__ = (N_) / TN, j__ = (N_) % TN;                                                     \
         const v8i av__ = {(int)A8[i__][0].x, (int)A8[i__][0].y, (int)A8[i__][0].z, (int)A8[i__][0].w,   \
                           (int)A8[i__][1].x, (int)A8[i__][1].y, (int)A8[i__][1].z, (int)A8[i__][1].w};  \
         const v8i bv__ = {(int)BS_[j__][0].x, (int)BS_[j__][0].y, (int)BS_[j__][0].z, (int)BS_[j__][0].w, \
                           (int)BS_[j__][1].x, (int)BS_[j__][1].y, (int)BS_[j__][1].z, (int)BS_[j__][1].w}; \
-        acc[i__][j__] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i__][j__], 0, 0, 0, \
-                                                                        0x7f7f7f7f, 0, 0x7f7f7f7f);     \
+        if (MX)                                                                                         \
+            acc[i__][j__] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i__][j__], 0, 0, 2 * (KS_), \
+                                                                            m8a[i__], 2 * (KS_), m8b[j__]); \
+        else                                                                                            \
+            acc[i__][j__] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av__, bv__, acc[i__][j__], 0, 0, 0, \
+                                                                            0x7f7f7f7f, 0, 0x7f7f7f7f); \
     }
 
     // ---- prologue: the first two stages of the first tile ---------------------------------------
@@ -1475,12 +1500,6 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         for (int rd = 0; rd < HR; ++rd) PIPE_READ1(rd, 0, 2 * q + 1, Ya, Yb)
 #pragma unroll
         for (int rd = 0; rd < TM + TN; ++rd) PIPE_READ_SCALE(rd, 0, 0, s0a, s0b)
-    } else {
-        // (block TM - 1 of A is read in the first two slots of the stage)
-#pragma unroll
-        for (int i = 0; i < TM - 1; ++i) { PIPE8_RA(i, 0, 0, 0) PIPE8_RA(i, 0, 0, 1) }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) { PIPE8_RB(Bp, j, 0, 0, 0) PIPE8_RB(Bp, j, 0, 0, 1) }
     }
     int buf = 0;
     int cpar = 0;  // FP8: which copy of the tile scales the tile under the compute cursor reads
@@ -1563,7 +1582,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
 #define PIPE8_STAGE                                                                                    \
     {                                                                                                  \
         _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
-            PIPE8_MFMA(n__, Bp)                                                                        \
+            PIPE8_MFMA(n__, Bp, 0)                                                                     \
             if (n__ < 2) PIPE8_RA(TM - 1, buf, 0, n__)                                                 \
             if (n__ < 2 * TN) PIPE8_RB(Bq, n__ / 2, buf, 1, n__ % 2)                                   \
             if (n__ >= TN && (n__ - TN) % TN < 2) PIPE8_RA((n__ - TN) / TN, buf, 1, (n__ - TN) % TN)   \
@@ -1571,7 +1590,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         }                                                                                              \
         _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
             const int k = NT + n__;                                                                    \
-            PIPE8_MFMA(n__, Bq)                                                                        \
+            PIPE8_MFMA(n__, Bq, 1)                                                                     \
             if (n__ < 2) PIPE8_RA(TM - 1, buf, 1, n__)                                                 \
             if (k == F8_A_AT) {                                                                        \
                 PIPE2_FENCE                                                                            \
@@ -1595,9 +1614,11 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
                 const int rd__ = k - F8_B_AT - 1;                                                      \
                 if (rd__ < 2 * TN) PIPE8_RB(Bp, rd__ / 2, buf ^ 1, 0, rd__ % 2)                        \
                 if (rd__ < 2 * (TM - 1)) PIPE8_RA(rd__ / 2, buf ^ 1, 0, rd__ % 2)                      \
+                if (MX && rd__ < TM + TN) PIPE8_READ_SCALE(rd__, buf ^ 1)                              \
             }                                                                                          \
             PIPE2_FENCE                                                                                \
         }                                                                                              \
+        if (MX) PIPE8_TAKE_SCALES                                                                      \
         PIPE2_ADVANCE                                                                                  \
         buf ^= 1;                                                                                      \
     }
@@ -1614,6 +1635,21 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         // the load cursor is at stage 2 of this tile; it will cross into the next one (if any)
         hasnext = ctile + step < last;
         if (hasnext) PIPE2_TILE_POS(ctile + step, nm0, nn0)
+        if constexpr (!DUAL) {
+            // 8-bit modes: the first fragments of a tile are read here, again for every tile but the first
+            // (the last stage of the tile before has read them already): 0.3 us per tile, and 70 registers
+            // fewer are alive across the epilogue, which otherwise spills its results
+            // (block TM - 1 of A is read in the first two slots of the stage)
+#pragma unroll
+            for (int i = 0; i < TM - 1; ++i) { PIPE8_RA(i, buf, 0, 0) PIPE8_RA(i, buf, 0, 1) }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) { PIPE8_RB(Bp, j, buf, 0, 0) PIPE8_RB(Bp, j, buf, 0, 1) }
+            if constexpr (MX) {
+#pragma unroll
+                for (int rd = 0; rd < TM + TN; ++rd) PIPE8_READ_SCALE(rd, buf)
+                PIPE8_TAKE_SCALES
+            }
+        }
         if constexpr (DUAL) {
 #pragma unroll 1
             for (int T = 0; T < nTA; ++T) PIPE2_STAGE(1)
@@ -1631,7 +1667,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         ctp.row_end = a.M;
         ctp.wp = a.Wpack;
         ctp.valid = true;
-        if constexpr (DUAL) {
+        if constexpr (BLKSC) {
             store_result<MODE, TM, TN, WN>(a, ctp, acc);
         } else {
             store_result<MODE, TM, TN, WN, true>(a, ctp, acc, reinterpret_cast<const float*>(scl + cpar * SCL));
@@ -1644,6 +1680,9 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
 #undef PIPE8_MFMA
 #undef PIPE8_RA
 #undef PIPE8_RB
+#undef PIPE8_PIECE
+#undef PIPE8_READ_SCALE
+#undef PIPE8_TAKE_SCALES
 #undef PIPE2_STAGE
 #undef PIPE2_GROUP
 #undef PIPE2_FENCE
@@ -1652,7 +1691,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
 template <int MODE, int TM, int TN, int WN = 2>
 static int launch_pipe2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
-    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (MODE == MODE_DUAL ? (size_t)(BM + BN) / 32 * 256 * 2 : (size_t)(BM + BN) * 4 * 2);
+    const size_t smem = (size_t)(BM + BN) * 128 * 2 + (MODE != MODE_FP8 ? (size_t)(BM + BN) / 32 * 256 * 2 : (size_t)(BM + BN) * 4 * 2);
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
     if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
@@ -2252,7 +2291,7 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
     int kind = lines ? 1 : 0;  // 0 = staged kernel, 1 = DMA kernel, 2 = persistent pipelined kernel, 3 = skinny kernel
     // persistent kernel: one dual-path problem, whole tiles along N, at least three stages; rows
     // past the last whole tile go to a second launch of the DMA kernel
-    const bool pipe_ok = (MODE == MODE_DUAL || MODE == MODE_FP8) && lines && !grouped && !p.row_map &&
+    const bool pipe_ok = lines && !grouped && !p.row_map &&
                          (rowbytes / 128 + (MODE == MODE_DUAL ? (p.K_o * 2 + 127) / 128 : 0)) >= 3;
     // (with at most one tile per CU there is no next tile to run ahead into, and the eight wavefronts of the
     // DMA kernel are 6 % faster: 4096 x 4096 x 4096 in 46.5 against 49.4 us)
@@ -2302,8 +2341,8 @@ static int launch_gemm(const GemmProblem& p, hipStream_t st) {
         if constexpr (MODE == MODE_DUAL) {
             if (tm == 4) return launch_pipe2<MODE_DUAL, 4, 4>(a, m_full, grouped, st);
             return launch_pipe2<MODE_DUAL, 2, 2>(a, m_full, grouped, st);
-        } else if constexpr (MODE == MODE_FP8) {
-            return launch_pipe2<MODE_FP8, 4, 4>(a, m_full, grouped, st);
+        } else {
+            return launch_pipe2<MODE, 4, 4>(a, m_full, grouped, st);
         }
     }
 

@@ -105,7 +105,7 @@ def test_fp8_small_tiles_with_k_split(osc, tuning, tile, M, N, K):
 
 @pytest.mark.parametrize("M,N,K", [(256, 512, 768), (300, 256, 384), (4392, 4096, 384), (2560, 7168, 640)])
 def test_fp8_persistent_pipeline(osc, tuning, M, N, K):
-    """The per-token FP8 GEMM on the persistent kernel (forced; the launcher takes it from 257 tiles of 256 x 256 on):
+    """The per-token FP8 GEMM (and, below, the MXFP8 GEMM) on the persistent kernel (forced; the launcher takes it from 257 tiles of 256 x 256 on):
     one tile, a ragged tail of rows (handled by a second launch), more tiles than workgroups (so that a workgroup
     walks several tiles and both copies of the tile scales in LDS are used), three (the minimum) and five stages."""
     tuning.gemm("4,2")
@@ -121,10 +121,33 @@ def test_fp8_persistent_pipeline(osc, tuning, M, N, K):
     for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
         Y = osc.osc_fp8_gemm(X8, xs, Wp, N, K, y_dtype=ydt)
         close(Y[sel], ref, f"fp8 persistent {M}x{N}x{K} bf16={bf}", bf)
+    if M <= 600:
+        # wide, shifted and odd output views: the 16-byte, 8-byte and element store paths of the epilogue
+        for dt, ydt, bf in ((torch.float32, osc.OSC_DT_F32, False), (torch.bfloat16, osc.OSC_DT_BF16, True)):
+            for width, col0 in ((N + 64, 0), (N + 64, 4), (N + 7, 3)):
+                wide = torch.full((M, width), 7.0, dtype=dt, device="cuda")
+                view = wide[:, col0:col0 + N]
+                osc.osc_fp8_gemm(X8, xs, Wp, N, K, y_dtype=ydt, out=view)
+                close(view, ref, f"fp8 persistent ldy={width} col0={col0} bf16={bf}", bf)
+                assert (torch.cat([wide[:, :col0], wide[:, col0 + N:]], dim=1) == 7.0).all(), "wrote outside the output view"
     # every element against the DMA kernel (same products, same order inside a stage)
     Y2 = osc.osc_fp8_gemm(X8, xs, Wp, N, K)
     tuning.gemm("4,1")
     Y1 = osc.osc_fp8_gemm(X8, xs, Wp, N, K)
+    assert float((Y1 - Y2).abs().max()) <= 1e-5 * float(Y1.abs().max())
+    # the MXFP8 form of the same kernel: block scales travel with the stages
+    tuning.gemm("4,2")
+    Xm, Xms = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_MXFP8)
+    q, sc = oracle.quantize_mxfp8(X[rows])
+    wq, wsc = oracle.quantize_mxfp8(W)
+    refm = oracle.mxfp8_gemm(q, sc, wq, wsc)
+    Wm = osc.osc_pack_weight_mxfp8(dev(W))
+    for ydt, bf in ((osc.OSC_DT_F32, False), (osc.OSC_DT_BF16, True)):
+        Ym = osc.osc_mxfp8_gemm(Xm, Xms, Wm, N, K, y_dtype=ydt)
+        close(Ym[sel], refm, f"mxfp8 persistent {M}x{N}x{K} bf16={bf}", bf)
+    Y2 = osc.osc_mxfp8_gemm(Xm, Xms, Wm, N, K)
+    tuning.gemm("4,1")
+    Y1 = osc.osc_mxfp8_gemm(Xm, Xms, Wm, N, K)
     assert float((Y1 - Y2).abs().max()) <= 1e-5 * float(Y1.abs().max())
 
 

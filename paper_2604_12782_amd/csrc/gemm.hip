@@ -1285,7 +1285,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     }();
     // FP8 stage (128 channels): 2 NT slots of one MFMA each, see PIPE8_STAGE below
     constexpr int F8_SLOT = 2 * NT;
-    constexpr int F8_A_AT = NT + 3;            // the last read of the stage (slot NT + 1) has landed
+    constexpr int F8_A_AT = NT;                // the last read of the stage (slot NT - 3) has landed
     constexpr int F8_B_AT = NT + NT / 2 - 1;
     constexpr int F8_LW = F8_SLOT - F8_A_AT - 1 > 0 ? F8_SLOT - F8_A_AT - 1 : 1;  // (only the 4 x 4 form is built for FP8)
     constexpr int F8_LPS = NLD / F8_LW + 2;
@@ -1438,10 +1438,11 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     }
     u32x4 Xa[TM], Xb[TN], Ya[TM], Yb[TN], Za[TM], Zb[TN];
     int s0a[TM], s0b[TN], s1a[TM], s1b[TN];
-    // FP8: a lane's fragment of a 64-channel MFMA step is two pieces (32 bytes).  One set for the A
-    // fragments (block i is read again as soon as its last MFMA of the step has been issued), two
-    // for the B fragments (every block of a step is in use until the step ends).
-    u32x4 A8[TM][2], Bp[TN][2], Bq[TN][2];
+    // 8-bit modes: a lane's fragment of a 64-channel MFMA step is two pieces (32 bytes).  One set for the A
+    // fragments (block i is read again as soon as its last MFMA of the step has been issued; the last
+    // block has a second set, A8x, for its step-1 fragment), two for the B fragments (every block of a
+    // step is in use until the step ends).
+    u32x4 A8[TM][2], Bp[TN][2], Bq[TN][2], A8x[2];
     // MXFP8: this lane's scale bytes of the stage (byte 2 KS_ = scale of MFMA step KS_) and the words of the next
     int m8a[TM], m8b[TN];
     uint32_t m8an[TM], m8bn[TN];
@@ -1469,8 +1470,10 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
 #define PIPE8_MFMA(N_, BS_, KS_)                                                                        \
     {                                                                                                   \
         const int i__ = (N_) / TN, j__ = (N_) % TN;                                                     \
-        const v8i av__ = {(int)A8[i__][0].x, (int)A8[i__][0].y, (int)A8[i__][0].z, (int)A8[i__][0].w,   \
-                          (int)A8[i__][1].x, (int)A8[i__][1].y, (int)A8[i__][1].z, (int)A8[i__][1].w};  \
+        const bool x__ = (KS_) == 1 && i__ == TM - 1;                                                   \
+        const u32x4 a0__ = x__ ? A8x[0] : A8[i__][0], a1__ = x__ ? A8x[1] : A8[i__][1];                 \
+        const v8i av__ = {(int)a0__.x, (int)a0__.y, (int)a0__.z, (int)a0__.w,                           \
+                          (int)a1__.x, (int)a1__.y, (int)a1__.z, (int)a1__.w};                          \
         const v8i bv__ = {(int)BS_[j__][0].x, (int)BS_[j__][0].y, (int)BS_[j__][0].z, (int)BS_[j__][0].w, \
                           (int)BS_[j__][1].x, (int)BS_[j__][1].y, (int)BS_[j__][1].z, (int)BS_[j__][1].w}; \
         if (MX)                                                                                         \
@@ -1570,20 +1573,22 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
 
     // FP8 stage: MFMA step 0 in slots 0 .. NT-1 (A8 x Bp), step 1 in slots NT .. 2NT-1 (A8 x Bq); slot
     // k = step * NT + i * TN + j.
-    //   slots 0, 1:            block TM-1 of A, step 0 (its step-1 fragment of the stage before was last
-    //                          used in that stage's last slot)
     //   slots 0 .. 2TN-1:      Bq <- step 1
-    //   slots (i+1) TN, +1:    block i of A <- step 1 (its step-0 MFMAs are slots i TN .. i TN + TN-1);
-    //                          block TM-1 falls into slots NT, NT+1
+    //   slots (i+1) TN, +1:    block i < TM-1 of A <- step 1 (its step-0 MFMAs are slots i TN .. i TN + TN-1)
+    //   slots NT-6, NT-5:      A8x <- step 1 of block TM-1 (a set of its own: waiting for that block's last
+    //                          step-0 MFMA would keep the buffer busy four slots longer)
     //   slot F8_A_AT:          every wave has read the whole stage -> barrier -> loads of stage T+2
     //   slot F8_B_AT:          loads of stage T+1 have landed -> barrier
-    //   behind it:             Bp and blocks 0 .. TM-2 of A <- step 0 of stage T+1 (block i is free after
-    //                          slot NT + i TN + TN-1 and is read in slots F8_B_AT + 1 + 2i, + 2 + 2i)
+    //   behind it:             Bp and A <- step 0 of stage T+1: block TM-1 first (free since slot NT-1), then
+    //                          blocks 0 .. TM-2 (block i is free after slot NT + i TN + TN-1 and is read in
+    //                          slots F8_B_AT + 3 + 2i, + 4 + 2i)
 #define PIPE8_STAGE                                                                                    \
     {                                                                                                  \
         _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
             PIPE8_MFMA(n__, Bp, 0)                                                                     \
-            if (n__ < 2) PIPE8_RA(TM - 1, buf, 0, n__)                                                 \
+            if (n__ == NT - 6 || n__ == NT - 5)                                                        \
+                A8x[n__ - (NT - 6)] = *reinterpret_cast<const u32x4*>(                                 \
+                    lds + buf * STG + st128_off(ra0 + 32 * (TM - 1), PIPE8_PIECE(1, n__ - (NT - 6)))); \
             if (n__ < 2 * TN) PIPE8_RB(Bq, n__ / 2, buf, 1, n__ % 2)                                   \
             if (n__ >= TN && (n__ - TN) % TN < 2) PIPE8_RA((n__ - TN) / TN, buf, 1, (n__ - TN) % TN)   \
             PIPE2_FENCE                                                                                \
@@ -1591,7 +1596,6 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         _Pragma("unroll") for (int n__ = 0; n__ < NT; ++n__) {                                         \
             const int k = NT + n__;                                                                    \
             PIPE8_MFMA(n__, Bq, 1)                                                                     \
-            if (n__ < 2) PIPE8_RA(TM - 1, buf, 1, n__)                                                 \
             if (k == F8_A_AT) {                                                                        \
                 PIPE2_FENCE                                                                            \
                 __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */                                   \
@@ -1613,7 +1617,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
             if (k > F8_B_AT) {                                                                         \
                 const int rd__ = k - F8_B_AT - 1;                                                      \
                 if (rd__ < 2 * TN) PIPE8_RB(Bp, rd__ / 2, buf ^ 1, 0, rd__ % 2)                        \
-                if (rd__ < 2 * (TM - 1)) PIPE8_RA(rd__ / 2, buf ^ 1, 0, rd__ % 2)                      \
+                if (rd__ < 2) PIPE8_RA(TM - 1, buf ^ 1, 0, rd__)                                       \
+                if (rd__ >= 2 && rd__ < 2 * TM) PIPE8_RA(rd__ / 2 - 1, buf ^ 1, 0, rd__ % 2)           \
                 if (MX && rd__ < TM + TN) PIPE8_READ_SCALE(rd__, buf ^ 1)                              \
             }                                                                                          \
             PIPE2_FENCE                                                                                \
@@ -1622,7 +1627,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         PIPE2_ADVANCE                                                                                  \
         buf ^= 1;                                                                                      \
     }
-    static_assert(DUAL || (NT + (TM - 2) * TN + TN - 1 < F8_B_AT + 1 + 2 * (TM - 2)), "FP8 stage: an A block is read before it is free");
+    static_assert(DUAL || (NT + (TM - 2) * TN + TN - 1 < F8_B_AT + 3 + 2 * (TM - 2) && F8_B_AT + 2 * TM < F8_SLOT),
+                  "8-bit stage: an A block is read before it is free");
 
 #pragma unroll 1
     for (;;) {
@@ -1639,9 +1645,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
             // 8-bit modes: the first fragments of a tile are read here, again for every tile but the first
             // (the last stage of the tile before has read them already): 0.3 us per tile, and 70 registers
             // fewer are alive across the epilogue, which otherwise spills its results
-            // (block TM - 1 of A is read in the first two slots of the stage)
 #pragma unroll
-            for (int i = 0; i < TM - 1; ++i) { PIPE8_RA(i, buf, 0, 0) PIPE8_RA(i, buf, 0, 1) }
+            for (int i = 0; i < TM; ++i) { PIPE8_RA(i, buf, 0, 0) PIPE8_RA(i, buf, 0, 1) }
 #pragma unroll
             for (int j = 0; j < TN; ++j) { PIPE8_RB(Bp, j, buf, 0, 0) PIPE8_RB(Bp, j, buf, 0, 1) }
             if constexpr (MX) {

@@ -1270,8 +1270,12 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // it), and X, Y of the next stage in group 3.
     constexpr int HR = TM + TN;                       // 16-byte reads per piece
     constexpr int RPS = (HR + NT - 1) / NT;           // reads per slot
-    constexpr int A_AT = NT + (HR + RPS - 1) / RPS + NT / 4;  // free point: the reads of group 1 have landed
-    constexpr int B_AT = 3 * NT - 1;
+    // group 1 reads two fragments per slot and the free point follows two slots behind the last of them: the
+    // earlier the buffer is released, the longer the next loads have to land (one read per slot and four slots
+    // of slack, i.e. slot 28 instead of 22 of 64: 2.8 % slower at 8192 x 4096 x 4096)
+    constexpr int RPS1 = 2;
+    constexpr int A_AT = NT + (HR + RPS1 - 1) / RPS1 + 2;  // free point: the reads of group 1 have landed
+    constexpr int B_AT = 3 * NT - 1;           // (slots 43 .. 55 of 64: within 0.5 %, 43 is 2 % slower)
     // loads: spread evenly over the LW slots behind the free point; load l goes to slot A_AT + 1 + l * LW / NLD
     constexpr int LW = NSLOT - A_AT - 1;
     constexpr int LPS = NLD / LW + 2;  // upper bound of loads in one slot
@@ -1532,8 +1536,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
             }                                                                                          \
             /* group 1: piece 4+2q -> X (group 0 has consumed piece 2q) */                             \
             if (g__ == 1) {                                                                            \
-                _Pragma("unroll") for (int u = 0; u < RPS; ++u)                                        \
-                    if (n__ * RPS + u < HR) PIPE_READ1(n__ * RPS + u, buf, 4 + 2 * q, Xa, Xb)          \
+                _Pragma("unroll") for (int u = 0; u < RPS1; ++u)                                       \
+                    if (n__ * RPS1 + u < HR) PIPE_READ1(n__ * RPS1 + u, buf, 4 + 2 * q, Xa, Xb)        \
             }                                                                                          \
             if (k == A_AT) {                                                                           \
                 PIPE2_FENCE                                                                            \

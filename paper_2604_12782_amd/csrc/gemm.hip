@@ -26,8 +26,8 @@
 //                      at most one 64x128 tile per CU splits every tile's K loop over two wavefront groups;
 //   gemm_dma2g_kernel  the same stages on persistent workgroups for grouped 8-bit problems;
 //   gemm_pipe2_kernel  the same data path, persistent workgroups, slot-pinned instruction order,
-//                      early buffer release; dual path, one problem of more than one whole 256x256 tile
-//                      per CU (a ragged row tail goes to the DMA kernel);
+//                      early buffer release; one problem (dual path, FP8 or MXFP8) of more than one whole
+//                      256x256 tile per CU (a ragged row tail goes to the DMA kernel);
 //   gemm_skinny_kernel M <= 64 (decode) and other launches of at most 512 blocks of 32x32 outputs: one
 //                      workgroup per 32 output channels streams the weights once, its wavefronts split
 //                      the reduction axis;
@@ -1221,7 +1221,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
 
 
 // ------------------------------------------------------------------------------------------
-// Persistent pipelined kernel (dual path) for one problem made of whole tiles (M % BM == 0,
+// Persistent pipelined kernel for one problem made of whole tiles (M % BM == 0,
 // N % BN == 0, no row map).  Same operands and LDS image as the DMA kernel above, but
 //  (1) the order of every instruction of a stage is pinned: a stage is a row of slots, one MFMA per
 //      slot, and every LDS read and DMA load is tied to a slot and fenced there (sched_barrier).
@@ -1246,6 +1246,9 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
 // uniform base per (tile, stage, 32-row block) plus one per-thread 32-bit offset.  XCD x
 // (= workgroup % 8) owns the x-th eighth of the tile list; its workgroups take neighbouring tiles
 // at any time (8 m-tiles x 4 n-tiles with 32 workgroups).
+// The description above is the dual path's stage (256 FP4 or 64 bf16 channels, four MFMA groups).  The 8-bit
+// modes (per-token FP8, MXFP8) keep (1)-(3), the load stream and the barriers, with a stage of 128 channels
+// = two MFMA steps and a register plan of their own, described at PIPE8_STAGE.
 // ------------------------------------------------------------------------------------------
 template <int MODE, int TM, int TN, int WN>
 __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntiles) {

@@ -122,6 +122,29 @@ def test_config2_attention_m8192(osc):
             dual_sampled(osc, qd, qr, Wp, wr, N, K, 256, rows[:16], osc.OSC_DT_F32, f"cfg2 N={N} f32")
 
 
+def test_config2_attention_m8192_fp8_comparison_leg(osc):
+    """The FP8 W8A8 step the bench compares against, at the bench's sizes and through the launcher's own choice
+    (N = 4096: the persistent kernel; N = 1024: the DMA kernel): the persistent-channel activations of the
+    workload, sampled rows in full and a point inside every 256 x 256 tile."""
+    M, K = 8192, 4096
+    X, _ = wl.activations_persistent(2001, M, K, 2)
+    X8, xs = osc.osc_quantize_act(dev(X), None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    r8, rs = oracle.quantize_fp8_rows(X)
+    assert np.array_equal(host(X8), r8) and np.array_equal(host(xs).view(np.uint32), rs.view(np.uint32))
+    rows = sample_rows(5, M, 24)
+    for i, N in enumerate((4096, 1024)):
+        W = wl.weights(2100 + i, N, K)
+        Wp = osc.osc_pack_weight_fp8(dev(W))
+        w8, wsc = oracle.quantize_fp8_rows(W)
+        Y = osc.osc_fp8_gemm(X8, xs, Wp, N, K, y_dtype=osc.OSC_DT_BF16)
+        assert torch.equal(Y, osc.osc_fp8_gemm(X8, xs, Wp, N, K, y_dtype=osc.OSC_DT_BF16)), "not run-to-run deterministic"
+        ref = oracle.fp8_gemm(r8[rows], rs[rows], w8, wsc)
+        check_close(host(Y[torch.from_numpy(rows).cuda()].float()), ref, f"cfg2 fp8 N={N}", bf16_out=True)
+        check_tiles(host(Y.float()), tile_points(41 + i, M, N),
+                    lambda m, c, w: oracle.fp8_gemm(r8[m:m + 1], rs[m:m + 1], w8[c:c + w], wsc[c:c + w]),
+                    np.abs(ref).max(), f"cfg2 fp8 N={N}")
+
+
 def test_config2_q_projection_whole_output(osc, capsys):
     """The bench's dominant launch (M = 8192, N = K = 4096, K_o = 256, bf16 out), every one of its
     33.5 million outputs against the oracle.  The oracle needs a few minutes on the host cores, so it

@@ -647,6 +647,10 @@ def main():
     cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     cp_dst = torch.empty_like(cp_src)
     ms_copy = b.time_one(lambda: cp_dst.copy_(cp_src), reps=3)
+    # a bare streaming loop (16-byte non-temporal accesses, eight loads in flight per lane): read only, and four
+    # bytes read per byte written (the mix of the fused SwiGLU quantisers)
+    ms_rd = b.time_one(lambda: osc_probe.osc_probe_stream(cp_src, cp_dst, 0), reps=3)
+    ms_rw = b.time_one(lambda: osc_probe.osc_probe_stream(cp_src, cp_dst, 4), reps=3)
     del cp_src, cp_dst
     probe_out = torch.zeros(1, dtype=torch.float32, device=dev)
     probe_flops = osc_probe.osc_probe_mfma_fp4(2048, 256, probe_out)
@@ -672,6 +676,8 @@ def main():
     torch.cuda.synchronize()
     out["achievable"] = {
         "copy_gbs": round(2 * (1 << 30) / (ms_copy * 1e-3) / 1e9, 1),
+        "stream_read_only_gbs": round((1 << 30) / (ms_rd * 1e-3) / 1e9, 1),
+        "stream_read4_write1_gbs": round(1.25 * (1 << 30) / (ms_rw * 1e-3) / 1e9, 1),
         "mfma_fp4_only_tflops_random_operands": round(probe_flops / (ms_probe * 1e-3) / 1e12, 1),
         "sclk_mhz_while_dominant_kernel_loops": sclk_load, "sclk_mhz_nominal": 2400,
         "dominant_vs_mfma_only": round(dom_tflops / (probe_flops / (ms_probe * 1e-3) / 1e12), 4),

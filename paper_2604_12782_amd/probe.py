@@ -1,4 +1,4 @@
-"""ctypes binding of libosc_probe.so, the benchmark's matrix-core yardstick (include/osc_probe.h).
+"""ctypes binding of libosc_probe.so, the benchmark's yardsticks (include/osc_probe.h).
 Not part of the product path: only bench.py loads it."""
 import ctypes as C
 import os
@@ -17,6 +17,8 @@ def lib():
         _lib = C.CDLL(_PATH)
         _lib.osc_probe_mfma_fp4.restype = C.c_int
         _lib.osc_probe_mfma_fp4.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.osc_probe_stream.restype = C.c_int
+        _lib.osc_probe_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
     return _lib
 
 
@@ -30,3 +32,13 @@ def osc_probe_mfma_fp4(workgroups, iters, out=None):
     if rc != 0:
         raise RuntimeError(f"osc_probe_mfma_fp4 failed with {rc}")
     return flops.value
+
+
+def osc_probe_stream(src, dst, loads_per_store=0, workgroups=8192):
+    """Enqueues the streaming probe over the whole of `src` (a device tensor); returns the bytes it moves."""
+    nbytes = src.numel() * src.element_size()
+    rc = lib().osc_probe_stream(src.data_ptr(), dst.data_ptr(), nbytes, loads_per_store, workgroups,
+                                torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError(f"osc_probe_stream failed with {rc}")
+    return nbytes + (nbytes // loads_per_store if loads_per_store else 0)

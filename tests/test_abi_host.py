@@ -138,6 +138,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     pr = probe.lib().osc_probe_mfma_fp4
     fl = C.c_double(0.0)
     assert pr(0, 4, FAKE, C.addressof(fl), None) == -2 and pr(4, 4, None, C.addressof(fl), None) == -1
+    ps = probe.lib().osc_probe_stream
+    assert ps(None, FAKE, 32768, 0, 4, None) == -1 and ps(FAKE, FAKE, 1000, 0, 4, None) == -2
+    assert ps(FAKE, FAKE, 32768, 3, 4, None) == -2 and ps(FAKE, FAKE + 8, 32768, 4, 4, None) == -4
     fq = lib.osc_rmsnorm_quantize_act
     assert fq(FAKE, None, 1e-6, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -1     # gamma
     assert fq(FAKE, FAKE, -1.0, 4, 64, 64, None, 0, FAKE, FAKE, None, 0, None, None) == -2     # eps < 0

@@ -110,3 +110,57 @@ def test_swiglu_fusions_with_table_replay_equal_eager(osc, tuning):
         osc.osc_swiglu_quantize_act(GU[:, :K], GU[:, K:])
         tuning.swiglu_table("1")
         torch.cuda.synchronize()
+
+
+def test_persistent_kernels_replay_equal_eager(osc, tuning):
+    """The persistent pipelined kernel in its three modes (dual path, per-token FP8, MXFP8; forced, with a
+    ragged row tail that adds a second launch each) captured in one graph; replays on changing inputs
+    equal the eager runs."""
+    tuning.gemm("4,2")
+    M, K, N = 552, 768, 512
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Xa, table = wl.activations_persistent(4201, M, K, 2)
+    Xb = wl.activations_diffuse(4202, M, K)
+    oidx = up(osc.osc_table_to_index(table))
+    K_o = int(oidx.numel())
+    W = up(wl.weights(4203, N, K))
+    Wp, W8, Wm = osc.osc_pack_weight(W, oidx), osc.osc_pack_weight_fp8(W), osc.osc_pack_weight_mxfp8(W)
+    X = up(Xa)
+    q = osc.osc_quantize_act(X, oidx)
+    f = osc.osc_quantize_act(X, None, osc.OSC_FMT_FP8_E4M3_TOKEN)
+    m = osc.osc_quantize_act(X, None, osc.OSC_FMT_MXFP8)
+    Y = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(3)]
+
+    def step():
+        osc.osc_quantize_act(X, oidx, out=q)
+        osc.osc_dual_gemm(*q, Wp, N, K, K_o, osc.OSC_DT_BF16, out=Y[0])
+        osc.osc_quantize_act(X, None, osc.OSC_FMT_FP8_E4M3_TOKEN, out=f)
+        osc.osc_fp8_gemm(*f, W8, N, K, y_dtype=osc.OSC_DT_BF16, out=Y[1])
+        osc.osc_quantize_act(X, None, osc.OSC_FMT_MXFP8, out=m)
+        osc.osc_mxfp8_gemm(*m, Wm, N, K, y_dtype=osc.OSC_DT_BF16, out=Y[2])
+
+    def eager(bits):
+        X.copy_(up(bits))
+        step()
+        torch.cuda.synchronize()
+        return [y.clone() for y in Y]
+
+    refs = [eager(Xa), eager(Xb)]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i in range(4):
+        X.copy_(up(Xa if i % 2 == 0 else Xb))
+        for y in Y:
+            y.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for y, r in zip(Y, refs[i % 2]):
+            assert torch.equal(y, r), f"replay {i}"
+        osc.osc_fp8_gemm(*f, W8, N, K, y_dtype=osc.OSC_DT_BF16)  # eager work of the same kernels in between
+        torch.cuda.synchronize()

@@ -1250,6 +1250,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
 // modes (per-token FP8, MXFP8) keep (1)-(3), the load stream and the barriers, with a stage of 128 channels
 // = two MFMA steps and a register plan of their own, described at PIPE8_STAGE.
 // ------------------------------------------------------------------------------------------
+#define NBLK_OF(BM_, BN_) (((BM_) + (BN_)) / 32)
 template <int MODE, int TM, int TN, int WN>
 __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntiles) {
     static_assert(MODE == MODE_DUAL || ((MODE == MODE_FP8 || MODE == MODE_MX8) && TM == 4 && TN == 4),
@@ -1264,7 +1265,11 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // and stage, fetched by both lane halves); FP8, NSB 64-float blocks of the tile's row and column scales
     // for the epilogue (fetched with every stage so that all stages move the same number of loads; two copies
     // in LDS, by parity of the tile's position in this workgroup's list)
-    constexpr int NBLK = (BM + BN) / 32, NSB = BLKSC ? NBLK / NWV : (BM + BN) / 64 / NWV, SCL = BLKSC ? NBLK * 256 : (BM + BN) * 4;
+    // (dual path with four scale blocks per wavefront that all belong to one operand: one 16-byte request per
+    // lane fetches the four 256-byte blocks at once; a request costs the memory pipeline the same whatever its width)
+    constexpr bool SC16 = DUAL && NBLK_OF(BM, BN) % (4 * NWV) == 0 && (BM / 32) % 4 == 0;
+    constexpr int NBLK = (BM + BN) / 32, NSB = SC16 ? NBLK / NWV / 4 : BLKSC ? NBLK / NWV : (BM + BN) / 64 / NWV,
+                  SCL = BLKSC ? NBLK * 256 : (BM + BN) * 4;
     static_assert(BLKSC || (BM + BN) % (64 * NWV) == 0, "tile scales do not split over the wavefronts");
     static_assert(BM % RPP == 0 && BN % RPP == 0 && NBLK % NWV == 0, "tile does not split over the wavefronts");
     constexpr int NT = TM * TN, NSLOT = 4 * NT, NRD = 2 * (TM + TN), NLD = NSB + LA + LB;
@@ -1330,6 +1335,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     const uint32_t vo_ba = (uint32_t)(t >> 3) * (uint32_t)a.bpitch + c8;         // branch phase, B rows
     const uint32_t vo_bw = (uint32_t)(t >> 3) * (uint32_t)a.wlpitch + c8;        // branch phase, W_L rows
     const uint32_t vo_s = (uint32_t)(r * 4 + (DUAL ? q * 128 : 0));               // scale word of row r (dual path: of half step q)
+    // 16-byte form: lane l fetches piece l % 16 of the 256 bytes (two half steps x 32 rows x 4) of block l / 16
+    const uint32_t vo_s16 = (uint32_t)(lane >> 4) * ((uint32_t)Kg4 * 128u) + (uint32_t)(lane & 15) * 16u;
     const uint8_t* const wq = a.Wpack + a.off_q;
     const uint8_t* const wl = a.Wpack + a.off_l;
     const uint8_t* const wsb = a.Wpack + a.off_s;
@@ -1385,7 +1392,12 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
     // load number L_ (0..NLD-1) of the stage under the load cursor into buffer BUF_
 #define PIPE2_LOAD(L_, BUF_)                                                                         \
     {                                                                                                \
-        if ((L_) < NSB && BLKSC) {                                                                   \
+        if ((L_) < NSB && SC16) {                                                                    \
+            const int b__ = (wave * NSB + (L_)) * 4;                                                 \
+            const uint8_t* src__ = (b__ < BM / 32 ? psa + (size_t)b__ * ((uint32_t)Kg4 * 128u)       \
+                                                  : psb + (size_t)(b__ - BM / 32) * ((uint32_t)Kg4 * 128u)) + vo_s16; \
+            load_to_lds16(src__, scl + (BUF_)*SCL + b__ * 256);                                      \
+        } else if ((L_) < NSB && BLKSC) {                                                            \
             const int b__ = wave * NSB + (L_);                                                       \
             const uint8_t* src__ = (b__ < BM / 32 ? psa + (size_t)b__ * ((uint32_t)Kg4 * 128u)       \
                                                   : psb + (size_t)(b__ - BM / 32) * ((uint32_t)Kg4 * 128u)) + vo_s; \
@@ -1688,6 +1700,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_pipe2_kernel(KArgs a, int ntile
         if (done) break;
         ctile += step;
     }
+#undef NBLK_OF
 #undef PIPE8_STAGE
 #undef PIPE8_MFMA
 #undef PIPE8_RA

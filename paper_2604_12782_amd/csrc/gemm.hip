@@ -686,6 +686,8 @@ __global__ void __launch_bounds__(GT) gemm_kernel(KArgs a) {
 // and one barrier.  Needs operand rows that are whole 128-byte stages.
 // ------------------------------------------------------------------------------------------
 
+constexpr int dma2_scale_bytes(int BM, int BN) { return ((BM + BN) / 32 * 256 + 1023) / 1024 * 1024; }
+
 template <int MODE, int TM, int TN, int WN, int KS = 1>
 __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
     // KS = 2 (dual path and FP8, small tiles): two groups of 2 x WN wavefronts share a tile and split its reduction
@@ -704,7 +706,9 @@ __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
     constexpr int NBLK = (BM + BN) / 32;      // 32-row blocks of a stage
     constexpr int NSB = (NBLK + NWV - 1) / NWV;  // scale DMA loads per wave and stage (one block each)
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile does not split over the wavefronts");
-    constexpr int SCL = NBLK * 256;            // bytes of scale words per stage: [block][half step][32 rows][4]
+    // bytes of scale words per stage: [block][half step][32 rows][4], rounded up to whole 1 KB requests
+    constexpr int SCL = dma2_scale_bytes(BM, BN);
+    constexpr int NREQ = (NBLK + 3) / 4;       // 16-byte scale requests per stage (four blocks each)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
     const int grp = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x / (128 * WN)) : 0;
     uint8_t* const lds = lds_all + grp * (2 * STG + 2 * SCL);  // this group's two stages and their scale words
@@ -757,6 +761,20 @@ __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
         }
     }
     const uint8_t* wsb = wp + a.off_s;
+    // Dual path, one problem, rows not mapped: a stage's scale words are whole 256-byte blocks of the
+    // row-block-major layout, and lane l of wavefront w < NREQ fetches piece l % 16 of block 4w + l / 16 with
+    // one 16-byte request (a request costs the memory pipeline the same whatever its width: three or four
+    // per stage and workgroup instead of one per block and lane half).  Blocks past the last valid row or
+    // channel repeat the last valid one; their rows are never stored.
+    const bool use16 = MODE == MODE_DUAL && !a.off && !a.row_map;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint8_t* sc16_src = nullptr;
+    if (use16) {
+        const int blk = min(4 * min(wave_u, NREQ - 1) + (lane >> 4), NBLK - 1);
+        const bool isa = blk < BM / 32;
+        const int gb = isa ? min((m0 >> 5) + blk, (row_end - 1) >> 5) : min((n0 >> 5) + blk - BM / 32, (a.N - 1) >> 5);
+        sc16_src = (isa ? a.Xs : wsb) + ((size_t)gb * (uint32_t)Kg4 * 128u + (uint32_t)(lane & 15) * 16u);
+    }
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -803,6 +821,9 @@ __global__ void __launch_bounds__(128 * WN * KS) gemm_dma2_kernel(KArgs a) {
 #define OSC_D2_SCALES(T_, BUF_)                                                                       \
     {                                                                                                 \
         const uint32_t o__ = (MODE == MODE_DUAL ? (uint32_t)min(2 * (T_), Kg4 - 2) : (uint32_t)min((T_), Kg4 - 1)) * 128u; \
+        if (use16) {                                                                                  \
+            if (wave_u < NREQ) load_to_lds16(sc16_src + o__, scl + (BUF_)*SCL + wave_u * 1024);       \
+        } else                                                                                        \
         _Pragma("unroll") for (int k = 0; k < NSB; ++k) {                                             \
             const int b__ = wave * NSB + k;                                                           \
             if (NBLK % NWV != 0 && b__ >= NBLK) continue;                                             \
@@ -1069,6 +1090,9 @@ __global__ void __launch_bounds__(128 * WN) gemm_dma2g_kernel(KArgs a, int ntile
     constexpr int NSB = (NBLK + NWV - 1) / NWV;
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile does not split over the wavefronts");
     constexpr int SCL = NBLK * 256;
+    constexpr bool use16 = false;  // (the 16-byte scale requests of the DMA kernel are for single problems)
+    constexpr int NREQ = 0, wave_u = 0;
+    const uint8_t* const sc16_src = nullptr;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t* const scl = lds + 2 * STG;
     // per expert, behind the two stages and their scale words: first tile number, first row, rows
@@ -2188,7 +2212,7 @@ static int launch_cfg(KArgs a, int64_t rows_total, bool grouped, hipStream_t st)
 template <int MODE, int TM, int TN, int WN = 2, int KS = 1>
 static int launch_dma2(KArgs a, int64_t rows_total, bool grouped, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 32 * TN * WN;
-    const size_t smem = ((size_t)(BM + BN) * 128 * 2 + (size_t)(BM + BN) / 32 * 256 * 2) * KS;
+    const size_t smem = ((size_t)(BM + BN) * 128 * 2 + (size_t)dma2_scale_bytes(BM, BN) * 2) * KS;
     a.tiles_n = (int)((a.N + BN - 1) / BN);
     int64_t tiles_m = (rows_total + BM - 1) / BM;
     if (grouped) {  // upper bounds, whole rounds of the 8 XCDs
